@@ -1,0 +1,159 @@
+/*
+ * dlcx -- the per-stage outer step of DiLoCoX (arXiv 2506.21263) on one MI355X.
+ *
+ * C ABI of libdlcx_hip.so.  Every pointer is a DEVICE pointer unless its name
+ * ends in _host; arrays of pointers (one entry per simulated data-parallel
+ * worker) are HOST arrays of device pointers.  The library keeps no state and
+ * never allocates: the caller owns every buffer, scratch space is passed as
+ * `workspace` (size from dlcx_workspace_bytes).  All calls are asynchronous on
+ * `stream` (a hipStream_t, NULL = the default stream) and never synchronise,
+ * except dlcx_select_rank, which returns integers to the host.
+ *
+ * Layout
+ *   matrix  : m x n, row-major fp32, element (i, j) at i*n + j.
+ *   factor  : P is m x r, Q is n x r; stored column by column, column c of a
+ *             factor of length L at c*L .. c*L+L  (so a factor is an r x L
+ *             row-major array).  The basis passed to the P phase is Q_in
+ *             (r x n), the basis of the Q phase is P_hat (r x m).
+ *   payload : codes + scales of one quantised factor.  Groups are `group`
+ *             consecutive elements of one factor column, one fp32 scale per
+ *             group.  int8: one signed byte per element.  int4: element 2j in
+ *             the low nibble of byte j, element 2j+1 in the high nibble,
+ *             two's complement.
+ *   All buffers must be 16-byte aligned.
+ *
+ * Errors: every function returns 0 (DLCX_OK) or a negative code; arguments
+ * are validated on the host before anything is launched, so a failed call
+ * has launched nothing.
+ *
+ * Determinism: no floating-point atomics; the same inputs give bitwise the
+ * same outputs from run to run.
+ */
+#ifndef DLCX_H
+#define DLCX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DLCX_OK 0
+#define DLCX_EINVAL (-1)       /* NULL/misaligned pointer, shape or parameter out of range */
+#define DLCX_EUNSUPPORTED (-2) /* valid request this build has no kernel for              */
+#define DLCX_ELAUNCH (-3)      /* the HIP runtime reported an error                       */
+
+#define DLCX_MAX_RANK 256
+#define DLCX_MAX_WORKERS 16
+
+enum { DLCX_PHASE_P = 0, DLCX_PHASE_Q = 1 };
+enum { DLCX_F32 = 0, DLCX_BF16 = 1 };
+/* arithmetic of the three rank-r products (projections and reconstruction) */
+enum {
+    DLCX_MMA_FMA = 0,      /* fp32 operands, fp64 accumulation on the vector ALU  */
+    DLCX_MMA_F32 = 1,      /* fp32 MFMA, fp32 accumulation                        */
+    DLCX_MMA_BF16 = 2      /* operands rounded to bf16, bf16 MFMA, fp32 accumulate */
+};
+
+typedef struct {
+    int64_t m, n;   /* matrix shape; m % group == 0 and n % group == 0            */
+    int32_t r;      /* rank, 1 <= r <= min(m, n, DLCX_MAX_RANK)                   */
+    int32_t qbits;  /* 4 or 8                                                     */
+    int32_t group;  /* quantisation group: 16, 32, 64, 128 or 256                 */
+    int32_t mma;    /* DLCX_MMA_*                                                 */
+} dlcx_desc;
+
+/* Pseudo-gradient with error compensation (Alg. 2; Appendix A.3, first display):
+ *   ef_inout[x] <- (theta_g[x] - theta_l[x]) + ef_inout[x]
+ * ef_inout holds the error buffer e_i on entry and delta_i on return.  theta_l is fp32
+ * (DLCX_F32) or bf16 (DLCX_BF16).  numel >= 0. */
+int dlcx_delta_ef(const float *theta_g, const void *theta_l, int theta_l_dtype,
+                  float *ef_inout, int64_t numel, void *stream);
+
+/* Compressor C[delta] of Alg. 1 for one worker and one phase of the shared-basis low-rank
+ * step: phase P computes P_i = delta * Q_in (basis = Q_in, r x n), phase Q computes
+ * Q_i = delta^T * P_hat (basis = P_hat, r x m); the factor is then quantised to
+ * qbits in groups.  On return the first r*L floats of `workspace` hold the fp32 factor
+ * that was quantised (L = m for phase P, n for phase Q). */
+int dlcx_compress(const dlcx_desc *desc, int phase, const float *delta, const float *basis,
+                  uint8_t *codes_out, float *scales_out, void *workspace, void *stream);
+
+/* The same for K workers in one launch sequence (deltas_host[k], codes_out_host[k],
+ * scales_out_host[k]); the workspace then holds K factors back to back. */
+int dlcx_compress_batched(const dlcx_desc *desc, int phase, int K,
+                          const float *const *deltas_host, const float *basis,
+                          uint8_t *const *codes_out_host, float *const *scales_out_host,
+                          void *workspace, void *stream);
+
+/* The AllReduce-average of Alg. 2 over the K data-parallel workers, on payloads held in this
+ * GPU's memory: factor_out = (1/K) sum_k dequant(codes_k, scales_k), workers added in index
+ * order.  For phase P the mean is then orthonormalised in place (see dlcx_orthonormalize),
+ * giving P_hat; for phase Q the mean Q_bar is returned as is. */
+int dlcx_average(const dlcx_desc *desc, int phase, int K, const uint8_t *const *codes_host,
+                 const float *const *scales_host, float *factor_out, void *workspace,
+                 void *stream);
+
+/* Decompression Delta_hat = P_hat * Q_bar^T and the error buffer of Alg. 2,
+ * e_i <- delta_i - Delta_hat, for K >= 0 workers.  delta_hat_out (m x n) may be NULL when only
+ * the error buffers are wanted; ef_inout_host may be NULL when K == 0. */
+int dlcx_decompress(const dlcx_desc *desc, const float *p_hat, const float *q_bar,
+                    float *delta_hat_out, int K, float *const *ef_inout_host, void *stream);
+
+/* OuterOpt of Alg. 2 / Appendix A.3: SGD with Nesterov momentum on the averaged
+ * pseudo-gradient,  v <- mu v + g ;  theta_g <- theta_g - lr (g + mu v).  In place. */
+int dlcx_outer_nesterov(float *theta_g, float *v, const float *delta_hat, int64_t numel,
+                        float lr, float mu, void *stream);
+
+/* Alg. 3 (Adaptive Gradient Compress) for the outer step t that is about to compress.
+ *   r'_t  : measured on the latest averages: per matrix, the smallest k whose k largest
+ *           eigenvalues of Q_bar^T Q_bar hold at least tau of the trace; the stage value is
+ *           the mean over the n_matrices matrices (a zero matrix counts as rmin), rounded
+ *           half-up.  With n_matrices == 0 the value in *rprime_inout_host is used instead
+ *           (the convention r'_1 = r_1 is the caller's).
+ *   rule  : r'_t is stored in rprime_hist_host[(t-1) % c] (a caller-owned ring of c ints);
+ *           t < c gives r_1 and H_1, otherwise r_t = mean of the ring, rounded half-up and
+ *           clamped to [rmin, rmax], and H_t = max(1, round(H_1 (r_1 - r_t) / r_1)).
+ * Synchronises `stream`.  workspace: dlcx_select_rank_workspace_bytes. */
+int dlcx_select_rank(const dlcx_desc *descs_host, const float *const *q_bars_host,
+                     int n_matrices, double tau, int32_t *rprime_hist_host, int32_t t,
+                     int32_t c, int32_t r1, int32_t rmin, int32_t rmax, int32_t H1,
+                     int32_t *rprime_inout_host, int32_t *r_next_out_host,
+                     int32_t *H_next_out_host, void *workspace, void *stream);
+
+/* ---- helpers: the steps the entry points above are made of ---------------------------- */
+
+/* Size of one payload; returns codes + scales bytes, 0 on a bad descriptor. */
+size_t dlcx_payload_bytes(const dlcx_desc *desc, int phase, size_t *codes_bytes,
+                          size_t *scales_bytes);
+/* Workspace needed by any per-matrix call with up to K workers. */
+size_t dlcx_workspace_bytes(const dlcx_desc *desc, int K);
+size_t dlcx_select_rank_workspace_bytes(const dlcx_desc *descs_host, int n_matrices);
+
+/* Projection only: factors_out_host[k] (r x L fp32) = delta_k * Q_in or delta_k^T * P_hat. */
+int dlcx_project(const dlcx_desc *desc, int phase, int K, const float *const *deltas_host,
+                 const float *basis, float *const *factors_out_host, void *workspace,
+                 void *stream);
+/* Quantiser only (Alg. 1 step 2) on `count` floats in consecutive groups. */
+int dlcx_quantize(const float *x, int64_t count, int qbits, int group, uint8_t *codes_out,
+                  float *scales_out, void *stream);
+/* Mean of K dequantised payloads of `count` elements, no orthonormalisation. */
+int dlcx_dequant_average(int K, const uint8_t *const *codes_host,
+                         const float *const *scales_host, int64_t count, int qbits, int group,
+                         float *mean_out, void *stream);
+/* Thin-QR Q-factor with positive diagonal of R of the L x r factor p_inout (r x L storage),
+ * in place.  A column whose component orthogonal to the earlier columns is at most 1e-6 of
+ * its norm (or that is zero) becomes the zero column. */
+int dlcx_orthonormalize(int64_t L, int32_t r, float *p_inout, void *workspace, void *stream);
+/* r' of one matrix, written to a DEVICE int32 (0 when Q_bar is all zero); asynchronous. */
+int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,
+                        int32_t *rprime_out_dev, void *workspace, void *stream);
+
+const char *dlcx_strerror(int code);
+/* Text of the last HIP error seen by this thread's calls (empty if none). */
+const char *dlcx_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLCX_H */

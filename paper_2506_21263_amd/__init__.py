@@ -1,0 +1,206 @@
+"""Python binding of libdlcx_hip.so (see include/dlcx.h for the contract).
+
+Argument marshalling only: every function below has the name of the C entry point it calls,
+takes torch tensors that live on the GPU (PyTorch is used for device memory and streams and for
+nothing else) and passes their addresses through.  There is no fallback: if the HIP library is
+missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdlcx_hip.so")
+
+OK, EINVAL, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3
+PHASE_P, PHASE_Q = 0, 1
+F32, BF16 = 0, 1
+MMA_FMA, MMA_F32, MMA_BF16 = 0, 1, 2
+MAX_RANK, MAX_WORKERS = 256, 16
+
+
+class DlcxError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        detail = lib().dlcx_last_hip_error().decode() if code == ELAUNCH else ""
+        super().__init__("%s: %s (%d) %s" % (what, lib().dlcx_strerror(code).decode(), code, detail))
+
+
+class Desc(C.Structure):
+    _fields_ = [("m", C.c_int64), ("n", C.c_int64), ("r", C.c_int32), ("qbits", C.c_int32),
+                ("group", C.c_int32), ("mma", C.c_int32)]
+
+
+def desc(m, n, r, qbits, group, mma=MMA_FMA):
+    return Desc(m, n, r, qbits, group, mma)
+
+
+_lib = None
+_vp, _i64, _i32, _int = C.c_void_p, C.c_int64, C.c_int32, C.c_int
+_dp = C.POINTER(Desc)
+
+SYMBOLS = {
+    "dlcx_delta_ef": (_int, [_vp, _vp, _int, _vp, _i64, _vp]),
+    "dlcx_compress": (_int, [_dp, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "dlcx_compress_batched": (_int, [_dp, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "dlcx_average": (_int, [_dp, _int, _int, _vp, _vp, _vp, _vp, _vp]),
+    "dlcx_decompress": (_int, [_dp, _vp, _vp, _vp, _int, _vp, _vp]),
+    "dlcx_outer_nesterov": (_int, [_vp, _vp, _vp, _i64, C.c_float, C.c_float, _vp]),
+    "dlcx_select_rank": (_int, [_dp, _vp, _int, C.c_double, _vp, _i32, _i32, _i32, _i32, _i32,
+                                _i32, _vp, _vp, _vp, _vp, _vp]),
+    "dlcx_payload_bytes": (C.c_size_t, [_dp, _int, _vp, _vp]),
+    "dlcx_workspace_bytes": (C.c_size_t, [_dp, _int]),
+    "dlcx_select_rank_workspace_bytes": (C.c_size_t, [_dp, _int]),
+    "dlcx_project": (_int, [_dp, _int, _int, _vp, _vp, _vp, _vp, _vp]),
+    "dlcx_quantize": (_int, [_vp, _i64, _int, _int, _vp, _vp, _vp]),
+    "dlcx_dequant_average": (_int, [_int, _vp, _vp, _i64, _int, _int, _vp, _vp]),
+    "dlcx_orthonormalize": (_int, [_i64, _i32, _vp, _vp, _vp]),
+    "dlcx_effective_rank": (_int, [_i64, _i32, _vp, C.c_double, _vp, _vp, _vp]),
+    "dlcx_strerror": (C.c_char_p, [_int]),
+    "dlcx_last_hip_error": (C.c_char_p, []),
+}
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: build it with `python paper_2506_21263_amd/build.py` "
+                              "(there is no CPU fallback)" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            f = getattr(L, name)
+            f.restype = res
+            f.argtypes = args
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return t.data_ptr()
+
+
+def _ptr_array(ts):
+    if ts is None:
+        return None
+    arr = (C.c_void_p * len(ts))(*[_ptr(t) for t in ts])
+    return C.cast(arr, C.c_void_p), arr  # keep `arr` alive with the caller
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(code, what):
+    if code != OK:
+        raise DlcxError(code, what)
+
+
+def dlcx_payload_bytes(d, phase):
+    cb, sb = C.c_size_t(0), C.c_size_t(0)
+    total = lib().dlcx_payload_bytes(C.byref(d), phase, C.addressof(cb), C.addressof(sb))
+    return total, cb.value, sb.value
+
+
+def dlcx_workspace_bytes(d, K):
+    return lib().dlcx_workspace_bytes(C.byref(d), K)
+
+
+def dlcx_delta_ef(theta_g, theta_l, ef_inout, numel=None, stream=None):
+    dt = BF16 if theta_l.dtype == torch.bfloat16 else F32
+    n = theta_g.numel() if numel is None else numel
+    _check(lib().dlcx_delta_ef(_ptr(theta_g), _ptr(theta_l), dt, _ptr(ef_inout), n,
+                               _stream(stream)), "dlcx_delta_ef")
+
+
+def dlcx_compress(d, phase, delta, basis, codes_out, scales_out, workspace, stream=None):
+    _check(lib().dlcx_compress(C.byref(d), phase, _ptr(delta), _ptr(basis), _ptr(codes_out),
+                               _ptr(scales_out), _ptr(workspace), _stream(stream)),
+           "dlcx_compress")
+
+
+def dlcx_compress_batched(d, phase, deltas, basis, codes_out, scales_out, workspace, stream=None):
+    dp, k1 = _ptr_array(deltas)
+    cp, k2 = _ptr_array(codes_out)
+    sp, k3 = _ptr_array(scales_out)
+    _check(lib().dlcx_compress_batched(C.byref(d), phase, len(deltas), dp, _ptr(basis), cp, sp,
+                                       _ptr(workspace), _stream(stream)), "dlcx_compress_batched")
+
+
+def dlcx_average(d, phase, codes, scales, factor_out, workspace, stream=None):
+    cp, k1 = _ptr_array(codes)
+    sp, k2 = _ptr_array(scales)
+    _check(lib().dlcx_average(C.byref(d), phase, len(codes), cp, sp, _ptr(factor_out),
+                              _ptr(workspace), _stream(stream)), "dlcx_average")
+
+
+def dlcx_decompress(d, p_hat, q_bar, delta_hat_out, ef_inout=(), stream=None):
+    ep, keep = _ptr_array(list(ef_inout)) if len(ef_inout) else (None, None)
+    _check(lib().dlcx_decompress(C.byref(d), _ptr(p_hat), _ptr(q_bar), _ptr(delta_hat_out),
+                                 len(ef_inout), ep, _stream(stream)), "dlcx_decompress")
+
+
+def dlcx_outer_nesterov(theta_g, v, delta_hat, lr, mu, numel=None, stream=None):
+    n = theta_g.numel() if numel is None else numel
+    _check(lib().dlcx_outer_nesterov(_ptr(theta_g), _ptr(v), _ptr(delta_hat), n, lr, mu,
+                                     _stream(stream)), "dlcx_outer_nesterov")
+
+
+def dlcx_select_rank_workspace_bytes(descs):
+    arr = (Desc * max(len(descs), 1))(*descs)
+    return lib().dlcx_select_rank_workspace_bytes(arr, len(descs))
+
+
+def dlcx_select_rank(descs, q_bars, tau, rprime_hist, t, c, r1, rmin, rmax, H1, workspace=None,
+                     rprime=None, stream=None):
+    """rprime_hist: ctypes int32 array of length c (the caller's ring).  Returns (r', r_t, H_t)."""
+    n = len(descs)
+    arr = (Desc * max(n, 1))(*descs)
+    qp, keep = _ptr_array(list(q_bars)) if n else (None, None)
+    rp = C.c_int32(0 if rprime is None else rprime)
+    r_next, h_next = C.c_int32(0), C.c_int32(0)
+    _check(lib().dlcx_select_rank(arr, qp, n, tau, C.addressof(rprime_hist), t, c, r1, rmin, rmax,
+                                  H1, C.addressof(rp), C.addressof(r_next), C.addressof(h_next),
+                                  _ptr(workspace), _stream(stream) if n else None),
+           "dlcx_select_rank")
+    return rp.value, r_next.value, h_next.value
+
+
+def dlcx_project(d, phase, deltas, basis, factors_out, workspace, stream=None):
+    dp, k1 = _ptr_array(deltas)
+    fp, k2 = _ptr_array(factors_out)
+    _check(lib().dlcx_project(C.byref(d), phase, len(deltas), dp, _ptr(basis), fp, _ptr(workspace),
+                              _stream(stream)), "dlcx_project")
+
+
+def dlcx_quantize(x, qbits, group, codes_out, scales_out, count=None, stream=None):
+    n = x.numel() if count is None else count
+    _check(lib().dlcx_quantize(_ptr(x), n, qbits, group, _ptr(codes_out), _ptr(scales_out),
+                               _stream(stream)), "dlcx_quantize")
+
+
+def dlcx_dequant_average(codes, scales, count, qbits, group, mean_out, stream=None):
+    cp, k1 = _ptr_array(codes)
+    sp, k2 = _ptr_array(scales)
+    _check(lib().dlcx_dequant_average(len(codes), cp, sp, count, qbits, group, _ptr(mean_out),
+                                      _stream(stream)), "dlcx_dequant_average")
+
+
+def dlcx_orthonormalize(L, r, p_inout, workspace, stream=None):
+    _check(lib().dlcx_orthonormalize(L, r, _ptr(p_inout), _ptr(workspace), _stream(stream)),
+           "dlcx_orthonormalize")
+
+
+def dlcx_effective_rank(L, r, q_bar, tau, rprime_out_dev, workspace, stream=None):
+    _check(lib().dlcx_effective_rank(L, r, _ptr(q_bar), tau, _ptr(rprime_out_dev),
+                                     _ptr(workspace), _stream(stream)), "dlcx_effective_rank")

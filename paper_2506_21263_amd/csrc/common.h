@@ -1,0 +1,68 @@
+// Shared host/device declarations of the dlcx HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/dlcx.h"
+
+namespace dlcx {
+
+// K device pointers passed to a kernel by value.
+template <typename T>
+struct PtrPack {
+    T p[DLCX_MAX_WORKERS];
+};
+
+// Records a HIP error for dlcx_last_hip_error(); returns DLCX_ELAUNCH or DLCX_OK.
+int note_hip(hipError_t e, const char *where);
+
+inline int check_launch(const char *where) { return note_hip(hipGetLastError(), where); }
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+// ---- streaming kernels (k_stream.hip) -------------------------------------------------
+int launch_delta_ef(const float *theta_g, const void *theta_l, int dtype, float *ef,
+                    int64_t numel, hipStream_t st);
+int launch_nesterov(float *theta, float *v, const float *g, int64_t numel, float lr, float mu,
+                    hipStream_t st);
+
+// ---- quantiser (k_quant.hip) ----------------------------------------------------------
+// K factors of `count` floats each; x.p[k] -> codes.p[k], scales.p[k].
+int launch_quantize(int K, const PtrPack<const float *> &x, int64_t count, int qbits, int group,
+                    const PtrPack<uint8_t *> &codes, const PtrPack<float *> &scales,
+                    hipStream_t st);
+int launch_dequant_average(int K, const PtrPack<const uint8_t *> &codes,
+                           const PtrPack<const float *> &scales, int64_t count, int qbits,
+                           int group, float *mean_out, hipStream_t st);
+
+// ---- rank-r products ------------------------------------------------------------------
+// P_k = delta_k * Q_in   (delta m x n, q_in r x n, out r x m)
+int launch_project_p(int mma, int64_t m, int64_t n, int r, int K,
+                     const PtrPack<const float *> &delta, const float *q_in,
+                     const PtrPack<float *> &out, void *workspace, hipStream_t st);
+// Q_k = delta_k^T * P_hat (p_hat r x m, out r x n)
+int launch_project_q(int mma, int64_t m, int64_t n, int r, int K,
+                     const PtrPack<const float *> &delta, const float *p_hat,
+                     const PtrPack<float *> &out, void *workspace, hipStream_t st);
+// delta_hat = P_hat Q_bar^T, optionally written, and e_k <- e_k - delta_hat for K workers
+int launch_reconstruct(int mma, int64_t m, int64_t n, int r, const float *p_hat,
+                       const float *q_bar, float *delta_hat_out, int K,
+                       const PtrPack<float *> &ef, hipStream_t st);
+size_t project_workspace_bytes(int mma, int64_t m, int64_t n, int r, int K);
+
+// ---- orthonormalisation and effective rank (k_orth.hip, k_rank.hip) ---------------------
+size_t orth_workspace_bytes(int64_t L, int r);
+int launch_orthonormalize(int64_t L, int r, float *p_inout, void *workspace, hipStream_t st);
+size_t effrank_workspace_bytes(int64_t L, int r);
+int launch_effective_rank(int64_t L, int r, const float *q_bar, double tau, int32_t *rprime_dev,
+                          void *workspace, hipStream_t st);
+// fp64 Gram matrix partials of an r x L factor: part[chunk][a][b] for a <= b (others untouched)
+int gram_chunks(int64_t L);
+int launch_gram_partials(int64_t L, int r, const float *f, double *partials, hipStream_t st);
+
+}  // namespace dlcx

@@ -1,0 +1,355 @@
+// Entry points of libdlcx_hip.so: argument validation on the host, then kernel launches.
+// Nothing here allocates or synchronises, except dlcx_select_rank which returns integers.
+#include <string.h>
+
+#include <string>
+
+#include "common.h"
+
+namespace dlcx {
+
+static thread_local std::string g_last_error;
+
+int note_hip(hipError_t e, const char *where) {
+    if (e == hipSuccess) return DLCX_OK;
+    g_last_error = std::string(where) + ": " + hipGetErrorString(e);
+    return DLCX_ELAUNCH;
+}
+
+// k_gemm_fma.hip
+int launch_project_p_fma(int64_t, int64_t, int, int, const PtrPack<const float *> &, const float *,
+                         const PtrPack<float *> &, hipStream_t);
+int launch_project_q_fma(int64_t, int64_t, int, int, const PtrPack<const float *> &, const float *,
+                         const PtrPack<float *> &, void *, hipStream_t);
+int launch_reconstruct_fma(int64_t, int64_t, int, const float *, const float *, float *, int,
+                           const PtrPack<float *> &, hipStream_t);
+size_t fma_project_workspace_bytes(int64_t, int64_t, int, int);
+// k_gemm_mfma.hip
+int launch_project_p_mfma(int, int64_t, int64_t, int, int, const PtrPack<const float *> &,
+                          const float *, const PtrPack<float *> &, void *, hipStream_t);
+int launch_project_q_mfma(int, int64_t, int64_t, int, int, const PtrPack<const float *> &,
+                          const float *, const PtrPack<float *> &, void *, hipStream_t);
+int launch_reconstruct_mfma(int, int64_t, int64_t, int, const float *, const float *, float *, int,
+                            const PtrPack<float *> &, hipStream_t);
+size_t mfma_project_workspace_bytes(int, int64_t, int64_t, int, int);
+
+static bool group_ok(int g) { return g == 16 || g == 32 || g == 64 || g == 128 || g == 256; }
+
+static int check_desc(const dlcx_desc *d) {
+    if (!d) return DLCX_EINVAL;
+    if (d->m <= 0 || d->n <= 0) return DLCX_EINVAL;
+    if (d->qbits != 4 && d->qbits != 8) return DLCX_EINVAL;
+    if (!group_ok(d->group)) return DLCX_EINVAL;
+    if (d->m % d->group || d->n % d->group) return DLCX_EINVAL;
+    if (d->r < 1 || d->r > DLCX_MAX_RANK || d->r > d->m || d->r > d->n) return DLCX_EINVAL;
+    if (d->mma < DLCX_MMA_FMA || d->mma > DLCX_MMA_BF16) return DLCX_EINVAL;
+    return DLCX_OK;
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static size_t factor_region_bytes(const dlcx_desc *d, int K) {
+    const int64_t lmax = d->m > d->n ? d->m : d->n;
+    return align256((size_t)K * d->r * lmax * sizeof(float));
+}
+
+size_t project_workspace_bytes(int mma, int64_t m, int64_t n, int r, int K) {
+    if (mma == DLCX_MMA_FMA) return fma_project_workspace_bytes(m, n, r, K);
+    return mfma_project_workspace_bytes(mma, m, n, r, K);
+}
+
+int launch_project_p(int mma, int64_t m, int64_t n, int r, int K,
+                     const PtrPack<const float *> &delta, const float *q_in,
+                     const PtrPack<float *> &out, void *workspace, hipStream_t st) {
+    if (mma == DLCX_MMA_FMA) return launch_project_p_fma(m, n, r, K, delta, q_in, out, st);
+    return launch_project_p_mfma(mma, m, n, r, K, delta, q_in, out, workspace, st);
+}
+
+int launch_project_q(int mma, int64_t m, int64_t n, int r, int K,
+                     const PtrPack<const float *> &delta, const float *p_hat,
+                     const PtrPack<float *> &out, void *workspace, hipStream_t st) {
+    if (mma == DLCX_MMA_FMA) return launch_project_q_fma(m, n, r, K, delta, p_hat, out, workspace, st);
+    return launch_project_q_mfma(mma, m, n, r, K, delta, p_hat, out, workspace, st);
+}
+
+int launch_reconstruct(int mma, int64_t m, int64_t n, int r, const float *p_hat,
+                       const float *q_bar, float *delta_hat_out, int K,
+                       const PtrPack<float *> &ef, hipStream_t st) {
+    if (mma == DLCX_MMA_FMA)
+        return launch_reconstruct_fma(m, n, r, p_hat, q_bar, delta_hat_out, K, ef, st);
+    return launch_reconstruct_mfma(mma, m, n, r, p_hat, q_bar, delta_hat_out, K, ef, st);
+}
+
+}  // namespace dlcx
+
+using namespace dlcx;
+
+extern "C" {
+
+const char *dlcx_strerror(int code) {
+    switch (code) {
+        case DLCX_OK: return "ok";
+        case DLCX_EINVAL: return "invalid argument";
+        case DLCX_EUNSUPPORTED: return "unsupported configuration";
+        case DLCX_ELAUNCH: return "HIP runtime error";
+        default: return "unknown error code";
+    }
+}
+
+const char *dlcx_last_hip_error(void) { return g_last_error.c_str(); }
+
+size_t dlcx_payload_bytes(const dlcx_desc *desc, int phase, size_t *codes_bytes,
+                          size_t *scales_bytes) {
+    if (check_desc(desc) != DLCX_OK || (phase != DLCX_PHASE_P && phase != DLCX_PHASE_Q)) return 0;
+    const size_t count = (size_t)desc->r * (size_t)(phase == DLCX_PHASE_P ? desc->m : desc->n);
+    const size_t cb = desc->qbits == 4 ? count / 2 : count;
+    const size_t sb = count / desc->group * sizeof(float);
+    if (codes_bytes) *codes_bytes = cb;
+    if (scales_bytes) *scales_bytes = sb;
+    return cb + sb;
+}
+
+size_t dlcx_workspace_bytes(const dlcx_desc *desc, int K) {
+    if (check_desc(desc) != DLCX_OK || K < 1 || K > DLCX_MAX_WORKERS) return 0;
+    const int64_t lmax = desc->m > desc->n ? desc->m : desc->n;
+    const size_t proj = factor_region_bytes(desc, K) +
+                        project_workspace_bytes(desc->mma, desc->m, desc->n, desc->r, K);
+    const size_t orth = orth_workspace_bytes(lmax, desc->r);
+    const size_t rank = effrank_workspace_bytes(lmax, desc->r);
+    size_t w = proj > orth ? proj : orth;
+    if (rank > w) w = rank;
+    return align256(w);
+}
+
+size_t dlcx_select_rank_workspace_bytes(const dlcx_desc *descs, int n_matrices) {
+    if (n_matrices < 0 || (n_matrices > 0 && !descs)) return 0;
+    size_t total = align256((size_t)(n_matrices > 0 ? n_matrices : 1) * sizeof(int32_t));
+    for (int i = 0; i < n_matrices; ++i) {
+        if (check_desc(&descs[i]) != DLCX_OK) return 0;
+        total += align256(effrank_workspace_bytes(descs[i].n, descs[i].r));
+    }
+    return total;
+}
+
+int dlcx_delta_ef(const float *theta_g, const void *theta_l, int theta_l_dtype, float *ef_inout,
+                  int64_t numel, void *stream) {
+    if (numel < 0) return DLCX_EINVAL;
+    if (theta_l_dtype != DLCX_F32 && theta_l_dtype != DLCX_BF16) return DLCX_EINVAL;
+    if (numel == 0) return DLCX_OK;
+    if (!theta_g || !theta_l || !ef_inout) return DLCX_EINVAL;
+    if (!aligned16(theta_g) || !aligned16(theta_l) || !aligned16(ef_inout)) return DLCX_EINVAL;
+    return launch_delta_ef(theta_g, theta_l, theta_l_dtype, ef_inout, numel, as_stream(stream));
+}
+
+int dlcx_outer_nesterov(float *theta_g, float *v, const float *delta_hat, int64_t numel, float lr,
+                        float mu, void *stream) {
+    if (numel < 0) return DLCX_EINVAL;
+    if (numel == 0) return DLCX_OK;
+    if (!theta_g || !v || !delta_hat) return DLCX_EINVAL;
+    if (!aligned16(theta_g) || !aligned16(v) || !aligned16(delta_hat)) return DLCX_EINVAL;
+    if (!(lr == lr) || !(mu == mu)) return DLCX_EINVAL;
+    return launch_nesterov(theta_g, v, delta_hat, numel, lr, mu, as_stream(stream));
+}
+
+int dlcx_project(const dlcx_desc *desc, int phase, int K, const float *const *deltas_host,
+                 const float *basis, float *const *factors_out_host, void *workspace,
+                 void *stream) {
+    int rc = check_desc(desc);
+    if (rc != DLCX_OK) return rc;
+    if (phase != DLCX_PHASE_P && phase != DLCX_PHASE_Q) return DLCX_EINVAL;
+    if (K < 1 || K > DLCX_MAX_WORKERS || !deltas_host || !factors_out_host || !basis)
+        return DLCX_EINVAL;
+    if (!aligned16(basis) || !aligned16(workspace)) return DLCX_EINVAL;
+    PtrPack<const float *> d;
+    PtrPack<float *> o;
+    for (int k = 0; k < K; ++k) {
+        if (!deltas_host[k] || !factors_out_host[k]) return DLCX_EINVAL;
+        if (!aligned16(deltas_host[k]) || !aligned16(factors_out_host[k])) return DLCX_EINVAL;
+        d.p[k] = deltas_host[k];
+        o.p[k] = factors_out_host[k];
+    }
+    if (project_workspace_bytes(desc->mma, desc->m, desc->n, desc->r, K) > 0 && !workspace)
+        return DLCX_EINVAL;
+    if (phase == DLCX_PHASE_P)
+        return launch_project_p(desc->mma, desc->m, desc->n, desc->r, K, d, basis, o, workspace,
+                                as_stream(stream));
+    return launch_project_q(desc->mma, desc->m, desc->n, desc->r, K, d, basis, o, workspace,
+                            as_stream(stream));
+}
+
+int dlcx_quantize(const float *x, int64_t count, int qbits, int group, uint8_t *codes_out,
+                  float *scales_out, void *stream) {
+    if (count < 0 || (qbits != 4 && qbits != 8) || !group_ok(group) || count % group)
+        return DLCX_EINVAL;
+    if (count == 0) return DLCX_OK;
+    if (!x || !codes_out || !scales_out) return DLCX_EINVAL;
+    if (!aligned16(x) || !aligned16(codes_out) || !aligned16(scales_out)) return DLCX_EINVAL;
+    PtrPack<const float *> xs;
+    PtrPack<uint8_t *> cs;
+    PtrPack<float *> ss;
+    xs.p[0] = x;
+    cs.p[0] = codes_out;
+    ss.p[0] = scales_out;
+    return launch_quantize(1, xs, count, qbits, group, cs, ss, as_stream(stream));
+}
+
+int dlcx_compress_batched(const dlcx_desc *desc, int phase, int K,
+                          const float *const *deltas_host, const float *basis,
+                          uint8_t *const *codes_out_host, float *const *scales_out_host,
+                          void *workspace, void *stream) {
+    int rc = check_desc(desc);
+    if (rc != DLCX_OK) return rc;
+    if (phase != DLCX_PHASE_P && phase != DLCX_PHASE_Q) return DLCX_EINVAL;
+    if (K < 1 || K > DLCX_MAX_WORKERS || !deltas_host || !codes_out_host || !scales_out_host ||
+        !basis || !workspace)
+        return DLCX_EINVAL;
+    if (!aligned16(workspace)) return DLCX_EINVAL;
+    const int64_t L = phase == DLCX_PHASE_P ? desc->m : desc->n;
+    const int64_t count = (int64_t)desc->r * L;
+    float *factors[DLCX_MAX_WORKERS];
+    PtrPack<const float *> xs;
+    PtrPack<uint8_t *> cs;
+    PtrPack<float *> ss;
+    for (int k = 0; k < K; ++k) {
+        if (!codes_out_host[k] || !scales_out_host[k]) return DLCX_EINVAL;
+        if (!aligned16(codes_out_host[k]) || !aligned16(scales_out_host[k])) return DLCX_EINVAL;
+        factors[k] = reinterpret_cast<float *>(workspace) + (int64_t)k * count;
+        xs.p[k] = factors[k];
+        cs.p[k] = codes_out_host[k];
+        ss.p[k] = scales_out_host[k];
+    }
+    void *inner = reinterpret_cast<char *>(workspace) + factor_region_bytes(desc, K);
+    rc = dlcx_project(desc, phase, K, deltas_host, basis, factors, inner, stream);
+    if (rc != DLCX_OK) return rc;
+    return launch_quantize(K, xs, count, desc->qbits, desc->group, cs, ss, as_stream(stream));
+}
+
+int dlcx_compress(const dlcx_desc *desc, int phase, const float *delta, const float *basis,
+                  uint8_t *codes_out, float *scales_out, void *workspace, void *stream) {
+    const float *d[1] = {delta};
+    uint8_t *c[1] = {codes_out};
+    float *s[1] = {scales_out};
+    return dlcx_compress_batched(desc, phase, 1, d, basis, c, s, workspace, stream);
+}
+
+int dlcx_dequant_average(int K, const uint8_t *const *codes_host, const float *const *scales_host,
+                         int64_t count, int qbits, int group, float *mean_out, void *stream) {
+    if (K < 1 || K > DLCX_MAX_WORKERS || count < 0 || (qbits != 4 && qbits != 8) ||
+        !group_ok(group) || count % group)
+        return DLCX_EINVAL;
+    if (count == 0) return DLCX_OK;
+    if (!codes_host || !scales_host || !mean_out || !aligned16(mean_out)) return DLCX_EINVAL;
+    PtrPack<const uint8_t *> cs;
+    PtrPack<const float *> ss;
+    for (int k = 0; k < K; ++k) {
+        if (!codes_host[k] || !scales_host[k]) return DLCX_EINVAL;
+        if (!aligned16(codes_host[k]) || !aligned16(scales_host[k])) return DLCX_EINVAL;
+        cs.p[k] = codes_host[k];
+        ss.p[k] = scales_host[k];
+    }
+    return launch_dequant_average(K, cs, ss, count, qbits, group, mean_out, as_stream(stream));
+}
+
+int dlcx_orthonormalize(int64_t L, int32_t r, float *p_inout, void *workspace, void *stream) {
+    if (L <= 0 || L % 16 || r < 1 || r > DLCX_MAX_RANK || r > L) return DLCX_EINVAL;
+    if (!p_inout || !workspace || !aligned16(p_inout) || !aligned16(workspace)) return DLCX_EINVAL;
+    return launch_orthonormalize(L, r, p_inout, workspace, as_stream(stream));
+}
+
+int dlcx_average(const dlcx_desc *desc, int phase, int K, const uint8_t *const *codes_host,
+                 const float *const *scales_host, float *factor_out, void *workspace,
+                 void *stream) {
+    int rc = check_desc(desc);
+    if (rc != DLCX_OK) return rc;
+    if (phase != DLCX_PHASE_P && phase != DLCX_PHASE_Q) return DLCX_EINVAL;
+    const int64_t L = phase == DLCX_PHASE_P ? desc->m : desc->n;
+    rc = dlcx_dequant_average(K, codes_host, scales_host, (int64_t)desc->r * L, desc->qbits,
+                              desc->group, factor_out, stream);
+    if (rc != DLCX_OK || phase == DLCX_PHASE_Q) return rc;
+    return dlcx_orthonormalize(L, desc->r, factor_out, workspace, stream);
+}
+
+int dlcx_decompress(const dlcx_desc *desc, const float *p_hat, const float *q_bar,
+                    float *delta_hat_out, int K, float *const *ef_inout_host, void *stream) {
+    int rc = check_desc(desc);
+    if (rc != DLCX_OK) return rc;
+    if (K < 0 || K > DLCX_MAX_WORKERS || !p_hat || !q_bar) return DLCX_EINVAL;
+    if (K > 0 && !ef_inout_host) return DLCX_EINVAL;
+    if (!aligned16(p_hat) || !aligned16(q_bar) || !aligned16(delta_hat_out)) return DLCX_EINVAL;
+    if (K == 0 && !delta_hat_out) return DLCX_OK;
+    PtrPack<float *> ef;
+    for (int k = 0; k < K; ++k) {
+        if (!ef_inout_host[k] || !aligned16(ef_inout_host[k])) return DLCX_EINVAL;
+        ef.p[k] = ef_inout_host[k];
+    }
+    return launch_reconstruct(desc->mma, desc->m, desc->n, desc->r, p_hat, q_bar, delta_hat_out, K,
+                              ef, as_stream(stream));
+}
+
+int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,
+                        int32_t *rprime_out_dev, void *workspace, void *stream) {
+    if (L <= 0 || L % 16 || r < 1 || r > DLCX_MAX_RANK || r > L) return DLCX_EINVAL;
+    if (!(tau > 0.0 && tau <= 1.0)) return DLCX_EINVAL;
+    if (!q_bar || !rprime_out_dev || !workspace || !aligned16(q_bar) || !aligned16(workspace))
+        return DLCX_EINVAL;
+    return launch_effective_rank(L, r, q_bar, tau, rprime_out_dev, workspace, as_stream(stream));
+}
+
+int dlcx_select_rank(const dlcx_desc *descs_host, const float *const *q_bars_host, int n_matrices,
+                     double tau, int32_t *rprime_hist_host, int32_t t, int32_t c, int32_t r1,
+                     int32_t rmin, int32_t rmax, int32_t H1, int32_t *rprime_inout_host,
+                     int32_t *r_next_out_host, int32_t *H_next_out_host, void *workspace,
+                     void *stream) {
+    if (n_matrices < 0 || t < 1 || c < 1 || r1 < 1 || rmin < 1 || rmax < rmin || H1 < 1)
+        return DLCX_EINVAL;
+    if (!rprime_hist_host || !rprime_inout_host || !r_next_out_host || !H_next_out_host)
+        return DLCX_EINVAL;
+    if (n_matrices > 0) {
+        if (!descs_host || !q_bars_host || !workspace || !aligned16(workspace)) return DLCX_EINVAL;
+        if (!(tau > 0.0 && tau <= 1.0)) return DLCX_EINVAL;
+        for (int i = 0; i < n_matrices; ++i) {
+            if (check_desc(&descs_host[i]) != DLCX_OK) return DLCX_EINVAL;
+            if (!q_bars_host[i] || !aligned16(q_bars_host[i])) return DLCX_EINVAL;
+        }
+        int32_t *out_dev = reinterpret_cast<int32_t *>(workspace);
+        char *ws = reinterpret_cast<char *>(workspace) + align256((size_t)n_matrices * sizeof(int32_t));
+        for (int i = 0; i < n_matrices; ++i) {
+            int rc = launch_effective_rank(descs_host[i].n, descs_host[i].r, q_bars_host[i], tau,
+                                           out_dev + i, ws, as_stream(stream));
+            if (rc != DLCX_OK) return rc;
+            ws += align256(effrank_workspace_bytes(descs_host[i].n, descs_host[i].r));
+        }
+        std::string tmp;
+        tmp.resize((size_t)n_matrices * sizeof(int32_t));
+        int rc = note_hip(hipMemcpyAsync(&tmp[0], out_dev, tmp.size(), hipMemcpyDeviceToHost,
+                                         as_stream(stream)),
+                          "select_rank copy");
+        if (rc != DLCX_OK) return rc;
+        rc = note_hip(hipStreamSynchronize(as_stream(stream)), "select_rank sync");
+        if (rc != DLCX_OK) return rc;
+        const int32_t *vals = reinterpret_cast<const int32_t *>(tmp.data());
+        int64_t sum = 0;
+        for (int i = 0; i < n_matrices; ++i) sum += vals[i] > 0 ? vals[i] : rmin;
+        *rprime_inout_host = (int32_t)((2 * sum + n_matrices) / (2 * (int64_t)n_matrices));
+    }
+    rprime_hist_host[(t - 1) % c] = *rprime_inout_host;
+    if (t < c) {
+        *r_next_out_host = r1;
+        *H_next_out_host = H1;
+        return DLCX_OK;
+    }
+    int64_t sum = 0;
+    for (int i = 0; i < c; ++i) sum += rprime_hist_host[i];
+    int64_t rt = (2 * sum + c) / (2 * (int64_t)c);
+    if (rt < rmin) rt = rmin;
+    if (rt > rmax) rt = rmax;
+    // H_t = H_1 (r_1 - r_t) / r_1, rounded half-up, at least 1
+    const int64_t num = (int64_t)H1 * ((int64_t)r1 - rt);
+    int64_t H = num >= 0 ? (2 * num + r1) / (2 * (int64_t)r1) : 0;
+    if (H < 1) H = 1;
+    *r_next_out_host = (int32_t)rt;
+    *H_next_out_host = (int32_t)H;
+    return DLCX_OK;
+}
+
+}  // extern "C"

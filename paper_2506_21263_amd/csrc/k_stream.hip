@@ -1,0 +1,135 @@
+// Streaming kernels of the outer step: pseudo-gradient with error compensation (Alg. 2) and the
+// Nesterov outer update (Appendix A.3).  Both are pure HBM streams: every thread moves UNROLL
+// 16-byte vectors, all loads issued before the first use so that a wave keeps several KB in
+// flight.
+#include "common.h"
+
+namespace dlcx {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;  // float4 per thread
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
+    return __uint_as_float(bits16 << 16);
+}
+
+template <bool kBf16>
+__global__ __launch_bounds__(kThreads) void delta_ef_kernel(const float *__restrict__ theta_g,
+                                                            const void *__restrict__ theta_l,
+                                                            float *__restrict__ ef,
+                                                            int64_t numel) {
+    const int64_t nvec = numel >> 2;
+    const int64_t base = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+    float4 g[kUnroll], e[kUnroll], l[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t v = base + (int64_t)u * kThreads;
+        if (v < nvec) {
+            g[u] = reinterpret_cast<const float4 *>(theta_g)[v];
+            e[u] = reinterpret_cast<const float4 *>(ef)[v];
+            if (kBf16) {
+                const uint2 b = reinterpret_cast<const uint2 *>(theta_l)[v];
+                l[u] = make_float4(bf16_bits_to_f32(b.x & 0xFFFFu), bf16_bits_to_f32(b.x >> 16),
+                                   bf16_bits_to_f32(b.y & 0xFFFFu), bf16_bits_to_f32(b.y >> 16));
+            } else {
+                l[u] = reinterpret_cast<const float4 *>(theta_l)[v];
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t v = base + (int64_t)u * kThreads;
+        if (v < nvec) {
+            float4 d;
+            d.x = (g[u].x - l[u].x) + e[u].x;
+            d.y = (g[u].y - l[u].y) + e[u].y;
+            d.z = (g[u].z - l[u].z) + e[u].z;
+            d.w = (g[u].w - l[u].w) + e[u].w;
+            reinterpret_cast<float4 *>(ef)[v] = d;
+        }
+    }
+    // ragged tail (numel not a multiple of 4): the last block's first threads
+    if (blockIdx.x == gridDim.x - 1) {
+        const int64_t x = (nvec << 2) + threadIdx.x;
+        if (threadIdx.x < 4 && x < numel) {
+            float tl;
+            if (kBf16)
+                tl = bf16_bits_to_f32(reinterpret_cast<const uint16_t *>(theta_l)[x]);
+            else
+                tl = reinterpret_cast<const float *>(theta_l)[x];
+            ef[x] = (theta_g[x] - tl) + ef[x];
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void nesterov_kernel(float *__restrict__ theta,
+                                                            float *__restrict__ vel,
+                                                            const float *__restrict__ grad,
+                                                            int64_t numel, float lr, float mu) {
+    const int64_t nvec = numel >> 2;
+    const int64_t base = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+    float4 t[kUnroll], v[kUnroll], g[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t i = base + (int64_t)u * kThreads;
+        if (i < nvec) {
+            t[u] = reinterpret_cast<const float4 *>(theta)[i];
+            v[u] = reinterpret_cast<const float4 *>(vel)[i];
+            g[u] = reinterpret_cast<const float4 *>(grad)[i];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t i = base + (int64_t)u * kThreads;
+        if (i < nvec) {
+            float4 vn, tn;
+            vn.x = fmaf(mu, v[u].x, g[u].x);
+            vn.y = fmaf(mu, v[u].y, g[u].y);
+            vn.z = fmaf(mu, v[u].z, g[u].z);
+            vn.w = fmaf(mu, v[u].w, g[u].w);
+            tn.x = fmaf(-lr, fmaf(mu, vn.x, g[u].x), t[u].x);
+            tn.y = fmaf(-lr, fmaf(mu, vn.y, g[u].y), t[u].y);
+            tn.z = fmaf(-lr, fmaf(mu, vn.z, g[u].z), t[u].z);
+            tn.w = fmaf(-lr, fmaf(mu, vn.w, g[u].w), t[u].w);
+            reinterpret_cast<float4 *>(vel)[i] = vn;
+            reinterpret_cast<float4 *>(theta)[i] = tn;
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1) {
+        const int64_t x = (nvec << 2) + threadIdx.x;
+        if (threadIdx.x < 4 && x < numel) {
+            const float vn = fmaf(mu, vel[x], grad[x]);
+            theta[x] = fmaf(-lr, fmaf(mu, vn, grad[x]), theta[x]);
+            vel[x] = vn;
+        }
+    }
+}
+
+static inline unsigned stream_blocks(int64_t numel) {
+    const int64_t per_block = (int64_t)kThreads * kUnroll * 4;
+    int64_t b = ceil_div(numel, per_block);
+    return (unsigned)(b < 1 ? 1 : b);
+}
+
+int launch_delta_ef(const float *theta_g, const void *theta_l, int dtype, float *ef,
+                    int64_t numel, hipStream_t st) {
+    if (numel == 0) return DLCX_OK;
+    const unsigned blocks = stream_blocks(numel);
+    if (dtype == DLCX_BF16)
+        hipLaunchKernelGGL(delta_ef_kernel<true>, dim3(blocks), dim3(kThreads), 0, st, theta_g,
+                           theta_l, ef, numel);
+    else
+        hipLaunchKernelGGL(delta_ef_kernel<false>, dim3(blocks), dim3(kThreads), 0, st, theta_g,
+                           theta_l, ef, numel);
+    return check_launch("delta_ef");
+}
+
+int launch_nesterov(float *theta, float *v, const float *g, int64_t numel, float lr, float mu,
+                    hipStream_t st) {
+    if (numel == 0) return DLCX_OK;
+    hipLaunchKernelGGL(nesterov_kernel, dim3(stream_blocks(numel)), dim3(kThreads), 0, st, theta,
+                       v, g, numel, lr, mu);
+    return check_launch("outer_nesterov");
+}
+
+}  // namespace dlcx

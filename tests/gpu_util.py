@@ -1,0 +1,57 @@
+"""Helpers shared by the GPU parity tests (numpy <-> device tensors, error measures)."""
+import numpy as np
+import torch
+
+import paper_2506_21263_amd as dlcx
+
+DEV = "cuda:0"
+
+
+def to_dev(a):
+    """numpy array -> device tensor with the same bytes (uint16 arrays are bf16 bit patterns)."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(a).to(DEV)
+
+
+def to_np(t):
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def rel_l2(got, want):
+    got = np.asarray(got, np.float64).ravel()
+    want = np.asarray(want, np.float64).ravel()
+    den = np.linalg.norm(want)
+    return np.linalg.norm(got - want) / (den if den > 0 else 1.0)
+
+
+def ws_for(d, K):
+    return torch.empty(dlcx.dlcx_workspace_bytes(d, K), device=DEV, dtype=torch.uint8)
+
+
+def payload_buffers(d, phase, K):
+    _, cb, sb = dlcx.dlcx_payload_bytes(d, phase)
+    codes = [torch.zeros(cb, device=DEV, dtype=torch.uint8) for _ in range(K)]
+    scales = [torch.zeros(sb // 4, device=DEV, dtype=torch.float32) for _ in range(K)]
+    return codes, scales
+
+
+def code_mismatch_report(codes_gpu, codes_ref, x_ref, scales_ref, count, qbits, group, unpack):
+    """Compare integer codes where the two sides quantised slightly different floats.
+
+    Returns (n_mismatch, all_legit): a mismatch is legitimate when it is by one step and the
+    reference value sits within `slack` of a rounding boundary (half-integer of x / scale).
+    """
+    a = unpack(codes_gpu, count, qbits)
+    b = unpack(codes_ref, count, qbits)
+    bad = np.nonzero(a != b)[0]
+    if bad.size == 0:
+        return 0, True
+    s = np.repeat(scales_ref, group)[bad].astype(np.float64)
+    u = x_ref.ravel()[bad].astype(np.float64) / np.where(s > 0, s, 1.0)
+    frac = np.abs(u - np.floor(u) - 0.5)
+    legit = (np.abs(a[bad] - b[bad]) == 1) & (frac < 1e-2)
+    return int(bad.size), bool(np.all(legit))

@@ -1,0 +1,90 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes payloads as the paper's accounting implies, and rejects bad arguments
+before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2506_21263_amd as dlcx
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dlcx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dlcx_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = C.CDLL(dlcx.LIB_PATH)
+    names = declared_symbols()
+    assert {"dlcx_delta_ef", "dlcx_compress", "dlcx_average", "dlcx_decompress",
+            "dlcx_outer_nesterov", "dlcx_select_rank"} <= set(names)
+    for name in names:
+        assert hasattr(L, name), name
+    assert set(names) == set(dlcx.SYMBOLS), set(names) ^ set(dlcx.SYMBOLS)
+
+
+def test_payload_bytes_follow_the_layout():
+    d = dlcx.desc(8192, 8192, 64, 4, 128)
+    total, cb, sb = dlcx.dlcx_payload_bytes(d, dlcx.PHASE_P)
+    assert cb == 8192 * 64 // 2 and sb == 8192 * 64 // 128 * 4 and total == cb + sb
+    d8 = dlcx.desc(512, 1024, 8, 8, 64)
+    assert dlcx.dlcx_payload_bytes(d8, dlcx.PHASE_Q)[1:] == (1024 * 8, 1024 * 8 // 64 * 4)
+    # config 0: (m + n) r = 8192 factor elements -> 4096 + 512 = 4608 payload bytes per worker
+    d0 = dlcx.desc(512, 512, 8, 4, 64)
+    assert dlcx.dlcx_payload_bytes(d0, 0)[0] + dlcx.dlcx_payload_bytes(d0, 1)[0] == 4608
+    assert dlcx.dlcx_workspace_bytes(d, 4) >= 4 * 64 * 8192 * 4
+
+
+@pytest.mark.parametrize("bad", [
+    dict(m=0), dict(n=-16), dict(r=0), dict(r=257), dict(r=600), dict(qbits=3), dict(qbits=16),
+    dict(group=48), dict(group=0), dict(m=520), dict(mma=3), dict(mma=-1)])
+def test_bad_descriptors_are_rejected(bad):
+    kw = dict(m=512, n=512, r=8, qbits=4, group=64, mma=0)
+    kw.update(bad)
+    d = dlcx.desc(**kw)
+    assert dlcx.dlcx_payload_bytes(d, 0)[0] == 0
+    assert dlcx.dlcx_workspace_bytes(d, 2) == 0
+    L = dlcx.lib()
+    fake = 0x1000  # aligned, never dereferenced: validation fails first
+    assert L.dlcx_compress(C.byref(d), 0, fake, fake, fake, fake, fake, None) == dlcx.EINVAL
+    assert L.dlcx_decompress(C.byref(d), fake, fake, fake, 0, None, None) == dlcx.EINVAL
+
+
+def test_null_misaligned_and_range_arguments():
+    L = dlcx.lib()
+    fake = 0x1000
+    assert L.dlcx_delta_ef(None, fake, 0, fake, 16, None) == dlcx.EINVAL
+    assert L.dlcx_delta_ef(fake, fake, 0, fake + 4, 16, None) == dlcx.EINVAL   # misaligned
+    assert L.dlcx_delta_ef(fake, fake, 7, fake, 16, None) == dlcx.EINVAL      # dtype
+    assert L.dlcx_delta_ef(fake, fake, 0, fake, -1, None) == dlcx.EINVAL
+    assert L.dlcx_delta_ef(None, None, 0, None, 0, None) == dlcx.OK           # empty input
+    assert L.dlcx_outer_nesterov(fake, None, fake, 4, 0.7, 0.9, None) == dlcx.EINVAL
+    assert L.dlcx_outer_nesterov(None, None, None, 0, 0.7, 0.9, None) == dlcx.OK
+    assert L.dlcx_quantize(fake, 100, 4, 64, fake, fake, None) == dlcx.EINVAL  # count % group
+    assert L.dlcx_quantize(fake, 128, 5, 64, fake, fake, None) == dlcx.EINVAL
+    assert L.dlcx_quantize(None, 0, 4, 64, None, None, None) == dlcx.OK
+    d = dlcx.desc(512, 512, 8, 4, 64)
+    assert L.dlcx_compress(C.byref(d), 2, fake, fake, fake, fake, fake, None) == dlcx.EINVAL
+    assert L.dlcx_compress(C.byref(d), 0, fake, fake, fake, fake, None, None) == dlcx.EINVAL
+    assert L.dlcx_average(C.byref(d), 0, 0, fake, fake, fake, fake, None) == dlcx.EINVAL  # K = 0
+    assert L.dlcx_average(C.byref(d), 0, 17, fake, fake, fake, fake, None) == dlcx.EINVAL
+    assert L.dlcx_orthonormalize(100, 4, fake, fake, None) == dlcx.EINVAL      # L % 16
+    assert L.dlcx_effective_rank(64, 4, fake, 1.5, fake, fake, None) == dlcx.EINVAL  # tau
+    assert dlcx.lib().dlcx_strerror(dlcx.EINVAL) == b"invalid argument"
+
+
+def test_select_rank_window_rule_on_the_host(golden):
+    g = golden("adagradcmp_window.txt")
+    c, r1, H1 = int(g["c"][0]), int(g["r1"][0]), int(g["H1"][0])
+    hist = (C.c_int32 * c)()
+    for t in range(1, 9):
+        rp, r, H = dlcx.dlcx_select_rank([], [], 0.99, hist, t, c, r1, 4, r1, H1,
+                                         rprime=int(g["rprime"][t - 1]))
+        assert (rp, r, H) == (int(g["rprime"][t - 1]), int(g["r_t"][t - 1]), int(g["H_t"][t - 1]))
+    with pytest.raises(dlcx.DlcxError):
+        dlcx.dlcx_select_rank([], [], 0.99, hist, 0, c, r1, 4, r1, H1, rprime=4)
