@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Outer-step throughput of one ~100B-class pipeline stage on one MI355X.
+
+One "step" is one full outer step of Alg. 2 (DiLoCoX) over every matrix of the stage: error
+buffers and outer Nesterov update from the previous round's average, pseudo-gradients with error
+compensation for K simulated workers, both compression phases (projection, quantisation,
+in-memory "AllReduce" average, orthonormalisation), and the rank measurement of Alg. 3.
+Inputs are synthetic (synth/), resident in HBM before the timed region.
+
+Prints ONE JSON line (see the keys below).  `value` is stage parameters per second.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_stage(cfg_id, mma, layers, device, fused):
+    import torch
+
+    import synth
+    from paper_2506_21263_amd.stage import MatrixState, Stage
+
+    cfg = synth.CONFIGS[cfg_id]
+    K, r = cfg["K"], cfg["r"]
+    mats, locals_ = [], []
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(1234 + cfg_id)
+    t0 = time.time()
+    idx = 0
+    for layer in range(layers):
+        for (m, n) in cfg["layer_shapes"]:
+            alpha = cfg["alpha"]
+            if alpha is None or alpha == "per-round":
+                alpha = float(0.5 + 1.5 * torch.rand(1, generator=gen).item())
+            sigma = float(synth.noise_sigma(cfg_id, m, n))
+            t = synth.torch_matrix_inputs(m, n, K, r, seed=synth.seed_for(cfg_id, layer, idx),
+                                          sigma=sigma, alpha=alpha, theta_l=cfg["theta_l"],
+                                          device=device)
+            mats.append(MatrixState(t["theta_g"], K, t["q_in"], cfg["qbits"], cfg["group"], mma))
+            locals_.append(t["theta_l"])
+            idx += 1
+        log("generated layer %d/%d  (%.1f s, %.1f GB allocated)" %
+            (layer + 1, layers, time.time() - t0, torch.cuda.memory_allocated() / 1e9))
+    stage = Stage(mats, synth.LR, synth.MU, fused=fused, warm_start=True)
+    return stage, locals_
+
+
+def algorithmic_bytes_per_param(kernel, K, tl_bytes, fused):
+    """HBM bytes one launch of `kernel` must move per matrix element (factor traffic, a few
+    per cent of it at r = 64, left out): every state read once and written once."""
+    table = {
+        "delta_ef": 4 + tl_bytes + 4 + 4,          # theta_g, theta_l, e in; delta out (per worker)
+        "project_p": 4 * K,                         # delta of K workers, read once
+        "project_q": 4 * K,
+        "outer_nesterov": 20,                       # theta, v in/out; delta_hat in
+        # fused: e_k in, theta_l,k in, delta_k out per worker + theta, v in/out
+        "reconstruct": ((8 + tl_bytes) * K + 16) if fused else (4 + 8 * K),
+    }
+    return table.get(kernel)
+
+
+def cpu_baseline(stage, locals_, cfg_id):
+    """The oracle, as it stands, on one matrix of the workload: two outer steps of the smallest
+    matrix shape of the stage (K workers), single thread."""
+    import numpy as np
+
+    import synth
+    from oracle import pipeline
+
+    cfg = synth.CONFIGS[cfg_id]
+    sizes = [M.m * M.n for M in stage.mats]
+    a = sizes.index(min(sizes))
+    M = stage.mats[a]
+    theta = M.theta_g.cpu().numpy()
+    q_in = M.q_in[: M.r].cpu().numpy()
+    tl = []
+    for x in locals_[a]:
+        if x.dtype.is_floating_point and x.element_size() == 2:
+            tl.append(x.view(__import__("torch").int16).cpu().numpy().view(np.uint16))
+        else:
+            tl.append(x.cpu().numpy())
+    orc = pipeline.MatrixOracle(theta, M.K, q_in, cfg["qbits"], cfg["group"], synth.LR, synth.MU)
+    t0 = time.time()
+    orc.step(tl)
+    orc.set_basis(orc.q_bar)
+    orc.step(tl)
+    dt = (time.time() - t0) / 2.0
+    return {"value": M.m * M.n / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": "2 outer steps of one %dx%d matrix of the stage (K=%d, r=%d, int%d/%d), "
+                      "%.1f s per step" % (M.m, M.n, M.K, M.r, cfg["qbits"], cfg["group"], dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration (synth.CONFIGS)")
+    ap.add_argument("--mma", type=int, default=2, help="0 fma/fp64-acc, 1 fp32-accurate MFMA, 2 bf16 MFMA")
+    ap.add_argument("--layers", type=int, default=0, help="layers resident (0 = the whole stage)")
+    ap.add_argument("--unfused", action="store_true", help="separate decompress / Nesterov kernels")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE MI355X; --gpus %d is not supported "
+              "(no collectives, no second GPU in this run)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2506_21263_amd as dlcx
+    import synth
+    from paper_2506_21263_amd.stage import RankSelector
+
+    dlcx.lib()  # fail loudly if the HIP library is missing
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    layers = args.layers or cfg["layers"]
+    fused = not args.unfused
+    stage, locals_ = build_stage(args.config, args.mma, layers, device, fused)
+    K = cfg["K"]
+    params = stage.params()
+    selector = RankSelector(stage, c=5, r1=cfg["r"], rmin=4, rmax=cfg["r"], H1=125)
+    selector.first()
+    log("stage: %d matrices, %.3f G params, K=%d, %.1f GB allocated" %
+        (len(stage.mats), params / 1e9, K, torch.cuda.memory_allocated() / 1e9))
+
+    def one_step():
+        stage.step(locals_)
+        # Alg. 3: measure r' on this round's averages (the configuration keeps the rank fixed,
+        # so the window rule's output is computed and not applied)
+        selector.next(stage.t + 1)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = params / (dt / args.steps)
+
+    # per-kernel durations: the same steps again with HIP events around every launch
+    dlcx.dlcx_profile_enable(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt_prof = time.perf_counter() - t1
+    prof = dlcx.dlcx_profile_read()
+    dlcx.dlcx_profile_enable(False)
+    tl_bytes = 2 if cfg["theta_l"] == "bf16" else 4
+    kernels = {}
+    for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+        kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps}
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    bpp = algorithmic_bytes_per_param(dom, K, tl_bytes, fused)
+    roofline = None
+    if bpp is not None:
+        per_worker = dom == "delta_ef"
+        launches = kernels[dom]["launches_per_step"]
+        # bytes of all launches of the kernel in one step / their summed duration
+        total_bytes = bpp * params * (K if per_worker else 1)
+        achieved = total_bytes / (kernels[dom]["ms_per_step"] * 1e-3) / 1e9
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "algorithmic_bytes_per_param_per_launch": bpp,
+                    "avg_launch_ms": kernels[dom]["ms_per_step"] / launches,
+                    "launches_per_step": launches}
+    b_alg = (14 if tl_bytes == 2 else 16) * K + 20
+    out = {
+        "metric": "outer-step params/sec per stage (compress+avg+Nesterov)",
+        "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": {0: "f32 (fp64 accumulate)", 1: "bf16x3-split MFMA (fp32-accurate), f32 accumulate",
+                  2: "bf16x2-split MFMA, f32 accumulate"}[args.mma],
+        "data": "synthetic",
+        "config": {"workload": cfg["name"], "layers": layers, "matrices": len(stage.mats),
+                   "params": params, "K": K, "rank": cfg["r"], "qbits": cfg["qbits"],
+                   "group": cfg["group"], "theta_l": cfg["theta_l"], "mma": args.mma,
+                   "fused": fused},
+        "roofline": roofline,
+        "stage_hbm": {"algorithmic_bytes_per_param": b_alg,
+                      "achieved_GBps": b_alg * params / (dt / args.steps) / 1e9,
+                      "frac_of_8TBps": b_alg * params / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
+        "kernels": kernels,
+        "ms_per_step_with_events": dt_prof / args.steps * 1e3,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(stage, locals_, args.config)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -4,7 +4,7 @@
  * C ABI of libdlcx_hip.so.  Every pointer is a DEVICE pointer unless its name
  * ends in _host; arrays of pointers (one entry per simulated data-parallel
  * worker) are HOST arrays of device pointers.  The library keeps no state and
- * never allocates: the caller owns every buffer, scratch space is passed as
+ * never allocates device memory: the caller owns every buffer, scratch space is passed as
  * `workspace` (size from dlcx_workspace_bytes).  All calls are asynchronous on
  * `stream` (a hipStream_t, NULL = the default stream) and never synchronise,
  * except dlcx_select_rank, which returns integers to the host.
@@ -98,7 +98,25 @@ int dlcx_average(const dlcx_desc *desc, int phase, int K, const uint8_t *const *
  * e_i <- delta_i - Delta_hat, for K >= 0 workers.  delta_hat_out (m x n) may be NULL when only
  * the error buffers are wanted; ef_inout_host may be NULL when K == 0. */
 int dlcx_decompress(const dlcx_desc *desc, const float *p_hat, const float *q_bar,
-                    float *delta_hat_out, int K, float *const *ef_inout_host, void *stream);
+                    float *delta_hat_out, int K, float *const *ef_inout_host, void *workspace,
+                    void *stream);
+
+/* The same decompression fused with its two consumers in Alg. 2, so that Delta_hat is never
+ * written to memory: e_i <- delta_i - Delta_hat for K >= 0 workers, then the OuterOpt step
+ * v <- mu v + Delta_hat ; theta_g <- theta_g - lr (Delta_hat + mu v), all tile by tile. */
+int dlcx_decompress_apply(const dlcx_desc *desc, const float *p_hat, const float *q_bar, int K,
+                          float *const *ef_inout_host, float *theta_g, float *v, float lr,
+                          float mu, void *workspace, void *stream);
+
+/* One pass over the matrix for everything Alg. 2 does between two compressions (outer step
+ * t >= 2), in its order:  e_i <- delta_i - Delta_hat  (previous round's average, P_hat Q_bar^T,
+ * never written to memory);  delta_i <- (theta_g - theta_l,i) + e_i  with theta_g still the
+ * value of step t-1;  then  theta_g <- OuterOpt(theta_g, Delta_hat).  Same result as
+ * dlcx_decompress (error buffers), K x dlcx_delta_ef and dlcx_outer_nesterov in that order. */
+int dlcx_ef_delta_apply(const dlcx_desc *desc, const float *p_hat, const float *q_bar, int K,
+                        const void *const *theta_l_host, int theta_l_dtype,
+                        float *const *ef_inout_host, float *theta_g, float *v, float lr, float mu,
+                        void *workspace, void *stream);
 
 /* OuterOpt of Alg. 2 / Appendix A.3: SGD with Nesterov momentum on the averaged
  * pseudo-gradient,  v <- mu v + g ;  theta_g <- theta_g - lr (g + mu v).  In place. */
@@ -148,6 +166,17 @@ int dlcx_orthonormalize(int64_t L, int32_t r, float *p_inout, void *workspace, v
 /* r' of one matrix, written to a DEVICE int32 (0 when Q_bar is all zero); asynchronous. */
 int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,
                         int32_t *rprime_out_dev, void *workspace, void *stream);
+
+/* ---- instrumentation ----------------------------------------------------------------------
+ * Per-kernel timing with HIP events on the launch stream.  dlcx_profile_enable(1) clears the
+ * records and starts recording every kernel launch of this library (process-wide, not
+ * thread-safe, meant for benchmarks); dlcx_profile_read waits for the recorded launches of one
+ * kernel id (0 .. dlcx_profile_kernels()-1) and returns their summed duration and count;
+ * dlcx_profile_enable(0) stops recording and frees the events. */
+int dlcx_profile_enable(int on);
+int dlcx_profile_kernels(void);
+const char *dlcx_profile_name(int kernel_id);
+int dlcx_profile_read(int kernel_id, double *total_ms_host, int64_t *launches_host);
 
 const char *dlcx_strerror(int code);
 /* Text of the last HIP error seen by this thread's calls (empty if none). */

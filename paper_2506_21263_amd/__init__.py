@@ -45,7 +45,11 @@ SYMBOLS = {
     "dlcx_compress": (_int, [_dp, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
     "dlcx_compress_batched": (_int, [_dp, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
     "dlcx_average": (_int, [_dp, _int, _int, _vp, _vp, _vp, _vp, _vp]),
-    "dlcx_decompress": (_int, [_dp, _vp, _vp, _vp, _int, _vp, _vp]),
+    "dlcx_decompress": (_int, [_dp, _vp, _vp, _vp, _int, _vp, _vp, _vp]),
+    "dlcx_decompress_apply": (_int, [_dp, _vp, _vp, _int, _vp, _vp, _vp, C.c_float, C.c_float, _vp,
+                                     _vp]),
+    "dlcx_ef_delta_apply": (_int, [_dp, _vp, _vp, _int, _vp, _int, _vp, _vp, _vp, C.c_float,
+                                   C.c_float, _vp, _vp]),
     "dlcx_outer_nesterov": (_int, [_vp, _vp, _vp, _i64, C.c_float, C.c_float, _vp]),
     "dlcx_select_rank": (_int, [_dp, _vp, _int, C.c_double, _vp, _i32, _i32, _i32, _i32, _i32,
                                 _i32, _vp, _vp, _vp, _vp, _vp]),
@@ -57,6 +61,10 @@ SYMBOLS = {
     "dlcx_dequant_average": (_int, [_int, _vp, _vp, _i64, _int, _int, _vp, _vp]),
     "dlcx_orthonormalize": (_int, [_i64, _i32, _vp, _vp, _vp]),
     "dlcx_effective_rank": (_int, [_i64, _i32, _vp, C.c_double, _vp, _vp, _vp]),
+    "dlcx_profile_enable": (_int, [_int]),
+    "dlcx_profile_kernels": (_int, []),
+    "dlcx_profile_name": (C.c_char_p, [_int]),
+    "dlcx_profile_read": (_int, [_int, _vp, _vp]),
     "dlcx_strerror": (C.c_char_p, [_int]),
     "dlcx_last_hip_error": (C.c_char_p, []),
 }
@@ -144,10 +152,29 @@ def dlcx_average(d, phase, codes, scales, factor_out, workspace, stream=None):
                               _ptr(workspace), _stream(stream)), "dlcx_average")
 
 
-def dlcx_decompress(d, p_hat, q_bar, delta_hat_out, ef_inout=(), stream=None):
+def dlcx_decompress(d, p_hat, q_bar, delta_hat_out, ef_inout=(), workspace=None, stream=None):
     ep, keep = _ptr_array(list(ef_inout)) if len(ef_inout) else (None, None)
     _check(lib().dlcx_decompress(C.byref(d), _ptr(p_hat), _ptr(q_bar), _ptr(delta_hat_out),
-                                 len(ef_inout), ep, _stream(stream)), "dlcx_decompress")
+                                 len(ef_inout), ep, _ptr(workspace), _stream(stream)),
+           "dlcx_decompress")
+
+
+def dlcx_decompress_apply(d, p_hat, q_bar, ef_inout, theta_g, v, lr, mu, workspace=None,
+                          stream=None):
+    ep, keep = _ptr_array(list(ef_inout)) if len(ef_inout) else (None, None)
+    _check(lib().dlcx_decompress_apply(C.byref(d), _ptr(p_hat), _ptr(q_bar), len(ef_inout), ep,
+                                       _ptr(theta_g), _ptr(v), lr, mu, _ptr(workspace),
+                                       _stream(stream)), "dlcx_decompress_apply")
+
+
+def dlcx_ef_delta_apply(d, p_hat, q_bar, theta_l, ef_inout, theta_g, v, lr, mu, workspace=None,
+                        stream=None):
+    dt = BF16 if theta_l[0].dtype == torch.bfloat16 else F32
+    tp, k1 = _ptr_array(list(theta_l))
+    ep, k2 = _ptr_array(list(ef_inout))
+    _check(lib().dlcx_ef_delta_apply(C.byref(d), _ptr(p_hat), _ptr(q_bar), len(ef_inout), tp, dt,
+                                     ep, _ptr(theta_g), _ptr(v), lr, mu, _ptr(workspace),
+                                     _stream(stream)), "dlcx_ef_delta_apply")
 
 
 def dlcx_outer_nesterov(theta_g, v, delta_hat, lr, mu, numel=None, stream=None):
@@ -204,3 +231,18 @@ def dlcx_orthonormalize(L, r, p_inout, workspace, stream=None):
 def dlcx_effective_rank(L, r, q_bar, tau, rprime_out_dev, workspace, stream=None):
     _check(lib().dlcx_effective_rank(L, r, _ptr(q_bar), tau, _ptr(rprime_out_dev),
                                      _ptr(workspace), _stream(stream)), "dlcx_effective_rank")
+
+
+def dlcx_profile_enable(on):
+    _check(lib().dlcx_profile_enable(1 if on else 0), "dlcx_profile_enable")
+
+
+def dlcx_profile_read():
+    """{kernel name: (total ms, launches)} of the launches recorded since dlcx_profile_enable(1)."""
+    out = {}
+    for kid in range(lib().dlcx_profile_kernels()):
+        ms, cnt = C.c_double(0.0), C.c_int64(0)
+        _check(lib().dlcx_profile_read(kid, C.addressof(ms), C.addressof(cnt)), "dlcx_profile_read")
+        if cnt.value:
+            out[lib().dlcx_profile_name(kid).decode()] = (ms.value, cnt.value)
+    return out

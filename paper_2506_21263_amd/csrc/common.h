@@ -19,6 +19,20 @@ int note_hip(hipError_t e, const char *where);
 
 inline int check_launch(const char *where) { return note_hip(hipGetLastError(), where); }
 
+// Optional per-kernel timing (dlcx_profile_*): when enabled, a Timed object brackets one kernel
+// launch with two HIP events on the launch stream.  Off by default; costs nothing when off.
+enum KernelId {
+    KID_DELTA_EF = 0, KID_NESTEROV, KID_QUANTIZE, KID_DEQUANT_AVG, KID_PACK, KID_PROJECT_P,
+    KID_PROJECT_Q, KID_SUM_SLABS, KID_RECONSTRUCT, KID_GRAM, KID_CHOL, KID_APPLY_W, KID_JACOBI,
+    KID_COUNT
+};
+struct Timed {
+    Timed(int kid, hipStream_t st);
+    ~Timed();
+    int slot;
+    hipStream_t st;
+};
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -49,11 +63,26 @@ int launch_project_p(int mma, int64_t m, int64_t n, int r, int K,
 int launch_project_q(int mma, int64_t m, int64_t n, int r, int K,
                      const PtrPack<const float *> &delta, const float *p_hat,
                      const PtrPack<float *> &out, void *workspace, hipStream_t st);
-// delta_hat = P_hat Q_bar^T, optionally written, and e_k <- e_k - delta_hat for K workers
+// What happens to each tile d of delta_hat = P_hat Q_bar^T, in this order:
+//   out            : d is written
+//   K > 0          : e_k <- e_k - d                     (error buffers of Alg. 2)
+//   tl_on          : e_k <- (theta - theta_l,k) + e_k   (next pseudo-gradient, same buffer)
+//   apply          : vel <- mu vel + d ; theta <- theta - lr (d + mu vel)   (OuterOpt)
+struct ReconEpilogue {
+    float *out;
+    int K;
+    PtrPack<float *> ef;
+    PtrPack<const void *> tl;
+    int tl_on, tl_bf16;
+    float *theta, *vel;
+    int apply;
+    float lr, mu;
+};
 int launch_reconstruct(int mma, int64_t m, int64_t n, int r, const float *p_hat,
-                       const float *q_bar, float *delta_hat_out, int K,
-                       const PtrPack<float *> &ef, hipStream_t st);
+                       const float *q_bar, const ReconEpilogue &ep, void *workspace,
+                       hipStream_t st);
 size_t project_workspace_bytes(int mma, int64_t m, int64_t n, int r, int K);
+size_t reconstruct_workspace_bytes(int mma, int64_t m, int64_t n, int r);
 
 // ---- orthonormalisation and effective rank (k_orth.hip, k_rank.hip) ---------------------
 size_t orth_workspace_bytes(int64_t L, int r);

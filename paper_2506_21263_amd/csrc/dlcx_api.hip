@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include <string>
+#include <vector>
 
 #include "common.h"
 
@@ -16,22 +17,44 @@ int note_hip(hipError_t e, const char *where) {
     return DLCX_ELAUNCH;
 }
 
+// ---- optional per-kernel timing ---------------------------------------------------------
+struct ProfRec {
+    int kid;
+    hipEvent_t a, b;
+};
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof;
+
+Timed::Timed(int kid, hipStream_t s) : slot(-1), st(s) {
+    if (!g_prof_on) return;
+    ProfRec r;
+    r.kid = kid;
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    hipEventRecord(r.a, st);
+    g_prof.push_back(r);
+    slot = (int)g_prof.size() - 1;
+}
+Timed::~Timed() {
+    if (slot >= 0) hipEventRecord(g_prof[slot].b, st);
+}
+
 // k_gemm_fma.hip
 int launch_project_p_fma(int64_t, int64_t, int, int, const PtrPack<const float *> &, const float *,
                          const PtrPack<float *> &, hipStream_t);
 int launch_project_q_fma(int64_t, int64_t, int, int, const PtrPack<const float *> &, const float *,
                          const PtrPack<float *> &, void *, hipStream_t);
-int launch_reconstruct_fma(int64_t, int64_t, int, const float *, const float *, float *, int,
-                           const PtrPack<float *> &, hipStream_t);
+int launch_reconstruct_fma(int64_t, int64_t, int, const float *, const float *,
+                           const ReconEpilogue &, hipStream_t);
 size_t fma_project_workspace_bytes(int64_t, int64_t, int, int);
 // k_gemm_mfma.hip
 int launch_project_p_mfma(int, int64_t, int64_t, int, int, const PtrPack<const float *> &,
                           const float *, const PtrPack<float *> &, void *, hipStream_t);
 int launch_project_q_mfma(int, int64_t, int64_t, int, int, const PtrPack<const float *> &,
                           const float *, const PtrPack<float *> &, void *, hipStream_t);
-int launch_reconstruct_mfma(int, int64_t, int64_t, int, const float *, const float *, float *, int,
-                            const PtrPack<float *> &, hipStream_t);
+int launch_reconstruct_mfma(int, int64_t, int64_t, int, const float *, const float *,
+                            const ReconEpilogue &, void *, hipStream_t);
 size_t mfma_project_workspace_bytes(int, int64_t, int64_t, int, int);
+size_t mfma_reconstruct_workspace_bytes(int, int64_t, int64_t, int);
 
 static bool group_ok(int g) { return g == 16 || g == 32 || g == 64 || g == 128 || g == 256; }
 
@@ -72,12 +95,16 @@ int launch_project_q(int mma, int64_t m, int64_t n, int r, int K,
     return launch_project_q_mfma(mma, m, n, r, K, delta, p_hat, out, workspace, st);
 }
 
+size_t reconstruct_workspace_bytes(int mma, int64_t m, int64_t n, int r) {
+    if (mma == DLCX_MMA_FMA) return 0;
+    return mfma_reconstruct_workspace_bytes(mma, m, n, r);
+}
+
 int launch_reconstruct(int mma, int64_t m, int64_t n, int r, const float *p_hat,
-                       const float *q_bar, float *delta_hat_out, int K,
-                       const PtrPack<float *> &ef, hipStream_t st) {
-    if (mma == DLCX_MMA_FMA)
-        return launch_reconstruct_fma(m, n, r, p_hat, q_bar, delta_hat_out, K, ef, st);
-    return launch_reconstruct_mfma(mma, m, n, r, p_hat, q_bar, delta_hat_out, K, ef, st);
+                       const float *q_bar, const ReconEpilogue &ep, void *workspace,
+                       hipStream_t st) {
+    if (mma == DLCX_MMA_FMA) return launch_reconstruct_fma(m, n, r, p_hat, q_bar, ep, st);
+    return launch_reconstruct_mfma(mma, m, n, r, p_hat, q_bar, ep, workspace, st);
 }
 
 }  // namespace dlcx
@@ -98,6 +125,47 @@ const char *dlcx_strerror(int code) {
 
 const char *dlcx_last_hip_error(void) { return g_last_error.c_str(); }
 
+static const char *const kKernelNames[KID_COUNT] = {
+    "delta_ef", "outer_nesterov", "quantize", "dequant_average", "pack_fragments", "project_p",
+    "project_q", "sum_slabs", "reconstruct", "gram_partials", "chol_inverse", "apply_w",
+    "jacobi_rank"};
+
+int dlcx_profile_enable(int on) {
+    for (auto &r : g_prof) {
+        hipEventDestroy(r.a);
+        hipEventDestroy(r.b);
+    }
+    g_prof.clear();
+    g_prof_on = on != 0;
+    return DLCX_OK;
+}
+
+int dlcx_profile_kernels(void) { return KID_COUNT; }
+
+const char *dlcx_profile_name(int kernel_id) {
+    return kernel_id >= 0 && kernel_id < KID_COUNT ? kKernelNames[kernel_id] : "";
+}
+
+int dlcx_profile_read(int kernel_id, double *total_ms_host, int64_t *launches_host) {
+    if (kernel_id < 0 || kernel_id >= KID_COUNT || !total_ms_host || !launches_host)
+        return DLCX_EINVAL;
+    double total = 0.0;
+    int64_t count = 0;
+    for (auto &r : g_prof) {
+        if (r.kid != kernel_id) continue;
+        int rc = note_hip(hipEventSynchronize(r.b), "profile sync");
+        if (rc != DLCX_OK) return rc;
+        float ms = 0.f;
+        rc = note_hip(hipEventElapsedTime(&ms, r.a, r.b), "profile elapsed");
+        if (rc != DLCX_OK) return rc;
+        total += ms;
+        ++count;
+    }
+    *total_ms_host = total;
+    *launches_host = count;
+    return DLCX_OK;
+}
+
 size_t dlcx_payload_bytes(const dlcx_desc *desc, int phase, size_t *codes_bytes,
                           size_t *scales_bytes) {
     if (check_desc(desc) != DLCX_OK || (phase != DLCX_PHASE_P && phase != DLCX_PHASE_Q)) return 0;
@@ -116,8 +184,10 @@ size_t dlcx_workspace_bytes(const dlcx_desc *desc, int K) {
                         project_workspace_bytes(desc->mma, desc->m, desc->n, desc->r, K);
     const size_t orth = orth_workspace_bytes(lmax, desc->r);
     const size_t rank = effrank_workspace_bytes(lmax, desc->r);
+    const size_t rec = reconstruct_workspace_bytes(desc->mma, desc->m, desc->n, desc->r);
     size_t w = proj > orth ? proj : orth;
     if (rank > w) w = rank;
+    if (rec > w) w = rec;
     return align256(w);
 }
 
@@ -269,21 +339,70 @@ int dlcx_average(const dlcx_desc *desc, int phase, int K, const uint8_t *const *
     return dlcx_orthonormalize(L, desc->r, factor_out, workspace, stream);
 }
 
-int dlcx_decompress(const dlcx_desc *desc, const float *p_hat, const float *q_bar,
-                    float *delta_hat_out, int K, float *const *ef_inout_host, void *stream) {
+static int decompress_common(const dlcx_desc *desc, const float *p_hat, const float *q_bar,
+                             float *delta_hat_out, int K, float *const *ef_inout_host,
+                             const void *const *theta_l_host, int theta_l_dtype, float *theta,
+                             float *vel, int apply, float lr, float mu, void *workspace,
+                             void *stream) {
     int rc = check_desc(desc);
     if (rc != DLCX_OK) return rc;
     if (K < 0 || K > DLCX_MAX_WORKERS || !p_hat || !q_bar) return DLCX_EINVAL;
     if (K > 0 && !ef_inout_host) return DLCX_EINVAL;
-    if (!aligned16(p_hat) || !aligned16(q_bar) || !aligned16(delta_hat_out)) return DLCX_EINVAL;
-    if (K == 0 && !delta_hat_out) return DLCX_OK;
-    PtrPack<float *> ef;
+    if (!aligned16(p_hat) || !aligned16(q_bar) || !aligned16(delta_hat_out) ||
+        !aligned16(workspace))
+        return DLCX_EINVAL;
+    if (reconstruct_workspace_bytes(desc->mma, desc->m, desc->n, desc->r) > 0 && !workspace)
+        return DLCX_EINVAL;
+    ReconEpilogue ep;
+    memset(&ep, 0, sizeof ep);
+    ep.out = delta_hat_out;
+    ep.K = K;
+    ep.theta = theta;
+    ep.vel = vel;
+    ep.apply = apply;
+    ep.lr = lr;
+    ep.mu = mu;
+    if (theta_l_host) {
+        if (theta_l_dtype != DLCX_F32 && theta_l_dtype != DLCX_BF16) return DLCX_EINVAL;
+        ep.tl_on = 1;
+        ep.tl_bf16 = theta_l_dtype == DLCX_BF16;
+    }
+    if ((ep.tl_on || apply) && (!theta || !aligned16(theta))) return DLCX_EINVAL;
+    if (apply && (!vel || !aligned16(vel) || !(lr == lr) || !(mu == mu))) return DLCX_EINVAL;
+    if (K == 0 && !delta_hat_out && !apply) return DLCX_OK;
     for (int k = 0; k < K; ++k) {
         if (!ef_inout_host[k] || !aligned16(ef_inout_host[k])) return DLCX_EINVAL;
-        ef.p[k] = ef_inout_host[k];
+        ep.ef.p[k] = ef_inout_host[k];
+        if (ep.tl_on) {
+            if (!theta_l_host[k] || !aligned16(theta_l_host[k])) return DLCX_EINVAL;
+            ep.tl.p[k] = theta_l_host[k];
+        }
     }
-    return launch_reconstruct(desc->mma, desc->m, desc->n, desc->r, p_hat, q_bar, delta_hat_out, K,
-                              ef, as_stream(stream));
+    return launch_reconstruct(desc->mma, desc->m, desc->n, desc->r, p_hat, q_bar, ep, workspace,
+                              as_stream(stream));
+}
+
+int dlcx_decompress(const dlcx_desc *desc, const float *p_hat, const float *q_bar,
+                    float *delta_hat_out, int K, float *const *ef_inout_host, void *workspace,
+                    void *stream) {
+    return decompress_common(desc, p_hat, q_bar, delta_hat_out, K, ef_inout_host, nullptr, 0,
+                             nullptr, nullptr, 0, 0.f, 0.f, workspace, stream);
+}
+
+int dlcx_decompress_apply(const dlcx_desc *desc, const float *p_hat, const float *q_bar, int K,
+                          float *const *ef_inout_host, float *theta_g, float *v, float lr,
+                          float mu, void *workspace, void *stream) {
+    return decompress_common(desc, p_hat, q_bar, nullptr, K, ef_inout_host, nullptr, 0, theta_g, v,
+                             1, lr, mu, workspace, stream);
+}
+
+int dlcx_ef_delta_apply(const dlcx_desc *desc, const float *p_hat, const float *q_bar, int K,
+                        const void *const *theta_l_host, int theta_l_dtype,
+                        float *const *ef_inout_host, float *theta_g, float *v, float lr, float mu,
+                        void *workspace, void *stream) {
+    if (K < 1 || !theta_l_host) return DLCX_EINVAL;
+    return decompress_common(desc, p_hat, q_bar, nullptr, K, ef_inout_host, theta_l_host,
+                             theta_l_dtype, theta_g, v, 1, lr, mu, workspace, stream);
 }
 
 int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,

@@ -2,6 +2,8 @@
 // fp64 accumulation.  This is the accuracy mode: it is not meant to reach the roofline, it is the
 // GPU path whose rounding is closest to the exact products, and it accepts every shape the
 // interface allows.  The MFMA modes live in k_gemm_mfma.hip.
+#include <type_traits>
+
 #include "common.h"
 
 namespace dlcx {
@@ -149,6 +151,7 @@ __global__ __launch_bounds__(kT) void sum_slabs_kernel(PtrPack<const float *> sl
 int launch_sum_slabs(int K, const PtrPack<const float *> &slabs, const PtrPack<float *> &outs,
                      int64_t count, int S, int64_t slab_stride, hipStream_t st) {
     const int64_t nvec = count >> 2;
+    Timed timed(KID_SUM_SLABS, st);
     hipLaunchKernelGGL(sum_slabs_kernel, dim3((unsigned)ceil_div(nvec, kT), (unsigned)K), dim3(kT),
                        0, st, slabs, outs, nvec, S, slab_stride);
     return check_launch("sum_slabs");
@@ -156,12 +159,12 @@ int launch_sum_slabs(int K, const PtrPack<const float *> &slabs, const PtrPack<f
 
 // ---------------------------------------------------------------------------------------------
 // delta_hat = P_hat Q_bar^T on 64 x 64 tiles, 4 x 4 outputs per thread; the epilogue writes the
-// tile (optional) and subtracts it from the K error buffers:  e_k <- delta_k - delta_hat.
+// tile (optional), subtracts it from the K error buffers (e_k <- delta_k - delta_hat) and, when
+// theta is given, applies the Nesterov outer update with the tile as the gradient.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kT) void reconstruct_fma_kernel(const float *__restrict__ p_hat,
                                                              const float *__restrict__ q_bar,
-                                                             float *__restrict__ out, int K,
-                                                             PtrPack<float *> efs, int64_t m,
+                                                             ReconEpilogue ep, int64_t m,
                                                              int64_t n, int r) {
     __shared__ float pt[kTk][64];
     __shared__ float qt[kTk][64];
@@ -208,11 +211,38 @@ __global__ __launch_bounds__(kT) void reconstruct_fma_kernel(const float *__rest
         if (i >= m) break;
         const float4 d = make_float4((float)acc[x][0], (float)acc[x][1], (float)acc[x][2],
                                      (float)acc[x][3]);
-        if (out) *reinterpret_cast<float4 *>(out + i * n + j) = d;
-        for (int k = 0; k < K; ++k) {
-            float4 e = *reinterpret_cast<float4 *>(efs.p[k] + i * n + j);
+        if (ep.out) *reinterpret_cast<float4 *>(ep.out + i * n + j) = d;
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ep.tl_on || ep.apply) t = *reinterpret_cast<const float4 *>(ep.theta + i * n + j);
+        for (int k = 0; k < ep.K; ++k) {
+            float4 e = *reinterpret_cast<float4 *>(ep.ef.p[k] + i * n + j);
             e.x -= d.x; e.y -= d.y; e.z -= d.z; e.w -= d.w;
-            *reinterpret_cast<float4 *>(efs.p[k] + i * n + j) = e;
+            if (ep.tl_on) {
+                float4 l;
+                if (ep.tl_bf16) {
+                    const uint2 b = *reinterpret_cast<const uint2 *>(
+                        reinterpret_cast<const uint16_t *>(ep.tl.p[k]) + i * n + j);
+                    l = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
+                                    __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u));
+                } else {
+                    l = *reinterpret_cast<const float4 *>(
+                        reinterpret_cast<const float *>(ep.tl.p[k]) + i * n + j);
+                }
+                e.x = (t.x - l.x) + e.x; e.y = (t.y - l.y) + e.y;
+                e.z = (t.z - l.z) + e.z; e.w = (t.w - l.w) + e.w;
+            }
+            *reinterpret_cast<float4 *>(ep.ef.p[k] + i * n + j) = e;
+        }
+        if (ep.apply) {
+            float4 v = *reinterpret_cast<float4 *>(ep.vel + i * n + j);
+            v.x = fmaf(ep.mu, v.x, d.x); v.y = fmaf(ep.mu, v.y, d.y);
+            v.z = fmaf(ep.mu, v.z, d.z); v.w = fmaf(ep.mu, v.w, d.w);
+            t.x = fmaf(-ep.lr, fmaf(ep.mu, v.x, d.x), t.x);
+            t.y = fmaf(-ep.lr, fmaf(ep.mu, v.y, d.y), t.y);
+            t.z = fmaf(-ep.lr, fmaf(ep.mu, v.z, d.z), t.z);
+            t.w = fmaf(-ep.lr, fmaf(ep.mu, v.w, d.w), t.w);
+            *reinterpret_cast<float4 *>(ep.vel + i * n + j) = v;
+            *reinterpret_cast<float4 *>(ep.theta + i * n + j) = t;
         }
     }
 }
@@ -245,6 +275,7 @@ int launch_project_p_fma(int64_t m, int64_t n, int r, int K, const PtrPack<const
                          const float *q_in, const PtrPack<float *> &out, hipStream_t st) {
     const dim3 grid((unsigned)ceil_div(m, kRows), (unsigned)K);
     const size_t lds = (size_t)(kRows + r) * (kTk + 1) * sizeof(float);
+    Timed timed(KID_PROJECT_P, st);
     return by_rank(r, [&](auto acc) {
         hipLaunchKernelGGL((project_p_fma_kernel<decltype(acc)::value>), grid, dim3(kT), lds, st,
                            delta, q_in, out, m, n, r);
@@ -264,11 +295,15 @@ int launch_project_q_fma(int64_t m, int64_t n, int r, int K, const PtrPack<const
         for (int k = 0; k < K; ++k) dst.p[k] = reinterpret_cast<float *>(workspace) + (int64_t)k * S * slab;
     const dim3 grid((unsigned)ceil_div(n, kRows), (unsigned)K, (unsigned)S);
     const size_t lds = (size_t)(kTk * kRows + r * (kTk + 1)) * sizeof(float);
-    int rc = by_rank(r, [&](auto acc) {
+    int rc;
+    {
+        Timed timed(KID_PROJECT_Q, st);
+        rc = by_rank(r, [&](auto acc) {
         hipLaunchKernelGGL((project_q_fma_kernel<decltype(acc)::value>), grid, dim3(kT), lds, st,
                            delta, p_hat, dst, m, n, r, rows, slab);
         return check_launch("project_q_fma");
-    });
+        });
+    }
     if (rc != DLCX_OK || S == 1) return rc;
     PtrPack<const float *> src;
     for (int k = 0; k < K; ++k) src.p[k] = dst.p[k];
@@ -276,10 +311,10 @@ int launch_project_q_fma(int64_t m, int64_t n, int r, int K, const PtrPack<const
 }
 
 int launch_reconstruct_fma(int64_t m, int64_t n, int r, const float *p_hat, const float *q_bar,
-                           float *out, int K, const PtrPack<float *> &ef, hipStream_t st) {
+                           const ReconEpilogue &ep, hipStream_t st) {
     const dim3 grid((unsigned)ceil_div(n, 64), (unsigned)ceil_div(m, 64));
-    hipLaunchKernelGGL(reconstruct_fma_kernel, grid, dim3(kT), 0, st, p_hat, q_bar, out, K, ef, m,
-                       n, r);
+    Timed timed(KID_RECONSTRUCT, st);
+    hipLaunchKernelGGL(reconstruct_fma_kernel, grid, dim3(kT), 0, st, p_hat, q_bar, ep, m, n, r);
     return check_launch("reconstruct_fma");
 }
 

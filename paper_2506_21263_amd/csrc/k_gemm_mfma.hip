@@ -1,11 +1,645 @@
-// placeholder until the MFMA kernels land
+// Rank-r products of the low-rank compressor on the bf16 matrix cores of gfx950
+// (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
+//
+// Every fp32 operand is split into NS bf16 pieces, x = x0 + x1 (+ x2), each piece the bf16
+// rounding of what the earlier pieces left over, and a product a*b is the sum of the piece
+// products whose weight is not below the last piece:
+//     NS = 2 (DLCX_MMA_BF16):  a0b0 + a0b1 + a1b0               error ~ 2^-17 per product
+//     NS = 3 (DLCX_MMA_F32):   + a1b1 + a0b2 + a2b0             error ~ 2^-24 per product
+// so the matrix cores run 3 or 6 bf16 instructions per 32x32x16 block.  At the ranks of interest
+// the products are bound by the HBM stream of delta (4 bytes per element against 6r or 12r
+// flops), not by the matrix cores, which is why the extra instructions are affordable; the native
+// fp32 MFMA would cost 16 instruction issues of twice the latency for the same block.
+//
+// Operand layout of v_mfma_f32_32x32x16_bf16 (D = A B + C, A is 32 x 16, B is 16 x 32):
+//   lane l holds A[l % 32][8 (l / 32) + e] and B[8 (l / 32) + e][l % 32], e = 0..7 (16 bytes);
+//   D[i][j] is in lane j + 32 ((i / 4) % 2), register (i % 4) + 4 (i / 8).
+// The small operand of every product (the basis, or both factors of the reconstruction) is first
+// repacked ("fragments") so that a wavefront fetches one 32 x 16 operand block of one piece as
+// 1 KB of consecutive memory; fragments are read straight from L2 into registers.  The big
+// operand delta is staged through LDS (P phase, reduction along a row) or loaded straight into
+// the operand layout with 128-byte row segments (Q phase, reduction down a column).
 #include "common.h"
+
 namespace dlcx {
-int launch_project_p_mfma(int, int64_t, int64_t, int, int, const PtrPack<const float *> &,
-                          const float *, const PtrPack<float *> &, void *, hipStream_t) { return DLCX_EUNSUPPORTED; }
-int launch_project_q_mfma(int, int64_t, int64_t, int, int, const PtrPack<const float *> &,
-                          const float *, const PtrPack<float *> &, void *, hipStream_t) { return DLCX_EUNSUPPORTED; }
-int launch_reconstruct_mfma(int, int64_t, int64_t, int, const float *, const float *, float *, int,
-                            const PtrPack<float *> &, hipStream_t) { return DLCX_EUNSUPPORTED; }
-size_t mfma_project_workspace_bytes(int, int64_t, int64_t, int, int) { return 0; }
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kW = 256;  // threads per workgroup (4 wavefronts)
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {  // round-to-nearest-even
+    const f32x2_t f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
 }
+
+// pieces of the pair (a, b): out[h] holds piece h of a in its low half, of b in its high half
+template <int NS>
+__device__ __forceinline__ void split2(float a, float b, uint32_t (&out)[NS]) {
+#pragma unroll
+    for (int h = 0; h < NS; ++h) {
+        const uint32_t p = pack_bf16x2(a, b);
+        out[h] = p;
+        if (h + 1 < NS) {
+            a -= __uint_as_float(p << 16);
+            b -= __uint_as_float(p & 0xFFFF0000u);
+        }
+    }
+}
+
+// 8 consecutive-k values -> NS operand registers (uint4 = 8 bf16)
+template <int NS>
+__device__ __forceinline__ void split8(const float (&x)[8], uint4 (&out)[NS]) {
+    uint32_t p[4][NS];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) split2<NS>(x[2 * q], x[2 * q + 1], p[q]);
+#pragma unroll
+    for (int h = 0; h < NS; ++h) out[h] = make_uint4(p[0][h], p[1][h], p[2][h], p[3][h]);
+}
+
+__device__ __forceinline__ f32x16_t mfma(const uint4 &a, const uint4 &b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+template <int NS>
+__device__ __forceinline__ void mfma_split(const uint4 (&a)[NS], const uint4 (&b)[NS],
+                                           f32x16_t &c) {
+    if (NS == 3) {  // smallest terms first
+        c = mfma(a[2], b[0], c);
+        c = mfma(a[0], b[2], c);
+        c = mfma(a[1], b[1], c);
+    }
+    if (NS >= 2) {
+        c = mfma(a[1], b[0], c);
+        c = mfma(a[0], b[1], c);
+    }
+    c = mfma(a[0], b[0], c);
+}
+
+// row of D held in register v of lane `lane`
+__device__ __forceinline__ int d_row(int v, int lane) {
+    return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fragment packing.
+// ---------------------------------------------------------------------------------------------
+// src is nrows x L with the reduction index contiguous (a basis: Q_in is r x n, P_hat is r x m).
+// Fragment (s, rb, h): rows rb*32 .. +32, reduction indices s*16 .. +16, piece h, at
+// frags[((s * RB + rb) * NS + h) * 64 + lane].  Rows >= nrows and indices >= L are zero.
+template <int NS>
+__global__ __launch_bounds__(kW) void pack_kcontig_kernel(const float *__restrict__ src,
+                                                          int nrows, int64_t L, int RB,
+                                                          int64_t KS, uint4 *__restrict__ frags) {
+    const int64_t f = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (f >= KS * RB) return;
+    const int64_t s = f / RB;
+    const int rb = (int)(f % RB);
+    const int row = rb * 32 + (lane & 31);
+    const int64_t k0 = s * 16 + (lane >> 5) * 8;
+    float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (row < nrows && k0 < L) {  // L is a multiple of 8
+        const float4 a = *reinterpret_cast<const float4 *>(src + (int64_t)row * L + k0);
+        const float4 b = *reinterpret_cast<const float4 *>(src + (int64_t)row * L + k0 + 4);
+        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+        x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    }
+    uint4 out[NS];
+    split8<NS>(x, out);
+#pragma unroll
+    for (int h = 0; h < NS; ++h) frags[(f * NS + h) * 64 + lane] = out[h];
+}
+
+// src is r x L with the reduction index c strided (a factor used in the reconstruction).
+// Fragment (xb, s, h): positions xb*32 .. +32 along L, reduction indices s*16 .. +16, at
+// frags[((xb * KS + s) * NS + h) * 64 + lane].
+template <int NS>
+__global__ __launch_bounds__(kW) void pack_kstrided_kernel(const float *__restrict__ src, int r,
+                                                           int64_t L, int KS, int64_t XB,
+                                                           uint4 *__restrict__ frags) {
+    const int64_t f = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (f >= XB * KS) return;
+    const int64_t xb = f / KS;
+    const int s = (int)(f % KS);
+    const int64_t x0 = xb * 32 + (lane & 31);
+    const int c0 = s * 16 + (lane >> 5) * 8;
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        x[e] = (x0 < L && c0 + e < r) ? src[(int64_t)(c0 + e) * L + x0] : 0.f;
+    uint4 out[NS];
+    split8<NS>(x, out);
+#pragma unroll
+    for (int h = 0; h < NS; ++h) frags[(f * NS + h) * 64 + lane] = out[h];
+}
+
+// ---------------------------------------------------------------------------------------------
+// P phase:  P_k[i][c] = sum_j delta_k[i][j] Q_in[c][j].
+// Workgroup: 64 rows of delta (2 row blocks), swept along j in stages of 64 (4 k-steps).
+// The 4 wavefronts split the work as WC (groups of CBW basis blocks) x WK (halves of a stage) x
+// WR (row blocks).  A = basis fragments (M = c), B = delta from LDS (N = i): D[c][i].
+// ---------------------------------------------------------------------------------------------
+constexpr int kPPitch = 64 * 2 + 16;  // bytes per LDS row of one piece: 64 bf16 + pad
+
+template <int NS, int CBW, int WC, int WK, int WR>
+__global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float *> deltas,
+                                                            const uint4 *__restrict__ afrags,
+                                                            PtrPack<float *> outs, int64_t m,
+                                                            int64_t n, int r) {
+    constexpr int CB = CBW * WC;
+    constexpr int RBW = 2 / WR;
+    constexpr int KSW = 4 / WK;
+    static_assert(WC * WK * WR == 4, "four wavefronts");
+    constexpr int kBuf = NS * 64 * kPPitch;
+    constexpr int kRed = (WK == 2) ? 2 * CBW * RBW * 16 * 64 * 4 : 0;
+    constexpr int kLds = (2 * kBuf > kRed) ? 2 * kBuf : kRed;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
+
+    const float *__restrict__ delta = deltas.p[blockIdx.y];
+    float *__restrict__ out = outs.p[blockIdx.y];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wc = wave % WC, wk = (wave / WC) % WK, wr = wave / (WC * WK);
+    const int64_t i0 = (int64_t)blockIdx.x * 64;
+    const int64_t nstages = (n + 63) / 64;
+
+    f32x16_t acc[CBW][RBW];
+#pragma unroll
+    for (int a = 0; a < CBW; ++a)
+#pragma unroll
+        for (int b = 0; b < RBW; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    // this thread's four float4 of a stage: (row, 4 columns)
+    float4 pre[4];
+    auto load_stage = [&](int64_t t) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = tid + kW * u;
+            const int row = idx >> 4, c4 = idx & 15;
+            const int64_t j = t * 64 + c4 * 4;
+            pre[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i0 + row < m && j < n)
+                pre[u] = *reinterpret_cast<const float4 *>(delta + (i0 + row) * n + j);
+        }
+    };
+    load_stage(0);
+    for (int64_t t = 0; t < nstages; ++t) {
+        unsigned char *buf = lds + (t & 1) * kBuf;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = tid + kW * u;
+            const int row = idx >> 4, c4 = idx & 15;
+            uint32_t lo[NS], hi[NS];
+            split2<NS>(pre[u].x, pre[u].y, lo);
+            split2<NS>(pre[u].z, pre[u].w, hi);
+#pragma unroll
+            for (int h = 0; h < NS; ++h)
+                *reinterpret_cast<uint2 *>(buf + (h * 64 + row) * kPPitch + c4 * 8) =
+                    make_uint2(lo[h], hi[h]);
+        }
+        if (t + 1 < nstages) load_stage(t + 1);
+        uint4 a[KSW][CBW][NS];
+#pragma unroll
+        for (int ks = 0; ks < KSW; ++ks)
+#pragma unroll
+            for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                for (int h = 0; h < NS; ++h) {
+                    const int64_t sg = t * 4 + wk * KSW + ks;
+                    a[ks][cb][h] = afrags[((sg * CB + wc * CBW + cb) * NS + h) * 64 + lane];
+                }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < KSW; ++ks) {
+            const int s = wk * KSW + ks;
+            uint4 b[RBW][NS];
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+                for (int h = 0; h < NS; ++h) {
+                    const int row = (wr * RBW + rb) * 32 + (lane & 31);
+                    b[rb][h] = *reinterpret_cast<const uint4 *>(
+                        buf + (h * 64 + row) * kPPitch + s * 32 + (lane >> 5) * 16);
+                }
+#pragma unroll
+            for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb) mfma_split<NS>(a[ks][cb], b[rb], acc[cb][rb]);
+        }
+    }
+    if (WK == 2) {  // add the two halves of the reduction: wk = 1 hands over through LDS
+        __syncthreads();
+        float *red = reinterpret_cast<float *>(lds);
+        const int slot = wr * WC + wc;  // WK == 2 => WC * WR == 2
+        if (wk == 1) {
+#pragma unroll
+            for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        red[((slot * CBW * RBW + cb * RBW + rb) * 16 + v) * 64 + lane] = acc[cb][rb][v];
+        }
+        __syncthreads();
+        if (wk == 1) return;
+#pragma unroll
+        for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    acc[cb][rb][v] += red[((slot * CBW * RBW + cb * RBW + rb) * 16 + v) * 64 + lane];
+    }
+#pragma unroll
+    for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
+            const int64_t i = i0 + (wr * RBW + rb) * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int c = (wc * CBW + cb) * 32 + d_row(v, lane);
+                if (c < r && i < m) out[(int64_t)c * m + i] = acc[cb][rb][v];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Q phase:  Q_k[j][c] = sum_i delta_k[i][j] P_hat[c][i].
+// Wavefront: JB column blocks of 32 x all CB basis blocks over its own range of rows; the B
+// operand (N = j, reduction down the column) is loaded straight into the operand layout: lane
+// (j, half) reads delta[i0 + 8 half + e][j], e = 0..7, i.e. 128-byte row segments.  The 4
+// wavefronts of a workgroup take consecutive quarters of the workgroup's rows and are added in
+// wavefront order at the end; blockIdx.z splits the rows further into slabs.
+// ---------------------------------------------------------------------------------------------
+constexpr int kQDepth = 4;  // k-steps of delta in flight per wavefront
+
+template <int NS, int CB, int JB>
+__global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float *> deltas,
+                                                            const uint4 *__restrict__ afrags,
+                                                            PtrPack<float *> outs, int64_t m,
+                                                            int64_t n, int r,
+                                                            int64_t ksteps_per_wave,
+                                                            int64_t slab_stride) {
+    __shared__ float red[CB * JB * 16 * 64];
+    const float *__restrict__ delta = deltas.p[blockIdx.y];
+    float *__restrict__ out = outs.p[blockIdx.y] + (int64_t)blockIdx.z * slab_stride;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t j0 = (int64_t)blockIdx.x * (32 * JB);
+    const int64_t s_begin = ((int64_t)blockIdx.z * 4 + wave) * ksteps_per_wave;
+    const int64_t s_end = s_begin + ksteps_per_wave;  // multiple of kQDepth k-steps
+
+    f32x16_t acc[CB][JB];
+#pragma unroll
+    for (int a = 0; a < CB; ++a)
+#pragma unroll
+        for (int b = 0; b < JB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    float breg[kQDepth][JB][8];
+    auto load_kstep = [&](int d, int64_t s) {
+        const int64_t ibase = s * 16 + (lane >> 5) * 8;
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) {
+            const int64_t j = j0 + jb * 32 + (lane & 31);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                breg[d][jb][e] = 0.f;
+                if (ibase + e < m && j < n) breg[d][jb][e] = delta[(ibase + e) * n + j];
+            }
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < kQDepth; ++d) load_kstep(d, s_begin + d);
+    for (int64_t s = s_begin; s < s_end; s += kQDepth) {
+#pragma unroll
+        for (int d = 0; d < kQDepth; ++d) {
+            uint4 a[CB][NS];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int h = 0; h < NS; ++h)
+                    a[cb][h] = afrags[(((s + d) * CB + cb) * NS + h) * 64 + lane];
+            uint4 b[JB][NS];
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) split8<NS>(breg[d][jb], b[jb]);
+            if (s + d + kQDepth < s_end) load_kstep(d, s + d + kQDepth);
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) mfma_split<NS>(a[cb], b[jb], acc[cb][jb]);
+        }
+    }
+    // wavefronts 3, 2, 1 hand their sums to wavefront 0, in that order
+    for (int w = 3; w >= 1; --w) {
+        if (wave == w) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        red[((cb * JB + jb) * 16 + v) * 64 + lane] = acc[cb][jb][v];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[cb][jb][v] += red[((cb * JB + jb) * 16 + v) * 64 + lane];
+        }
+        __syncthreads();
+    }
+    if (wave != 0) return;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) {
+            const int64_t j = j0 + jb * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int c = cb * 32 + d_row(v, lane);
+                if (c < r && j < n) out[(int64_t)c * n + j] = acc[cb][jb][v];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Reconstruction  delta_hat[i][j] = sum_c P_hat[c][i] Q_bar[c][j]  with fused consumers.
+// Workgroup: 32 rows x (4 wavefronts x 32 columns), swept along j.  A = P_hat fragments (M = i),
+// B = Q_bar fragments (N = j): D[i][j], lane = column, so every load and store of a matrix
+// element below is a 128-byte row segment per half-wavefront.
+//   out != NULL      : delta_hat is written
+//   K > 0            : e_k <- e_k - delta_hat                       (error buffers of Alg. 2)
+//   theta != NULL    : v <- mu v + delta_hat; theta <- theta - lr (delta_hat + mu v)   (OuterOpt)
+// ---------------------------------------------------------------------------------------------
+template <int NS>
+__global__ __launch_bounds__(kW) void reconstruct_mfma_kernel(
+    const uint4 *__restrict__ pfrags, const uint4 *__restrict__ qfrags, ReconEpilogue ep,
+    int64_t m, int64_t n, int64_t cols_per_wg, int KS) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t ib = blockIdx.y;
+    const int64_t jbegin = (int64_t)blockIdx.x * cols_per_wg;
+    int64_t jend = jbegin + cols_per_wg;
+    if (jend > n) jend = n;
+
+    for (int64_t jt = jbegin + wave * 32; jt < jend; jt += 128) {
+        const int64_t jb = jt >> 5;
+        f32x16_t d;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) d[v] = 0.f;
+#pragma unroll 2
+        for (int s = 0; s < KS; ++s) {
+            uint4 a[NS], b[NS];
+#pragma unroll
+            for (int h = 0; h < NS; ++h) {
+                a[h] = pfrags[((ib * KS + s) * NS + h) * 64 + lane];
+                b[h] = qfrags[((jb * KS + s) * NS + h) * 64 + lane];
+            }
+            mfma_split<NS>(a, b, d);
+        }
+        const int64_t j = jt + (lane & 31);
+        if (j >= n) continue;
+        int64_t off[16];
+        bool ok[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t i = ib * 32 + d_row(v, lane);
+            ok[v] = i < m;
+            off[v] = i * n + j;
+        }
+        if (ep.out) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (ok[v]) ep.out[off[v]] = d[v];
+        }
+        float tv[16];
+        if (ep.tl_on || ep.apply) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) tv[v] = ok[v] ? ep.theta[off[v]] : 0.f;
+        }
+        for (int k = 0; k < ep.K; ++k) {
+            float *__restrict__ e = ep.ef.p[k];
+            float x[16], l[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) x[v] = ok[v] ? e[off[v]] : 0.f;
+            if (ep.tl_on) {
+                if (ep.tl_bf16) {
+                    const uint16_t *__restrict__ t16 = reinterpret_cast<const uint16_t *>(ep.tl.p[k]);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        l[v] = ok[v] ? __uint_as_float((uint32_t)t16[off[v]] << 16) : 0.f;
+                } else {
+                    const float *__restrict__ t32 = reinterpret_cast<const float *>(ep.tl.p[k]);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) l[v] = ok[v] ? t32[off[v]] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (ok[v]) {
+                    float r = x[v] - d[v];
+                    if (ep.tl_on) r = (tv[v] - l[v]) + r;
+                    e[off[v]] = r;
+                }
+        }
+        if (ep.apply) {
+            float vv[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) vv[v] = ok[v] ? ep.vel[off[v]] : 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (ok[v]) {
+                    const float vn = fmaf(ep.mu, vv[v], d[v]);
+                    ep.vel[off[v]] = vn;
+                    ep.theta[off[v]] = fmaf(-ep.lr, fmaf(ep.mu, vn, d[v]), tv[v]);
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+static inline int ns_of(int mma) { return mma == DLCX_MMA_F32 ? 3 : 2; }
+static inline int cb_of(int r) { return r <= 32 ? 1 : r <= 64 ? 2 : r <= 128 ? 4 : 8; }
+static inline size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct QPlan {
+    int JB, S;
+    int64_t ksteps_per_wave, KS;
+};
+
+static QPlan q_plan(int64_t m, int64_t n, int r, int K) {
+    QPlan p;
+    const int cb = cb_of(r);
+    p.JB = cb <= 2 ? 2 : 1;
+    const int64_t col_wgs = ceil_div(n, 32 * p.JB) * K;
+    int64_t S = ceil_div(1024, col_wgs);
+    const int64_t smax = ceil_div(m, 64 * kQDepth * 2);  // at least 2 pipeline rounds per wave
+    if (S > smax) S = smax;
+    if (S < 1) S = 1;
+    if (S > 64) S = 64;
+    p.S = (int)S;
+    int64_t kpw = ceil_div(ceil_div(m, 16), (int64_t)p.S * 4);
+    p.ksteps_per_wave = ceil_div(kpw, kQDepth) * kQDepth;
+    p.KS = p.ksteps_per_wave * 4 * p.S;
+    return p;
+}
+
+size_t mfma_project_workspace_bytes(int mma, int64_t m, int64_t n, int r, int K) {
+    const int ns = ns_of(mma), cb = cb_of(r);
+    const size_t p_frags = (size_t)ceil_div(n, 64) * 4 * cb * ns * 1024;
+    const QPlan q = q_plan(m, n, r, K);
+    const size_t q_frags = (size_t)q.KS * cb * ns * 1024;
+    const size_t slabs = q.S > 1 ? (size_t)K * q.S * r * n * sizeof(float) : 0;
+    const size_t a = a256(p_frags), b = a256(q_frags) + a256(slabs);
+    return a > b ? a : b;
+}
+
+template <int NS>
+static int pack_kcontig(const float *src, int nrows, int64_t L, int RB, int64_t KS, uint4 *frags,
+                        hipStream_t st) {
+    const int64_t nf = KS * RB;
+    Timed timed(KID_PACK, st);
+    hipLaunchKernelGGL(pack_kcontig_kernel<NS>, dim3((unsigned)ceil_div(nf, 4)), dim3(kW), 0, st,
+                       src, nrows, L, RB, KS, frags);
+    return check_launch("pack_kcontig");
+}
+
+template <int NS>
+static int project_p_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const float *> &delta,
+                        const float *q_in, const PtrPack<float *> &out, void *workspace,
+                        hipStream_t st) {
+    const int cb = cb_of(r);
+    const int64_t KS = ceil_div(n, 64) * 4;
+    uint4 *frags = reinterpret_cast<uint4 *>(workspace);
+    int rc = pack_kcontig<NS>(q_in, r, n, cb, KS, frags, st);
+    if (rc != DLCX_OK) return rc;
+    const dim3 grid((unsigned)ceil_div(m, 64), (unsigned)K);
+    Timed timed(KID_PROJECT_P, st);
+    switch (cb) {
+        case 1: hipLaunchKernelGGL((project_p_mfma_kernel<NS, 1, 1, 2, 2>), grid, dim3(kW), 0, st, delta, frags, out, m, n, r); break;
+        case 2: hipLaunchKernelGGL((project_p_mfma_kernel<NS, 2, 1, 2, 2>), grid, dim3(kW), 0, st, delta, frags, out, m, n, r); break;
+        case 4: hipLaunchKernelGGL((project_p_mfma_kernel<NS, 2, 2, 1, 2>), grid, dim3(kW), 0, st, delta, frags, out, m, n, r); break;
+        default: hipLaunchKernelGGL((project_p_mfma_kernel<NS, 2, 4, 1, 1>), grid, dim3(kW), 0, st, delta, frags, out, m, n, r); break;
+    }
+    return check_launch("project_p_mfma");
+}
+
+int launch_sum_slabs(int K, const PtrPack<const float *> &slabs, const PtrPack<float *> &outs,
+                     int64_t count, int S, int64_t slab_stride, hipStream_t st);
+
+template <int NS>
+static int project_q_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const float *> &delta,
+                        const float *p_hat, const PtrPack<float *> &out, void *workspace,
+                        hipStream_t st) {
+    const int cb = cb_of(r);
+    const QPlan q = q_plan(m, n, r, K);
+    uint4 *frags = reinterpret_cast<uint4 *>(workspace);
+    int rc = pack_kcontig<NS>(p_hat, r, m, cb, q.KS, frags, st);
+    if (rc != DLCX_OK) return rc;
+    const int64_t slab = (int64_t)r * n;
+    PtrPack<float *> dst = out;
+    if (q.S > 1) {
+        float *base = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
+                                                a256((size_t)q.KS * cb * NS * 1024));
+        for (int k = 0; k < K; ++k) dst.p[k] = base + (int64_t)k * q.S * slab;
+    }
+    const dim3 grid((unsigned)ceil_div(n, 32 * q.JB), (unsigned)K, (unsigned)q.S);
+    {
+    Timed timed(KID_PROJECT_Q, st);
+    switch (cb) {
+        case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 2: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 2, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 4: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 4, 1>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        default: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 8, 1>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+    }
+    rc = check_launch("project_q_mfma");
+    }
+    if (rc != DLCX_OK || q.S == 1) return rc;
+    PtrPack<const float *> src;
+    for (int k = 0; k < K; ++k) src.p[k] = dst.p[k];
+    return launch_sum_slabs(K, src, out, slab, q.S, slab, st);
+}
+
+int launch_project_p_mfma(int mma, int64_t m, int64_t n, int r, int K,
+                          const PtrPack<const float *> &delta, const float *q_in,
+                          const PtrPack<float *> &out, void *workspace, hipStream_t st) {
+    if (mma == DLCX_MMA_F32) return project_p_ns<3>(m, n, r, K, delta, q_in, out, workspace, st);
+    return project_p_ns<2>(m, n, r, K, delta, q_in, out, workspace, st);
+}
+
+int launch_project_q_mfma(int mma, int64_t m, int64_t n, int r, int K,
+                          const PtrPack<const float *> &delta, const float *p_hat,
+                          const PtrPack<float *> &out, void *workspace, hipStream_t st) {
+    if (mma == DLCX_MMA_F32) return project_q_ns<3>(m, n, r, K, delta, p_hat, out, workspace, st);
+    return project_q_ns<2>(m, n, r, K, delta, p_hat, out, workspace, st);
+}
+
+size_t mfma_reconstruct_workspace_bytes(int mma, int64_t m, int64_t n, int r) {
+    const int ns = ns_of(mma);
+    const size_t ks = (size_t)(r + 15) / 16;
+    return a256((size_t)ceil_div(m, 32) * ks * ns * 1024) + a256((size_t)ceil_div(n, 32) * ks * ns * 1024);
+}
+
+template <int NS>
+static int reconstruct_launch(int64_t m, int64_t n, int ks, const uint4 *pf, const uint4 *qf,
+                              const ReconEpilogue &ep, hipStream_t st) {
+    // columns per workgroup: a multiple of 128, chosen for a few thousand workgroups
+    const int64_t rows = ceil_div(m, 32);
+    int64_t chunks = ceil_div(4096, rows);
+    const int64_t max_chunks = ceil_div(n, 128);
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    const int64_t cols = ceil_div(ceil_div(n, chunks), 128) * 128;
+    const dim3 grid((unsigned)ceil_div(n, cols), (unsigned)rows);
+    Timed timed(KID_RECONSTRUCT, st);
+    hipLaunchKernelGGL(reconstruct_mfma_kernel<NS>, grid, dim3(kW), 0, st, pf, qf, ep, m, n, cols,
+                       ks);
+    return check_launch("reconstruct_mfma");
+}
+
+template <int NS>
+static int reconstruct_ns(int64_t m, int64_t n, int r, const float *p_hat, const float *q_bar,
+                          const ReconEpilogue &ep, void *workspace, hipStream_t st) {
+    const int ks = (r + 15) / 16;
+    const int64_t xbm = ceil_div(m, 32), xbn = ceil_div(n, 32);
+    uint4 *pf = reinterpret_cast<uint4 *>(workspace);
+    uint4 *qf = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(workspace) +
+                                          a256((size_t)xbm * ks * NS * 1024));
+    int rc;
+    {
+        Timed timed(KID_PACK, st);
+        hipLaunchKernelGGL(pack_kstrided_kernel<NS>, dim3((unsigned)ceil_div(xbm * ks, 4)), dim3(kW), 0,
+                           st, p_hat, r, m, ks, xbm, pf);
+        rc = check_launch("pack p_hat");
+    }
+    if (rc != DLCX_OK) return rc;
+    {
+        Timed timed(KID_PACK, st);
+        hipLaunchKernelGGL(pack_kstrided_kernel<NS>, dim3((unsigned)ceil_div(xbn * ks, 4)), dim3(kW), 0,
+                           st, q_bar, r, n, ks, xbn, qf);
+        rc = check_launch("pack q_bar");
+    }
+    if (rc != DLCX_OK) return rc;
+    return reconstruct_launch<NS>(m, n, ks, pf, qf, ep, st);
+}
+
+int launch_reconstruct_mfma(int mma, int64_t m, int64_t n, int r, const float *p_hat,
+                            const float *q_bar, const ReconEpilogue &ep, void *workspace,
+                            hipStream_t st) {
+    if (mma == DLCX_MMA_F32) return reconstruct_ns<3>(m, n, r, p_hat, q_bar, ep, workspace, st);
+    return reconstruct_ns<2>(m, n, r, p_hat, q_bar, ep, workspace, st);
+}
+
+}  // namespace dlcx

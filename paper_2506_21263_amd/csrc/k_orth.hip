@@ -83,6 +83,7 @@ __global__ __launch_bounds__(kGT) void gram_partial_kernel(const float *__restri
 int launch_gram_partials(int64_t L, int r, const float *f, double *partials, hipStream_t st) {
     const int nt = (r + 63) / 64;
     const dim3 grid((unsigned)gram_chunks(L), (unsigned)(nt * (nt + 1) / 2));
+    Timed timed(KID_GRAM, st);
     hipLaunchKernelGGL(gram_partial_kernel, grid, dim3(kGT), 0, st, f, L, r, partials);
     return check_launch("gram_partials");
 }
@@ -192,9 +193,12 @@ static int cholqr_pass(int64_t L, int r, float *p, double *part, double *g, doub
                       "chol_inverse attribute");
         if (rc != DLCX_OK) return rc;
     }
-    hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(kCT), in_lds ? g_bytes : 0, st, part,
-                       gram_chunks(L), r, g, w, in_lds);
-    rc = check_launch("chol_inverse");
+    {
+        Timed timed(KID_CHOL, st);
+        hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(kCT), in_lds ? g_bytes : 0, st, part,
+                           gram_chunks(L), r, g, w, in_lds);
+        rc = check_launch("chol_inverse");
+    }
     if (rc != DLCX_OK) return rc;
     const size_t lds = (size_t)r * 64 * sizeof(float);
     if (lds > 48 * 1024) {
@@ -203,6 +207,7 @@ static int cholqr_pass(int64_t L, int r, float *p, double *part, double *g, doub
                       "apply_w attribute");
         if (rc != DLCX_OK) return rc;
     }
+    Timed timed(KID_APPLY_W, st);
     hipLaunchKernelGGL(apply_w_kernel, dim3((unsigned)ceil_div(L, 64)), dim3(kGT), lds, st, p, L, r,
                        w);
     return check_launch("apply_w");

@@ -95,6 +95,7 @@ static int quantize_dispatch(int K, const PtrPack<const float *> &x, int64_t nve
                              hipStream_t st) {
     const dim3 grid((unsigned)ceil_div(nvec, kQThreads), (unsigned)K);
     const dim3 block(kQThreads);
+    Timed timed(KID_QUANTIZE, st);
     switch (group) {
         case 16: hipLaunchKernelGGL((quantize_kernel<kQbits, 4>), grid, block, 0, st, x, nvec, codes, scales); break;
         case 32: hipLaunchKernelGGL((quantize_kernel<kQbits, 8>), grid, block, 0, st, x, nvec, codes, scales); break;
@@ -122,6 +123,7 @@ int launch_dequant_average(int K, const PtrPack<const uint8_t *> &codes,
     const int64_t nvec = count >> 2;
     const dim3 grid((unsigned)ceil_div(nvec, kQThreads));
     const float inv_k = 1.0f / (float)K;
+    Timed timed(KID_DEQUANT_AVG, st);
     if (qbits == 4)
         hipLaunchKernelGGL(dequant_average_kernel<4>, grid, dim3(kQThreads), 0, st, K, codes,
                            scales, nvec, group / 4, inv_k, mean_out);

@@ -138,6 +138,7 @@ int launch_effective_rank(int64_t L, int r, const float *q_bar, double tau, int3
                       "jacobi attribute");
         if (rc != DLCX_OK) return rc;
     }
+    Timed timed(KID_JACOBI, st);
     hipLaunchKernelGGL(jacobi_rank_kernel, dim3(1), dim3(kJT), in_lds ? bytes : 0, st, part,
                        gram_chunks(L), r, tau, a, in_lds, rprime_dev);
     return check_launch("jacobi_rank");

@@ -115,6 +115,7 @@ int launch_delta_ef(const float *theta_g, const void *theta_l, int dtype, float 
                     int64_t numel, hipStream_t st) {
     if (numel == 0) return DLCX_OK;
     const unsigned blocks = stream_blocks(numel);
+    Timed timed(KID_DELTA_EF, st);
     if (dtype == DLCX_BF16)
         hipLaunchKernelGGL(delta_ef_kernel<true>, dim3(blocks), dim3(kThreads), 0, st, theta_g,
                            theta_l, ef, numel);
@@ -127,6 +128,7 @@ int launch_delta_ef(const float *theta_g, const void *theta_l, int dtype, float 
 int launch_nesterov(float *theta, float *v, const float *g, int64_t numel, float lr, float mu,
                     hipStream_t st) {
     if (numel == 0) return DLCX_OK;
+    Timed timed(KID_NESTEROV, st);
     hipLaunchKernelGGL(nesterov_kernel, dim3(stream_blocks(numel)), dim3(kThreads), 0, st, theta,
                        v, g, numel, lr, mu);
     return check_launch("outer_nesterov");

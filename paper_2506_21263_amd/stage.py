@@ -14,7 +14,7 @@ import ctypes as C
 import torch
 
 from . import (PHASE_P, PHASE_Q, desc, dlcx_average, dlcx_compress_batched, dlcx_decompress,
-               dlcx_delta_ef, dlcx_outer_nesterov, dlcx_payload_bytes, dlcx_select_rank,
+               dlcx_delta_ef, dlcx_ef_delta_apply, dlcx_outer_nesterov, dlcx_payload_bytes, dlcx_select_rank,
                dlcx_select_rank_workspace_bytes, dlcx_workspace_bytes)
 
 
@@ -49,33 +49,46 @@ class MatrixState:
 
 
 class Stage:
-    """All matrices of one pipeline stage plus shared scratch; `step` is one outer step."""
+    """All matrices of one pipeline stage plus shared scratch; `step` is one outer step.
 
-    def __init__(self, matrices, lr, mu):
+    fused=True uses dlcx_ef_delta_apply (one pass for error buffers, pseudo-gradients and the
+    outer update, the decompressed average never written); fused=False runs the separate entry
+    points.  warm_start=True takes Q_bar of the previous round as the basis of the P phase.
+    """
+
+    def __init__(self, matrices, lr, mu, fused=False, warm_start=False):
         self.mats = matrices
         self.lr, self.mu = lr, mu
+        self.fused, self.warm_start = fused, warm_start
         self.t = 0
         dev = matrices[0].theta_g.device
         ws = max(m.workspace_bytes for m in matrices)
         self.workspace = torch.empty(ws, device=dev, dtype=torch.uint8)
-        big = max(m.m * m.n for m in matrices)
-        self.delta_hat = torch.empty(big, device=dev, dtype=torch.float32)
+        self.delta_hat = None
+        if not fused:
+            big = max(m.m * m.n for m in matrices)
+            self.delta_hat = torch.empty(big, device=dev, dtype=torch.float32)
 
     def params(self):
         return sum(m.m * m.n for m in self.mats)
 
     def step_matrix(self, M, theta_l, stream=None):
         t = self.t
-        if t >= 2:
-            dprev = M.desc(M.r_prev)
-            dlcx_decompress(dprev, M.p_hat, M.q_bar, self.delta_hat, M.ef, stream=stream)
-        for i in range(M.K):
-            dlcx_delta_ef(M.theta_g, theta_l[i], M.ef[i], stream=stream)
-        if t >= 2:
-            dlcx_outer_nesterov(M.theta_g, M.v, self.delta_hat, self.lr, self.mu,
-                                numel=M.m * M.n, stream=stream)
+        if t >= 2 and self.fused:
+            dlcx_ef_delta_apply(M.desc(M.r_prev), M.p_hat, M.q_bar, theta_l, M.ef, M.theta_g, M.v,
+                                self.lr, self.mu, workspace=self.workspace, stream=stream)
+        else:
+            if t >= 2:
+                dlcx_decompress(M.desc(M.r_prev), M.p_hat, M.q_bar, self.delta_hat, M.ef,
+                                workspace=self.workspace, stream=stream)
+            for i in range(M.K):
+                dlcx_delta_ef(M.theta_g, theta_l[i], M.ef[i], stream=stream)
+            if t >= 2:
+                dlcx_outer_nesterov(M.theta_g, M.v, self.delta_hat, self.lr, self.mu,
+                                    numel=M.m * M.n, stream=stream)
         d = M.desc()
-        dlcx_compress_batched(d, PHASE_P, M.ef, M.q_in, M.codes_p, M.scales_p, self.workspace,
+        basis = M.q_bar if (self.warm_start and t >= 2 and M.r_prev == M.r) else M.q_in
+        dlcx_compress_batched(d, PHASE_P, M.ef, basis, M.codes_p, M.scales_p, self.workspace,
                               stream=stream)
         dlcx_average(d, PHASE_P, M.codes_p, M.scales_p, M.p_hat, self.workspace, stream=stream)
         dlcx_compress_batched(d, PHASE_Q, M.ef, M.p_hat, M.codes_q, M.scales_q, self.workspace,

@@ -52,7 +52,7 @@ def test_bad_descriptors_are_rejected(bad):
     L = dlcx.lib()
     fake = 0x1000  # aligned, never dereferenced: validation fails first
     assert L.dlcx_compress(C.byref(d), 0, fake, fake, fake, fake, fake, None) == dlcx.EINVAL
-    assert L.dlcx_decompress(C.byref(d), fake, fake, fake, 0, None, None) == dlcx.EINVAL
+    assert L.dlcx_decompress(C.byref(d), fake, fake, fake, 0, None, fake, None) == dlcx.EINVAL
 
 
 def test_null_misaligned_and_range_arguments():

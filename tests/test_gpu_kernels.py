@@ -161,16 +161,31 @@ def test_decompress_and_error_buffer(mma, m, n, r, K, group):
     d = dlcx.desc(m, n, r, 4, group, mma)
     out = torch.zeros(m, n, device=DEV)
     efs = [to_dev(x) for x in deltas]
-    dlcx.dlcx_decompress(d, to_dev(p_hat), to_dev(q_bar), out, efs)
+    ws = ws_for(d, max(K, 1))
+    dlcx.dlcx_decompress(d, to_dev(p_hat), to_dev(q_bar), out, efs, workspace=ws)
     assert rel_l2(to_np(out), want) <= TOL[mma]
     for k in range(K):
         # e = delta - delta_hat: compare the correction, not the (larger) buffer
         assert rel_l2(deltas[k] - to_np(efs[k]), deltas[k] - want_e[k]) <= TOL[mma]
     # error buffers only (no materialised delta_hat) gives the same buffers
     efs2 = [to_dev(x) for x in deltas]
-    dlcx.dlcx_decompress(d, to_dev(p_hat), to_dev(q_bar), None, efs2)
+    dlcx.dlcx_decompress(d, to_dev(p_hat), to_dev(q_bar), None, efs2, workspace=ws)
     for k in range(K):
         assert torch.equal(efs2[k], efs[k])
+    # fused with the outer update: same error buffers, and (theta, v) as the separate kernels give
+    g2 = rng(7)
+    th = (0.02 * g2.standard_normal((m, n))).astype(np.float32)
+    v = (1e-3 * g2.standard_normal((m, n))).astype(np.float32)
+    th_w, v_w = th.copy(), v.copy()
+    ref.outer_nesterov(th_w.reshape(-1), v_w.reshape(-1), want.reshape(-1), synth.LR, synth.MU)
+    efs3 = [to_dev(x) for x in deltas]
+    d_th, d_v = to_dev(th), to_dev(v)
+    dlcx.dlcx_decompress_apply(d, to_dev(p_hat), to_dev(q_bar), efs3, d_th, d_v, synth.LR, synth.MU,
+                               workspace=ws)
+    for k in range(K):
+        assert torch.equal(efs3[k], efs[k])
+    assert rel_l2(th - to_np(d_th), th - th_w) <= TOL[mma]
+    assert rel_l2(to_np(d_v), v_w) <= TOL[mma]
 
 
 # ------------------------------------------------------------------ compress = project + quantise

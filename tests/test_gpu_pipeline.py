@@ -1,14 +1,19 @@
 """GPU parity of whole outer steps (Alg. 2 with the one-step delay) against the oracle.
 
-Both sides run freely from the same seeded inputs for several rounds; nothing computed on the GPU
-is ever fed to the oracle (the local replicas of round t are built from the ORACLE's theta).
+The compressed pipeline is discontinuous: a factor value that sits on a rounding boundary of the
+quantiser lands one code apart when the two sides' float arithmetic differs in the last bit, and
+from then on the trailing (noise-level) columns of the orthonormal basis, which are determined
+only up to a rotation inside a nearly degenerate subspace, may differ macroscopically.  Two kinds
+of test follow from that:
 
-What is compared.  delta_i, theta_g, v and the decompressed average Delta_hat are unique and are
-compared in rel-L2.  A quantised code is an integer decided by a float: the two sides quantise
-factors that differ in the last bits, so a value that sits on a rounding boundary may legitimately
-land one step apart.  Codes are therefore compared bit for bit, and a mismatch is accepted only
-if it is by one step on a value within 1e-2 of a boundary; when any such flip happened the float
-bar of that round is widened to the size of the flipped steps (stated in `flip_allowance`).
+* lockstep: the oracle runs the rounds; before every entry-point call the GPU is given the
+  ORACLE's inputs of that call and its outputs are compared (floats in rel-L2 at the mode's bar,
+  codes bit for bit, a mismatch being accepted only if it is by one step on a value within 1e-2
+  of a rounding boundary).  Nothing computed on the GPU is ever fed to the oracle.
+* free-running: the library's own call sequence (stage driver) runs the rounds on the GPU and is
+  compared with the oracle strictly until the first code flip; after a flip only what stays
+  well defined is checked (the flip is by one step on a boundary value, theta_g at a loose bar,
+  and the error-feedback telescoping identity of the GPU's own outputs).
 """
 import numpy as np
 import pytest
@@ -18,7 +23,7 @@ import paper_2506_21263_amd as dlcx
 import synth
 from oracle import pipeline, ref
 from paper_2506_21263_amd.stage import MatrixState, Stage
-from gpu_util import DEV, code_mismatch_report, rel_l2, to_dev, to_np
+from gpu_util import DEV, code_mismatch_report, payload_buffers, rel_l2, to_dev, to_np, ws_for
 
 pytestmark = pytest.mark.gpu
 
@@ -32,86 +37,147 @@ CASES = [
     ("cfg1-like", 1024, 2048, 4, 32, 4, 128, "f32", 3, 1e-3),
     ("cfg2-like", 1024, 768, 4, 64, 4, 128, "bf16", 2, 1e-3),
     ("cfg4-like", 768, 1024, 8, 64, 8, 64, "bf16", 2, 1e-3),
+    ("ragged", 528, 336, 3, 20, 4, 16, "bf16", 2, 1e-3),
 ]
 
 
-def flip_allowance(n_flips, count, K):
-    """rel-L2 a factor mean can move when n_flips of its K*count codes move by one step.
-    One step is about 0.4 of the rms of its group for int4 (less for int8): the mean moves by
-    step/K on n_flips elements of count."""
-    return 0.5 * np.sqrt(n_flips / float(count)) / K
+def _check_codes(name, t, tag, k, codes_gpu, orc, count, qbits, group):
+    nb, ok = code_mismatch_report(to_np(codes_gpu), orc.trace[tag + "_codes"][k], orc.trace[tag][k],
+                                  orc.trace[tag + "_scales"][k], count, qbits, group,
+                                  ref.unpack_codes)
+    assert ok, (name, t, tag, k, "code mismatch that is not a one-step boundary flip")
+    return nb
 
 
 @pytest.mark.parametrize("mma", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
-def test_outer_rounds_match_oracle(case, mma):
+def test_lockstep_rounds(case, mma):
     name, m, n, K, r, qbits, group, kind, T, sigma = case
     inp = synth.MatrixInputs(m, n, K, r, seed=sum(map(ord, name)), sigma=sigma, alpha=1.0,
                              theta_l=kind)
     orc = pipeline.MatrixOracle(inp.theta_g, K, inp.q_in, qbits, group, synth.LR, synth.MU)
-    M = MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), qbits, group, mma)
-    st = Stage([M], synth.LR, synth.MU)
+    d = dlcx.desc(m, n, r, qbits, group, mma)
+    ws = ws_for(d, K)
     tol = TOL[mma]
-    allow = 0.0  # flips move the state for good (error feedback): the allowance accumulates
+    total_flips = 0
+    for t in range(1, T + 1):
+        # the oracle's state at the start of the round
+        theta0, v0 = orc.theta.copy(), orc.v.copy()
+        ef0 = [e.copy() for e in orc.ef]
+        p_prev = None if orc.p_hat is None else orc.p_hat.copy()
+        q_prev = None if orc.q_bar is None else orc.q_bar.copy()
+        tl = [inp.theta_local(orc.theta, t, i) for i in range(K)]
+        orc.step(tl)
+        # --- error buffer and outer update from the previous round's average
+        efs = [to_dev(e) for e in ef0]
+        if t >= 2:
+            d_hat = torch.zeros(m, n, device=DEV)
+            dlcx.dlcx_decompress(d, to_dev(p_prev), to_dev(q_prev), d_hat, efs, workspace=ws)
+            assert rel_l2(to_np(d_hat), orc.trace["delta_hat_prev"]) <= tol, (name, t)
+            for k in range(K):
+                assert rel_l2(ef0[k] - to_np(efs[k]), ef0[k] - orc.trace["e"][k]) <= tol
+            efs = [to_dev(e) for e in orc.trace["e"]]
+            th, v = to_dev(theta0), to_dev(v0)
+            dlcx.dlcx_outer_nesterov(th, v, to_dev(orc.trace["delta_hat_prev"]), synth.LR, synth.MU)
+            assert rel_l2(to_np(th), orc.theta) <= 1e-6 and rel_l2(to_np(v), orc.v) <= 1e-6
+            # fused form: decompress + error buffers + outer update in one pass
+            efs2 = [to_dev(e) for e in ef0]
+            th2, v2 = to_dev(theta0), to_dev(v0)
+            dlcx.dlcx_decompress_apply(d, to_dev(p_prev), to_dev(q_prev), efs2, th2, v2, synth.LR,
+                                       synth.MU, workspace=ws)
+            assert rel_l2(theta0 - to_np(th2), theta0 - orc.theta) <= tol, (name, t)
+            assert rel_l2(to_np(v2), orc.v) <= tol
+            for k in range(K):
+                assert rel_l2(ef0[k] - to_np(efs2[k]), ef0[k] - orc.trace["e"][k]) <= tol
+            # fully fused form: error buffers, next pseudo-gradients and outer update in one pass
+            efs3 = [to_dev(e) for e in ef0]
+            th3, v3 = to_dev(theta0), to_dev(v0)
+            dlcx.dlcx_ef_delta_apply(d, to_dev(p_prev), to_dev(q_prev), [to_dev(x) for x in tl], efs3,
+                                     th3, v3, synth.LR, synth.MU, workspace=ws)
+            assert torch.equal(th3, th2) and torch.equal(v3, v2)
+            for k in range(K):
+                # delta = g + e with e = delta_prev - delta_hat: compare the part the kernel adds
+                base = ref.delta_ef(theta0.reshape(-1), np.ascontiguousarray(tl[k]).reshape(-1),
+                                    ef0[k].reshape(-1)).reshape(m, n)
+                assert rel_l2(base - to_np(efs3[k]), base - orc.trace["delta"][k]) <= tol
+                assert rel_l2(to_np(efs3[k]), orc.trace["delta"][k]) <= tol
+        # --- pseudo-gradient with error compensation
+        for k in range(K):
+            dlcx.dlcx_delta_ef(to_dev(theta0), to_dev(tl[k]), efs[k])
+            assert rel_l2(to_np(efs[k]), orc.trace["delta"][k]) <= 1e-6, (name, t, k)
+        deltas = [to_dev(x) for x in orc.trace["delta"]]
+        # --- P phase
+        codes, scales = payload_buffers(d, dlcx.PHASE_P, K)
+        dlcx.dlcx_compress_batched(d, dlcx.PHASE_P, deltas, to_dev(orc.trace["q_in"]), codes, scales, ws)
+        torch.cuda.synchronize()
+        factors = to_np(ws[: K * r * m * 4].view(torch.float32)).reshape(K, r, m)
+        for k in range(K):
+            assert rel_l2(factors[k], orc.trace["P"][k]) <= tol, (name, t, "P", k)
+            total_flips += _check_codes(name, t, "P", k, codes[k], orc, r * m, qbits, group)
+        p_hat = torch.zeros(r, m, device=DEV)
+        dlcx.dlcx_average(d, dlcx.PHASE_P, [to_dev(c) for c in orc.trace["P_codes"]],
+                          [to_dev(s) for s in orc.trace["P_scales"]], p_hat, ws)
+        cond = np.linalg.cond(orc.trace["p_bar"].astype(np.float64))
+        assert rel_l2(to_np(p_hat), orc.p_hat) <= max(1e-5, 4e-7 * cond), (name, t, cond)
+        # --- Q phase
+        codes, scales = payload_buffers(d, dlcx.PHASE_Q, K)
+        dlcx.dlcx_compress_batched(d, dlcx.PHASE_Q, deltas, to_dev(orc.p_hat), codes, scales, ws)
+        torch.cuda.synchronize()
+        factors = to_np(ws[: K * r * n * 4].view(torch.float32)).reshape(K, r, n)
+        for k in range(K):
+            assert rel_l2(factors[k], orc.trace["Q"][k]) <= tol, (name, t, "Q", k)
+            total_flips += _check_codes(name, t, "Q", k, codes[k], orc, r * n, qbits, group)
+        q_bar = torch.zeros(r, n, device=DEV)
+        dlcx.dlcx_average(d, dlcx.PHASE_Q, [to_dev(c) for c in orc.trace["Q_codes"]],
+                          [to_dev(s) for s in orc.trace["Q_scales"]], q_bar, ws)
+        assert rel_l2(to_np(q_bar), orc.q_bar) <= 1e-6, (name, t)
+        orc.set_basis(orc.q_bar)
+    # identical inputs: boundary flips are rare
+    assert total_flips <= max(4, 1e-3 * T * K * r * (m + n)), total_flips
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+@pytest.mark.parametrize("mma", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("case", CASES[:3], ids=[c[0] for c in CASES[:3]])
+def test_free_running_stage_driver(case, mma, fused):
+    name, m, n, K, r, qbits, group, kind, T, sigma = case
+    inp = synth.MatrixInputs(m, n, K, r, seed=sum(map(ord, name)) + 1, sigma=sigma, alpha=1.0,
+                             theta_l=kind)
+    orc = pipeline.MatrixOracle(inp.theta_g, K, inp.q_in, qbits, group, synth.LR, synth.MU)
+    M = MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), qbits, group, mma)
+    st = Stage([M], synth.LR, synth.MU, fused=fused, warm_start=True)
+    tol = TOL[mma]
+    flipped = False
+    sum_g = [np.zeros((m, n)) for _ in range(K)]
+    sum_d = np.zeros((m, n))
     for t in range(1, T + 1):
         tl = [inp.theta_local(orc.theta, t, i) for i in range(K)]
+        theta_before = to_np(M.theta_g).astype(np.float64)
         orc.step(tl)
         st.step([[to_dev(x) for x in tl]])
         torch.cuda.synchronize()
-        for tag, codes_gpu, scales_gpu, L in (("P", M.codes_p, M.scales_p, m),
-                                              ("Q", M.codes_q, M.scales_q, n)):
-            flips = 0
-            for k in range(K):
-                nb, ok = code_mismatch_report(to_np(codes_gpu[k]), orc.trace[tag + "_codes"][k],
-                                              orc.trace[tag][k], orc.trace[tag + "_scales"][k],
-                                              r * L, qbits, group, ref.unpack_codes)
-                assert ok, (name, t, tag, k, "code mismatch that is not a boundary flip")
-                flips += nb
-                if mma != dlcx.MMA_BF16:
-                    assert rel_l2(to_np(scales_gpu[k]), orc.trace[tag + "_scales"][k]) <= tol
-            if mma != dlcx.MMA_BF16:
-                # on the fp32 paths flips are rare events
-                assert flips <= max(2, 1e-4 * K * r * L), (name, t, tag, flips)
-            allow = max(allow, flip_allowance(flips, r * L, K))
-        for k in range(K):
-            assert rel_l2(to_np(M.ef[k]), orc.trace["delta"][k]) <= tol + allow, (name, t, k)
-        d_hat = torch.zeros(m, n, device=DEV)
-        dlcx.dlcx_decompress(M.desc(), M.p_hat, M.q_bar, d_hat)
-        cond = np.linalg.cond(orc.trace["p_bar"].astype(np.float64))
-        bar = (tol + allow) * max(1.0, cond / 50.0) if mma == dlcx.MMA_BF16 else tol + allow
-        assert rel_l2(to_np(d_hat), orc.delta_hat()) <= max(bar, 4e-7 * cond), (name, t, cond, allow)
-        assert rel_l2(to_np(M.theta_g), orc.theta) <= tol, (name, t)
-        assert rel_l2(to_np(M.v), orc.v) <= tol + allow, (name, t)
-        # warm start for the next round, on both sides
-        orc.set_basis(orc.q_bar)
-        M.q_in.copy_(M.q_bar)
-    assert st.t == T and orc.n_applied == T - 1
-
-
-def test_theta_untouched_in_round_one_and_telescoping_on_gpu():
-    # one-step delay: nothing is applied at t = 1; and for the GPU's own outputs the error
-    # feedback telescopes: sum_t Delta_hat^t + e^{T+1} = sum_t g^t for every worker.
-    m, n, K, r = 256, 384, 3, 8
-    inp = synth.MatrixInputs(m, n, K, r, seed=77, sigma=1e-3, alpha=1.0)
-    M = MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), 4, 64, dlcx.MMA_FMA)
-    st = Stage([M], synth.LR, synth.MU)
-    sum_g = [np.zeros((m, n)) for _ in range(K)]
-    sum_d = np.zeros((m, n))
-    theta_host = inp.theta_g.copy()
-    T = 4
-    for t in range(1, T + 1):
-        tl = [inp.theta_local(theta_host, t, i) for i in range(K)]
-        theta_before = to_np(M.theta_g).astype(np.float64)
-        st.step([[to_dev(x) for x in tl]])
-        torch.cuda.synchronize()
-        if t == 1:
-            assert np.array_equal(to_np(M.theta_g), inp.theta_g)
         for i in range(K):
-            sum_g[i] += theta_before - tl[i].astype(np.float64)
+            sum_g[i] += theta_before - (synth.bf16_bits_to_f32(tl[i]) if kind == "bf16" else tl[i])
         d_hat = torch.zeros(m, n, device=DEV)
-        dlcx.dlcx_decompress(M.desc(), M.p_hat, M.q_bar, d_hat)
+        dlcx.dlcx_decompress(M.desc(), M.p_hat, M.q_bar, d_hat, workspace=st.workspace)
         sum_d += to_np(d_hat)
-        M.q_in.copy_(M.q_bar)
+        if t == 1:
+            assert np.array_equal(to_np(M.theta_g), inp.theta_g)  # nothing applied at t = 1
+        if not flipped:
+            for tag, cg, L in (("P", M.codes_p, m), ("Q", M.codes_q, n)):
+                for k in range(K):
+                    if not flipped:
+                        flipped = _check_codes(name, t, tag, k, cg[k], orc, r * L, qbits, group) > 0
+        if not flipped:  # strict parity while the two code streams are identical
+            for k in range(K):
+                assert rel_l2(to_np(M.ef[k]), orc.trace["delta"][k]) <= tol, (name, t, k)
+            cond = np.linalg.cond(orc.trace["p_bar"].astype(np.float64))
+            assert rel_l2(to_np(d_hat), orc.delta_hat()) <= max(tol, 4e-7 * cond), (name, t, cond)
+            assert rel_l2(to_np(M.theta_g), orc.theta) <= tol and rel_l2(to_np(M.v), orc.v) <= tol
+        assert rel_l2(to_np(M.theta_g), orc.theta) <= 2e-2, (name, t)  # sanity bar after a flip
+        orc.set_basis(orc.q_bar)
+    assert st.t == T and orc.n_applied == T - 1
+    # error feedback telescopes on the GPU's own outputs, flips or not
     for i in range(K):
         e_next = to_np(M.ef[i]).astype(np.float64) - to_np(d_hat)
         assert rel_l2(sum_d + e_next, sum_g[i]) <= 1e-6 * T
