@@ -25,7 +25,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_stage(cfg_id, mma, layers, device, fused):
+def build_stage(cfg_id, mma, layers, device, fused, streams):
     import torch
 
     import synth
@@ -52,7 +52,8 @@ def build_stage(cfg_id, mma, layers, device, fused):
             idx += 1
         log("generated layer %d/%d  (%.1f s, %.1f GB allocated)" %
             (layer + 1, layers, time.time() - t0, torch.cuda.memory_allocated() / 1e9))
-    stage = Stage(mats, synth.LR, synth.MU, fused=fused, warm_start=True)
+    stage = Stage(mats, synth.LR, synth.MU, fused=fused, warm_start=True, streams=streams,
+                  measure_rank=True)
     return stage, locals_
 
 
@@ -110,6 +111,7 @@ def main():
     ap.add_argument("--mma", type=int, default=2, help="0 fma/fp64-acc, 1 fp32-accurate MFMA, 2 bf16 MFMA")
     ap.add_argument("--layers", type=int, default=0, help="layers resident (0 = the whole stage)")
     ap.add_argument("--unfused", action="store_true", help="separate decompress / Nesterov kernels")
+    ap.add_argument("--streams", type=int, default=2, help="HIP streams the matrices are dealt to")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -129,7 +131,7 @@ def main():
     cfg = synth.CONFIGS[args.config]
     layers = args.layers or cfg["layers"]
     fused = not args.unfused
-    stage, locals_ = build_stage(args.config, args.mma, layers, device, fused)
+    stage, locals_ = build_stage(args.config, args.mma, layers, device, fused, args.streams)
     K = cfg["K"]
     params = stage.params()
     selector = RankSelector(stage, c=5, r1=cfg["r"], rmin=4, rmax=cfg["r"], H1=125)
@@ -194,7 +196,7 @@ def main():
         "config": {"workload": cfg["name"], "layers": layers, "matrices": len(stage.mats),
                    "params": params, "K": K, "rank": cfg["r"], "qbits": cfg["qbits"],
                    "group": cfg["group"], "theta_l": cfg["theta_l"], "mma": args.mma,
-                   "fused": fused},
+                   "fused": fused, "streams": stage.nstreams},
         "roofline": roofline,
         "stage_hbm": {"algorithmic_bytes_per_param": b_alg,
                       "achieved_GBps": b_alg * params / (dt / args.steps) / 1e9,

@@ -139,6 +139,15 @@ int dlcx_select_rank(const dlcx_desc *descs_host, const float *const *q_bars_hos
                      int32_t *rprime_inout_host, int32_t *r_next_out_host,
                      int32_t *H_next_out_host, void *workspace, void *stream);
 
+/* The second half of dlcx_select_rank alone: the per-matrix r' values were already measured with
+ * dlcx_effective_rank into the DEVICE array rprime_dev (n_matrices ints; with n_matrices == 0
+ * the value in *rprime_inout_host is used).  Copies them back (synchronises `stream`), forms the
+ * stage value and applies the window rule. */
+int dlcx_select_rank_from(const int32_t *rprime_dev, int n_matrices, int32_t *rprime_hist_host,
+                          int32_t t, int32_t c, int32_t r1, int32_t rmin, int32_t rmax, int32_t H1,
+                          int32_t *rprime_inout_host, int32_t *r_next_out_host,
+                          int32_t *H_next_out_host, void *stream);
+
 /* ---- helpers: the steps the entry points above are made of ---------------------------- */
 
 /* Size of one payload; returns codes + scales bytes, 0 on a bad descriptor. */

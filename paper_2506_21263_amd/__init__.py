@@ -53,6 +53,8 @@ SYMBOLS = {
     "dlcx_outer_nesterov": (_int, [_vp, _vp, _vp, _i64, C.c_float, C.c_float, _vp]),
     "dlcx_select_rank": (_int, [_dp, _vp, _int, C.c_double, _vp, _i32, _i32, _i32, _i32, _i32,
                                 _i32, _vp, _vp, _vp, _vp, _vp]),
+    "dlcx_select_rank_from": (_int, [_vp, _int, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp,
+                                     _vp]),
     "dlcx_payload_bytes": (C.c_size_t, [_dp, _int, _vp, _vp]),
     "dlcx_workspace_bytes": (C.c_size_t, [_dp, _int]),
     "dlcx_select_rank_workspace_bytes": (C.c_size_t, [_dp, _int]),
@@ -200,6 +202,18 @@ def dlcx_select_rank(descs, q_bars, tau, rprime_hist, t, c, r1, rmin, rmax, H1, 
                                   H1, C.addressof(rp), C.addressof(r_next), C.addressof(h_next),
                                   _ptr(workspace), _stream(stream) if n else None),
            "dlcx_select_rank")
+    return rp.value, r_next.value, h_next.value
+
+
+def dlcx_select_rank_from(rprime_dev, n, rprime_hist, t, c, r1, rmin, rmax, H1, rprime=None,
+                          stream=None):
+    """Window rule on r' values already measured into the device int32 tensor rprime_dev."""
+    rp = C.c_int32(0 if rprime is None else rprime)
+    r_next, h_next = C.c_int32(0), C.c_int32(0)
+    _check(lib().dlcx_select_rank_from(_ptr(rprime_dev) if n else None, n,
+                                       C.addressof(rprime_hist), t, c, r1, rmin, rmax, H1,
+                                       C.addressof(rp), C.addressof(r_next), C.addressof(h_next),
+                                       _stream(stream) if n else None), "dlcx_select_rank_from")
     return rp.value, r_next.value, h_next.value
 
 

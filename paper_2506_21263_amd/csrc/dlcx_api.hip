@@ -414,51 +414,16 @@ int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,
     return launch_effective_rank(L, r, q_bar, tau, rprime_out_dev, workspace, as_stream(stream));
 }
 
-int dlcx_select_rank(const dlcx_desc *descs_host, const float *const *q_bars_host, int n_matrices,
-                     double tau, int32_t *rprime_hist_host, int32_t t, int32_t c, int32_t r1,
-                     int32_t rmin, int32_t rmax, int32_t H1, int32_t *rprime_inout_host,
-                     int32_t *r_next_out_host, int32_t *H_next_out_host, void *workspace,
-                     void *stream) {
-    if (n_matrices < 0 || t < 1 || c < 1 || r1 < 1 || rmin < 1 || rmax < rmin || H1 < 1)
-        return DLCX_EINVAL;
-    if (!rprime_hist_host || !rprime_inout_host || !r_next_out_host || !H_next_out_host)
-        return DLCX_EINVAL;
-    if (n_matrices > 0) {
-        if (!descs_host || !q_bars_host || !workspace || !aligned16(workspace)) return DLCX_EINVAL;
-        if (!(tau > 0.0 && tau <= 1.0)) return DLCX_EINVAL;
-        for (int i = 0; i < n_matrices; ++i) {
-            if (check_desc(&descs_host[i]) != DLCX_OK) return DLCX_EINVAL;
-            if (!q_bars_host[i] || !aligned16(q_bars_host[i])) return DLCX_EINVAL;
-        }
-        int32_t *out_dev = reinterpret_cast<int32_t *>(workspace);
-        char *ws = reinterpret_cast<char *>(workspace) + align256((size_t)n_matrices * sizeof(int32_t));
-        for (int i = 0; i < n_matrices; ++i) {
-            int rc = launch_effective_rank(descs_host[i].n, descs_host[i].r, q_bars_host[i], tau,
-                                           out_dev + i, ws, as_stream(stream));
-            if (rc != DLCX_OK) return rc;
-            ws += align256(effrank_workspace_bytes(descs_host[i].n, descs_host[i].r));
-        }
-        std::string tmp;
-        tmp.resize((size_t)n_matrices * sizeof(int32_t));
-        int rc = note_hip(hipMemcpyAsync(&tmp[0], out_dev, tmp.size(), hipMemcpyDeviceToHost,
-                                         as_stream(stream)),
-                          "select_rank copy");
-        if (rc != DLCX_OK) return rc;
-        rc = note_hip(hipStreamSynchronize(as_stream(stream)), "select_rank sync");
-        if (rc != DLCX_OK) return rc;
-        const int32_t *vals = reinterpret_cast<const int32_t *>(tmp.data());
-        int64_t sum = 0;
-        for (int i = 0; i < n_matrices; ++i) sum += vals[i] > 0 ? vals[i] : rmin;
-        *rprime_inout_host = (int32_t)((2 * sum + n_matrices) / (2 * (int64_t)n_matrices));
-    }
-    rprime_hist_host[(t - 1) % c] = *rprime_inout_host;
+static int window_rule(int32_t rprime, int32_t *hist, int32_t t, int32_t c, int32_t r1,
+                       int32_t rmin, int32_t rmax, int32_t H1, int32_t *r_next, int32_t *H_next) {
+    hist[(t - 1) % c] = rprime;
     if (t < c) {
-        *r_next_out_host = r1;
-        *H_next_out_host = H1;
+        *r_next = r1;
+        *H_next = H1;
         return DLCX_OK;
     }
     int64_t sum = 0;
-    for (int i = 0; i < c; ++i) sum += rprime_hist_host[i];
+    for (int i = 0; i < c; ++i) sum += hist[i];
     int64_t rt = (2 * sum + c) / (2 * (int64_t)c);
     if (rt < rmin) rt = rmin;
     if (rt > rmax) rt = rmax;
@@ -466,9 +431,64 @@ int dlcx_select_rank(const dlcx_desc *descs_host, const float *const *q_bars_hos
     const int64_t num = (int64_t)H1 * ((int64_t)r1 - rt);
     int64_t H = num >= 0 ? (2 * num + r1) / (2 * (int64_t)r1) : 0;
     if (H < 1) H = 1;
-    *r_next_out_host = (int32_t)rt;
-    *H_next_out_host = (int32_t)H;
+    *r_next = (int32_t)rt;
+    *H_next = (int32_t)H;
     return DLCX_OK;
+}
+
+int dlcx_select_rank_from(const int32_t *rprime_dev, int n_matrices, int32_t *rprime_hist_host,
+                          int32_t t, int32_t c, int32_t r1, int32_t rmin, int32_t rmax, int32_t H1,
+                          int32_t *rprime_inout_host, int32_t *r_next_out_host,
+                          int32_t *H_next_out_host, void *stream) {
+    if (n_matrices < 0 || t < 1 || c < 1 || r1 < 1 || rmin < 1 || rmax < rmin || H1 < 1)
+        return DLCX_EINVAL;
+    if (!rprime_hist_host || !rprime_inout_host || !r_next_out_host || !H_next_out_host)
+        return DLCX_EINVAL;
+    if (n_matrices > 0) {
+        if (!rprime_dev) return DLCX_EINVAL;
+        std::vector<int32_t> vals((size_t)n_matrices);
+        int rc = note_hip(hipMemcpyAsync(vals.data(), rprime_dev, vals.size() * sizeof(int32_t),
+                                         hipMemcpyDeviceToHost, as_stream(stream)),
+                          "select_rank copy");
+        if (rc != DLCX_OK) return rc;
+        rc = note_hip(hipStreamSynchronize(as_stream(stream)), "select_rank sync");
+        if (rc != DLCX_OK) return rc;
+        int64_t sum = 0;
+        for (int i = 0; i < n_matrices; ++i) sum += vals[i] > 0 ? vals[i] : rmin;
+        *rprime_inout_host = (int32_t)((2 * sum + n_matrices) / (2 * (int64_t)n_matrices));
+    }
+    return window_rule(*rprime_inout_host, rprime_hist_host, t, c, r1, rmin, rmax, H1,
+                       r_next_out_host, H_next_out_host);
+}
+
+int dlcx_select_rank(const dlcx_desc *descs_host, const float *const *q_bars_host, int n_matrices,
+                     double tau, int32_t *rprime_hist_host, int32_t t, int32_t c, int32_t r1,
+                     int32_t rmin, int32_t rmax, int32_t H1, int32_t *rprime_inout_host,
+                     int32_t *r_next_out_host, int32_t *H_next_out_host, void *workspace,
+                     void *stream) {
+    if (n_matrices < 0) return DLCX_EINVAL;
+    int32_t *out_dev = nullptr;
+    if (n_matrices > 0) {
+        if (!descs_host || !q_bars_host || !workspace || !aligned16(workspace)) return DLCX_EINVAL;
+        if (!(tau > 0.0 && tau <= 1.0)) return DLCX_EINVAL;
+        if (t < 1 || c < 1 || r1 < 1 || rmin < 1 || rmax < rmin || H1 < 1 || !rprime_hist_host ||
+            !rprime_inout_host || !r_next_out_host || !H_next_out_host)
+            return DLCX_EINVAL;
+        for (int i = 0; i < n_matrices; ++i) {
+            if (check_desc(&descs_host[i]) != DLCX_OK) return DLCX_EINVAL;
+            if (!q_bars_host[i] || !aligned16(q_bars_host[i])) return DLCX_EINVAL;
+        }
+        out_dev = reinterpret_cast<int32_t *>(workspace);
+        char *ws = reinterpret_cast<char *>(workspace) + align256((size_t)n_matrices * sizeof(int32_t));
+        for (int i = 0; i < n_matrices; ++i) {
+            int rc = launch_effective_rank(descs_host[i].n, descs_host[i].r, q_bars_host[i], tau,
+                                           out_dev + i, ws, as_stream(stream));
+            if (rc != DLCX_OK) return rc;
+            ws += align256(effrank_workspace_bytes(descs_host[i].n, descs_host[i].r));
+        }
+    }
+    return dlcx_select_rank_from(out_dev, n_matrices, rprime_hist_host, t, c, r1, rmin, rmax, H1,
+                                 rprime_inout_host, r_next_out_host, H_next_out_host, stream);
 }
 
 }  // extern "C"

@@ -375,94 +375,121 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
 
 // ---------------------------------------------------------------------------------------------
 // Reconstruction  delta_hat[i][j] = sum_c P_hat[c][i] Q_bar[c][j]  with fused consumers.
-// Workgroup: 32 rows x (4 wavefronts x 32 columns), swept along j.  A = P_hat fragments (M = i),
-// B = Q_bar fragments (N = j): D[i][j], lane = column, so every load and store of a matrix
-// element below is a 128-byte row segment per half-wavefront.
-//   out != NULL      : delta_hat is written
-//   K > 0            : e_k <- e_k - delta_hat                       (error buffers of Alg. 2)
-//   theta != NULL    : v <- mu v + delta_hat; theta <- theta - lr (delta_hat + mu v)   (OuterOpt)
+// Workgroup: 32 rows x 256 columns per iteration, swept along j; wavefront w owns the 64 columns
+// 64 w .. 64 w + 63 (two 32 x 32 MFMA blocks; A = P_hat fragments with M = i, B = Q_bar fragments
+// with N = j).  The accumulators (lane = column, register = row) go through a wavefront-private
+// LDS tile so that every access to a matrix element is a 16-byte vector and a wavefront
+// instruction covers 4 rows x 256 contiguous bytes, the same shape as a plain streaming kernel:
+//   out            : delta_hat is written
+//   K > 0          : e_k <- e_k - delta_hat                      (error buffers of Alg. 2)
+//   tl_on          : e_k <- (theta - theta_l,k) + e_k            (next pseudo-gradient)
+//   apply          : v <- mu v + delta_hat; theta <- theta - lr (delta_hat + mu v)   (OuterOpt)
 // ---------------------------------------------------------------------------------------------
+constexpr int kRPitch = 64 + 4;  // floats per LDS tile row
+
 template <int NS>
 __global__ __launch_bounds__(kW) void reconstruct_mfma_kernel(
     const uint4 *__restrict__ pfrags, const uint4 *__restrict__ qfrags, ReconEpilogue ep,
     int64_t m, int64_t n, int64_t cols_per_wg, int KS) {
+    __shared__ __attribute__((aligned(16))) float tile[4][32][kRPitch];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t ib = blockIdx.y;
     const int64_t jbegin = (int64_t)blockIdx.x * cols_per_wg;
     int64_t jend = jbegin + cols_per_wg;
     if (jend > n) jend = n;
+    const int64_t nblk = (n + 31) >> 5;
+    const int prow = lane >> 4, pc4 = lane & 15;  // epilogue: 4 rows x 16 float4 per instruction
 
-    for (int64_t jt = jbegin + wave * 32; jt < jend; jt += 128) {
-        const int64_t jb = jt >> 5;
-        f32x16_t d;
+    for (int64_t jt0 = jbegin; jt0 < jend; jt0 += 256) {  // uniform over the workgroup
+        const int64_t jt = jt0 + wave * 64;
+        f32x16_t d[2];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) d[v] = 0.f;
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) d[nb][v] = 0.f;
+        if (jt < jend) {
+            const int64_t jb0 = jt >> 5;
+            const bool two = jb0 + 1 < nblk;
 #pragma unroll 2
-        for (int s = 0; s < KS; ++s) {
-            uint4 a[NS], b[NS];
+            for (int s = 0; s < KS; ++s) {
+                uint4 a[NS], b0[NS], b1[NS];
 #pragma unroll
-            for (int h = 0; h < NS; ++h) {
-                a[h] = pfrags[((ib * KS + s) * NS + h) * 64 + lane];
-                b[h] = qfrags[((jb * KS + s) * NS + h) * 64 + lane];
+                for (int h = 0; h < NS; ++h) {
+                    a[h] = pfrags[((ib * KS + s) * NS + h) * 64 + lane];
+                    b0[h] = qfrags[((jb0 * KS + s) * NS + h) * 64 + lane];
+                    b1[h] = two ? qfrags[(((jb0 + 1) * KS + s) * NS + h) * 64 + lane]
+                                : make_uint4(0u, 0u, 0u, 0u);
+                }
+                mfma_split<NS>(a, b0, d[0]);
+                mfma_split<NS>(a, b1, d[1]);
             }
-            mfma_split<NS>(a, b, d);
         }
-        const int64_t j = jt + (lane & 31);
-        if (j >= n) continue;
-        int64_t off[16];
-        bool ok[16];
+        __syncthreads();  // the previous iteration's readers are done with the tile
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t i = ib * 32 + d_row(v, lane);
-            ok[v] = i < m;
-            off[v] = i * n + j;
-        }
-        if (ep.out) {
+        for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                if (ok[v]) ep.out[off[v]] = d[v];
-        }
-        float tv[16];
-        if (ep.tl_on || ep.apply) {
+                tile[wave][d_row(v, lane)][nb * 32 + (lane & 31)] = d[nb][v];
+        __syncthreads();
+        const int64_t j = jt + pc4 * 4;
+        if (jt >= jend || j >= n) continue;
+#pragma unroll 2
+        for (int pass = 0; pass < 8; ++pass) {
+            const int row = pass * 4 + prow;
+            const int64_t i = ib * 32 + row;
+            if (i >= m) continue;
+            const int64_t off = i * n + j;
+            const float4 dv = *reinterpret_cast<const float4 *>(&tile[wave][row][pc4 * 4]);
+            if (ep.out) *reinterpret_cast<float4 *>(ep.out + off) = dv;
+            float4 tv = make_float4(0.f, 0.f, 0.f, 0.f), vv = tv;
+            if (ep.tl_on || ep.apply) tv = *reinterpret_cast<const float4 *>(ep.theta + off);
+            if (ep.apply) vv = *reinterpret_cast<const float4 *>(ep.vel + off);
+            for (int k0 = 0; k0 < ep.K; k0 += 4) {
+                float4 x[4], l[4];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) tv[v] = ok[v] ? ep.theta[off[v]] : 0.f;
-        }
-        for (int k = 0; k < ep.K; ++k) {
-            float *__restrict__ e = ep.ef.p[k];
-            float x[16], l[16];
+                for (int kk = 0; kk < 4; ++kk) {
+                    if (k0 + kk < ep.K) {
+                        x[kk] = *reinterpret_cast<const float4 *>(ep.ef.p[k0 + kk] + off);
+                        if (ep.tl_on) {
+                            if (ep.tl_bf16) {
+                                const uint2 bits = *reinterpret_cast<const uint2 *>(
+                                    reinterpret_cast<const uint16_t *>(ep.tl.p[k0 + kk]) + off);
+                                l[kk] = make_float4(__uint_as_float(bits.x << 16),
+                                                    __uint_as_float(bits.x & 0xFFFF0000u),
+                                                    __uint_as_float(bits.y << 16),
+                                                    __uint_as_float(bits.y & 0xFFFF0000u));
+                            } else {
+                                l[kk] = *reinterpret_cast<const float4 *>(
+                                    reinterpret_cast<const float *>(ep.tl.p[k0 + kk]) + off);
+                            }
+                        }
+                    }
+                }
 #pragma unroll
-            for (int v = 0; v < 16; ++v) x[v] = ok[v] ? e[off[v]] : 0.f;
-            if (ep.tl_on) {
-                if (ep.tl_bf16) {
-                    const uint16_t *__restrict__ t16 = reinterpret_cast<const uint16_t *>(ep.tl.p[k]);
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        l[v] = ok[v] ? __uint_as_float((uint32_t)t16[off[v]] << 16) : 0.f;
-                } else {
-                    const float *__restrict__ t32 = reinterpret_cast<const float *>(ep.tl.p[k]);
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) l[v] = ok[v] ? t32[off[v]] : 0.f;
+                for (int kk = 0; kk < 4; ++kk) {
+                    if (k0 + kk < ep.K) {
+                        float4 e;
+                        e.x = x[kk].x - dv.x; e.y = x[kk].y - dv.y;
+                        e.z = x[kk].z - dv.z; e.w = x[kk].w - dv.w;
+                        if (ep.tl_on) {
+                            e.x = (tv.x - l[kk].x) + e.x; e.y = (tv.y - l[kk].y) + e.y;
+                            e.z = (tv.z - l[kk].z) + e.z; e.w = (tv.w - l[kk].w) + e.w;
+                        }
+                        *reinterpret_cast<float4 *>(ep.ef.p[k0 + kk] + off) = e;
+                    }
                 }
             }
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-                if (ok[v]) {
-                    float r = x[v] - d[v];
-                    if (ep.tl_on) r = (tv[v] - l[v]) + r;
-                    e[off[v]] = r;
-                }
-        }
-        if (ep.apply) {
-            float vv[16];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) vv[v] = ok[v] ? ep.vel[off[v]] : 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-                if (ok[v]) {
-                    const float vn = fmaf(ep.mu, vv[v], d[v]);
-                    ep.vel[off[v]] = vn;
-                    ep.theta[off[v]] = fmaf(-ep.lr, fmaf(ep.mu, vn, d[v]), tv[v]);
-                }
+            if (ep.apply) {
+                float4 vn, tn;
+                vn.x = fmaf(ep.mu, vv.x, dv.x); vn.y = fmaf(ep.mu, vv.y, dv.y);
+                vn.z = fmaf(ep.mu, vv.z, dv.z); vn.w = fmaf(ep.mu, vv.w, dv.w);
+                tn.x = fmaf(-ep.lr, fmaf(ep.mu, vn.x, dv.x), tv.x);
+                tn.y = fmaf(-ep.lr, fmaf(ep.mu, vn.y, dv.y), tv.y);
+                tn.z = fmaf(-ep.lr, fmaf(ep.mu, vn.z, dv.z), tv.z);
+                tn.w = fmaf(-ep.lr, fmaf(ep.mu, vn.w, dv.w), tv.w);
+                *reinterpret_cast<float4 *>(ep.vel + off) = vn;
+                *reinterpret_cast<float4 *>(ep.theta + off) = tn;
+            }
         }
     }
 }
@@ -595,13 +622,13 @@ size_t mfma_reconstruct_workspace_bytes(int mma, int64_t m, int64_t n, int r) {
 template <int NS>
 static int reconstruct_launch(int64_t m, int64_t n, int ks, const uint4 *pf, const uint4 *qf,
                               const ReconEpilogue &ep, hipStream_t st) {
-    // columns per workgroup: a multiple of 128, chosen for a few thousand workgroups
+    // columns per workgroup: a multiple of 256, chosen for a few thousand workgroups
     const int64_t rows = ceil_div(m, 32);
     int64_t chunks = ceil_div(4096, rows);
-    const int64_t max_chunks = ceil_div(n, 128);
+    const int64_t max_chunks = ceil_div(n, 256);
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
-    const int64_t cols = ceil_div(ceil_div(n, chunks), 128) * 128;
+    const int64_t cols = ceil_div(ceil_div(n, chunks), 256) * 256;
     const dim3 grid((unsigned)ceil_div(n, cols), (unsigned)rows);
     Timed timed(KID_RECONSTRUCT, st);
     hipLaunchKernelGGL(reconstruct_mfma_kernel<NS>, grid, dim3(kW), 0, st, pf, qf, ep, m, n, cols,

@@ -88,9 +88,10 @@ int launch_gram_partials(int64_t L, int r, const float *f, double *partials, hip
     return check_launch("gram_partials");
 }
 
-// One workgroup.  g (r x r fp64, global or LDS) <- sum of partials (upper triangle), scaled to
-// unit diagonal; right-looking Cholesky; w <- inverse of the factor, with the column scaling
-// folded in.  dead columns (pivot <= 1e-12, or zero norm) give a zero column of w.
+// One workgroup.  g (r rows of pitch r + 1, fp64, LDS or global) <- sum of the partials (upper
+// triangle), scaled to unit diagonal; right-looking Cholesky G = R^T R in place; in-place
+// inversion of R column by column; w <- diag(scale) R^-1.  A dead column (pivot <= 1e-12, i.e.
+// residual <= 1e-6 of the column norm, or zero norm) gives a zero row of R and a zero column of w.
 constexpr int kCT = 256;
 
 __global__ __launch_bounds__(kCT) void chol_inverse_kernel(const double *__restrict__ part,
@@ -98,58 +99,60 @@ __global__ __launch_bounds__(kCT) void chol_inverse_kernel(const double *__restr
                                                            double *__restrict__ g_global,
                                                            double *__restrict__ w, int g_in_lds) {
     extern __shared__ double smem[];
-    double *g = g_in_lds ? smem : g_global;              // r x r
+    double *g = g_in_lds ? smem : g_global;
+    const int rp = r + 1;                                // pitch: odd multiple avoids bank conflicts
     __shared__ double dscale[DLCX_MAX_RANK];             // 1 / column norm (0 for a zero column)
     __shared__ double dinv[DLCX_MAX_RANK];               // 1 / R_cc (0 for a dead column)
+    __shared__ double colbuf[DLCX_MAX_RANK];
     const int tid = threadIdx.x;
-    const int rr = r * r;
-    // sum of the partials in chunk order
-    for (int x = tid; x < rr; x += kCT) {
-        const int a = x / r, b = x % r;
-        double s = 0.0;
-        if (a <= b)
-            for (int c = 0; c < nchunks; ++c) s += part[(int64_t)c * rr + x];
-        g[x] = s;
-    }
+    const int ty = tid >> 4, tx = tid & 15;
+    for (int a = ty; a < r; a += 16)
+        for (int b = a + tx; b < r; b += 16) {  // sum of the partials in chunk order
+            double s = 0.0;
+            for (int c = 0; c < nchunks; ++c) s += part[(int64_t)c * r * r + a * r + b];
+            g[a * rp + b] = s;
+        }
     __syncthreads();
     for (int c = tid; c < r; c += kCT) {
-        const double d = g[c * r + c];
+        const double d = g[c * rp + c];
         dscale[c] = d > 0.0 ? 1.0 / sqrt(d) : 0.0;
     }
     __syncthreads();
-    for (int x = tid; x < rr; x += kCT) {
-        const int a = x / r, b = x % r;
-        if (a <= b) g[x] *= dscale[a] * dscale[b];
-    }
+    for (int a = ty; a < r; a += 16)
+        for (int b = a + tx; b < r; b += 16) g[a * rp + b] *= dscale[a] * dscale[b];
     __syncthreads();
-    // right-looking Cholesky on the upper triangle: row c of R overwrites row c of g
     for (int c = 0; c < r; ++c) {
-        const double piv = g[c * r + c];
+        const double piv = g[c * rp + c];
         const bool dead = !(piv > 1e-12);
         const double inv = dead ? 0.0 : 1.0 / sqrt(piv);
         __syncthreads();  // everyone has read the pivot
         if (tid == 0) dinv[c] = inv;
-        for (int j = c + tid; j < r; j += kCT) g[c * r + j] *= inv;  // dead: whole row -> 0
+        for (int j = c + tid; j < r; j += kCT) g[c * rp + j] *= inv;  // dead: whole row -> 0
         __syncthreads();
-        const int rem = r - c - 1;
-        for (int x = tid; x < rem * rem; x += kCT) {
-            const int i = c + 1 + x / rem, j = c + 1 + x % rem;
-            if (i <= j) g[i * r + j] -= g[c * r + i] * g[c * r + j];
+        for (int i = c + 1 + ty; i < r; i += 16) {
+            const double gi = g[c * rp + i];
+            for (int j = c + 1 + tx; j < r; j += 16)
+                if (i <= j) g[i * rp + j] -= gi * g[c * rp + j];
         }
         __syncthreads();
     }
-    // W' = R^-1 by back substitution, one column per thread; W = diag(dscale) W'
-    for (int j = tid; j < r; j += kCT) {
-        for (int k = r - 1; k > j; --k) w[k * r + j] = 0.0;
-        w[j * r + j] = dinv[j];
-        for (int k = j - 1; k >= 0; --k) {
+    // in-place inverse of the upper triangular R: column j from the inverted leading block
+    for (int j = 0; j < r; ++j) {
+        for (int l = tid; l < j; l += kCT) colbuf[l] = g[l * rp + j];
+        __syncthreads();
+        const double dj = dinv[j];
+        for (int i = tid; i < j; i += kCT) {
             double s = 0.0;
-            for (int l = k + 1; l <= j; ++l) s += g[k * r + l] * w[l * r + j];
-            w[k * r + j] = -dinv[k] * s;
+            for (int l = i; l < j; ++l) s = fma(g[i * rp + l], colbuf[l], s);
+            g[i * rp + j] = -dj * s;
         }
+        if (tid == 0) g[j * rp + j] = dj;
+        __syncthreads();
     }
-    __syncthreads();
-    for (int x = tid; x < rr; x += kCT) w[x] *= dscale[x / r];
+    for (int x = tid; x < r * r; x += kCT) {
+        const int k = x / r, j = x % r;
+        w[x] = k <= j ? dscale[k] * g[k * rp + j] : 0.0;
+    }
 }
 
 // P <- P W in place, fp64 accumulation.  Workgroup: 64 rows of P (= 64 consecutive elements of
@@ -176,16 +179,16 @@ __global__ __launch_bounds__(kGT) void apply_w_kernel(float *__restrict__ p, int
 }
 
 size_t orth_workspace_bytes(int64_t L, int r) {
-    // partials + g + w
-    return ((size_t)gram_chunks(L) + 2) * (size_t)r * r * sizeof(double);
+    // partials + g (pitch r + 1) + w
+    return ((size_t)gram_chunks(L) * r * r + (size_t)r * (r + 1) + (size_t)r * r) * sizeof(double);
 }
 
 static int cholqr_pass(int64_t L, int r, float *p, double *part, double *g, double *w,
                        hipStream_t st) {
     int rc = launch_gram_partials(L, r, p, part, st);
     if (rc != DLCX_OK) return rc;
-    const size_t g_bytes = (size_t)r * r * sizeof(double);
-    const int in_lds = g_bytes <= 128 * 1024 ? 1 : 0;
+    const size_t g_bytes = (size_t)r * (r + 1) * sizeof(double);
+    const int in_lds = g_bytes <= 140 * 1024 ? 1 : 0;
     if (in_lds && g_bytes > 48 * 1024) {
         rc = note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(chol_inverse_kernel),
                                           hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -216,7 +219,7 @@ static int cholqr_pass(int64_t L, int r, float *p, double *part, double *g, doub
 int launch_orthonormalize(int64_t L, int r, float *p_inout, void *workspace, hipStream_t st) {
     double *part = reinterpret_cast<double *>(workspace);
     double *g = part + (size_t)gram_chunks(L) * r * r;
-    double *w = g + (size_t)r * r;
+    double *w = g + (size_t)r * (r + 1);
     int rc = cholqr_pass(L, r, p_inout, part, g, w, st);
     if (rc != DLCX_OK) return rc;
     return cholqr_pass(L, r, p_inout, part, g, w, st);

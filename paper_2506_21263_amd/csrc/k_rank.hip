@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(const double *__restri
                 alpha = team_sum(alpha);
                 beta = team_sum(beta);
                 gamma = team_sum(gamma);
-                if (fabs(gamma) > 1e-15 * sqrt(alpha * beta) && gamma != 0.0) {
+                if (gamma * gamma > 1e-26 * alpha * beta) {
                     const double zeta = (beta - alpha) / (2.0 * gamma);
                     const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
                     const double cs = 1.0 / sqrt(1.0 + t * t), sn = cs * t;

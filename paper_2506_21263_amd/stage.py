@@ -1,21 +1,28 @@
 """Call sequence of one outer step (Alg. 2) for the matrices of a pipeline stage.
 
-Only sequencing lives here: which entry point of the HIP library runs on which buffers, in the
-order of Alg. 2 with the one-step delay.  Every arithmetic step is a kernel of libdlcx_hip.so.
+Only sequencing lives here: which entry point of the HIP library runs on which buffers and on
+which HIP stream, in the order of Alg. 2 with the one-step delay.  Every arithmetic step is a
+kernel of libdlcx_hip.so.
 
-    t >= 2 :  e_i <- delta_i - Delta_hat^{t-1}                 dlcx_decompress
-              delta_i <- (theta_g - theta_l,i) + e_i            dlcx_delta_ef
-    t >= 2 :  theta_g <- OuterOpt(theta_g, Delta_hat^{t-1})     dlcx_outer_nesterov
+    t >= 2 :  e_i <- delta_i - Delta_hat^{t-1}                 \\
+              delta_i <- (theta_g - theta_l,i) + e_i            > dlcx_ef_delta_apply (fused), or
+    t >= 2 :  theta_g <- OuterOpt(theta_g, Delta_hat^{t-1})    /  dlcx_decompress, dlcx_delta_ef,
+                                                                  dlcx_outer_nesterov
               P phase: compress, average (+ orthonormalise)     dlcx_compress_batched, dlcx_average
               Q phase: compress, average                        dlcx_compress_batched, dlcx_average
+              r' of the new average (Alg. 3)                    dlcx_effective_rank
+
+The matrices of a stage are independent, so they are dealt round-robin to a few HIP streams (all
+at the default priority): the short, latency-bound kernels of one matrix (Cholesky, Jacobi,
+quantiser) then run beside the HBM-bound sweeps of another.
 """
 import ctypes as C
 
 import torch
 
 from . import (PHASE_P, PHASE_Q, desc, dlcx_average, dlcx_compress_batched, dlcx_decompress,
-               dlcx_delta_ef, dlcx_ef_delta_apply, dlcx_outer_nesterov, dlcx_payload_bytes, dlcx_select_rank,
-               dlcx_select_rank_workspace_bytes, dlcx_workspace_bytes)
+               dlcx_delta_ef, dlcx_effective_rank, dlcx_ef_delta_apply, dlcx_outer_nesterov,
+               dlcx_payload_bytes, dlcx_select_rank_from, dlcx_workspace_bytes)
 
 
 class MatrixState:
@@ -54,76 +61,96 @@ class Stage:
     fused=True uses dlcx_ef_delta_apply (one pass for error buffers, pseudo-gradients and the
     outer update, the decompressed average never written); fused=False runs the separate entry
     points.  warm_start=True takes Q_bar of the previous round as the basis of the P phase.
+    streams > 1 deals the matrices to that many HIP streams.  measure_rank=True also launches
+    the effective-rank kernel of Alg. 3 for every matrix (results in self.rprime_dev).
     """
 
-    def __init__(self, matrices, lr, mu, fused=False, warm_start=False):
+    def __init__(self, matrices, lr, mu, fused=False, warm_start=False, streams=1,
+                 measure_rank=False, tau=0.99):
         self.mats = matrices
         self.lr, self.mu = lr, mu
         self.fused, self.warm_start = fused, warm_start
+        self.measure_rank, self.tau = measure_rank, tau
         self.t = 0
         dev = matrices[0].theta_g.device
+        self.nstreams = max(1, min(streams, len(matrices)))
         ws = max(m.workspace_bytes for m in matrices)
-        self.workspace = torch.empty(ws, device=dev, dtype=torch.uint8)
-        self.delta_hat = None
+        big = max(m.m * m.n for m in matrices)
+        self.workspaces = [torch.empty(ws, device=dev, dtype=torch.uint8)
+                           for _ in range(self.nstreams)]
+        self.workspace = self.workspaces[0]
+        self.delta_hats = [None] * self.nstreams
         if not fused:
-            big = max(m.m * m.n for m in matrices)
-            self.delta_hat = torch.empty(big, device=dev, dtype=torch.float32)
+            self.delta_hats = [torch.empty(big, device=dev, dtype=torch.float32)
+                               for _ in range(self.nstreams)]
+        self.side = [torch.cuda.Stream(device=dev) for _ in range(self.nstreams)] \
+            if self.nstreams > 1 else []
+        self.rprime_dev = torch.zeros(len(matrices), device=dev, dtype=torch.int32)
 
     def params(self):
         return sum(m.m * m.n for m in self.mats)
 
-    def step_matrix(self, M, theta_l, stream=None):
-        t = self.t
+    def step_matrix(self, a, theta_l, lane=0, stream=None):
+        M, t = self.mats[a], self.t
+        ws, d_hat = self.workspaces[lane], self.delta_hats[lane]
         if t >= 2 and self.fused:
             dlcx_ef_delta_apply(M.desc(M.r_prev), M.p_hat, M.q_bar, theta_l, M.ef, M.theta_g, M.v,
-                                self.lr, self.mu, workspace=self.workspace, stream=stream)
+                                self.lr, self.mu, workspace=ws, stream=stream)
         else:
             if t >= 2:
-                dlcx_decompress(M.desc(M.r_prev), M.p_hat, M.q_bar, self.delta_hat, M.ef,
-                                workspace=self.workspace, stream=stream)
+                dlcx_decompress(M.desc(M.r_prev), M.p_hat, M.q_bar, d_hat, M.ef, workspace=ws,
+                                stream=stream)
             for i in range(M.K):
                 dlcx_delta_ef(M.theta_g, theta_l[i], M.ef[i], stream=stream)
             if t >= 2:
-                dlcx_outer_nesterov(M.theta_g, M.v, self.delta_hat, self.lr, self.mu,
-                                    numel=M.m * M.n, stream=stream)
+                dlcx_outer_nesterov(M.theta_g, M.v, d_hat, self.lr, self.mu, numel=M.m * M.n,
+                                    stream=stream)
         d = M.desc()
         basis = M.q_bar if (self.warm_start and t >= 2 and M.r_prev == M.r) else M.q_in
-        dlcx_compress_batched(d, PHASE_P, M.ef, basis, M.codes_p, M.scales_p, self.workspace,
-                              stream=stream)
-        dlcx_average(d, PHASE_P, M.codes_p, M.scales_p, M.p_hat, self.workspace, stream=stream)
-        dlcx_compress_batched(d, PHASE_Q, M.ef, M.p_hat, M.codes_q, M.scales_q, self.workspace,
-                              stream=stream)
-        dlcx_average(d, PHASE_Q, M.codes_q, M.scales_q, M.q_bar, self.workspace, stream=stream)
+        dlcx_compress_batched(d, PHASE_P, M.ef, basis, M.codes_p, M.scales_p, ws, stream=stream)
+        dlcx_average(d, PHASE_P, M.codes_p, M.scales_p, M.p_hat, ws, stream=stream)
+        dlcx_compress_batched(d, PHASE_Q, M.ef, M.p_hat, M.codes_q, M.scales_q, ws, stream=stream)
+        dlcx_average(d, PHASE_Q, M.codes_q, M.scales_q, M.q_bar, ws, stream=stream)
         M.r_prev = M.r
+        if self.measure_rank:
+            dlcx_effective_rank(M.n, M.r, M.q_bar, self.tau, self.rprime_dev[a:], ws,
+                                stream=stream)
 
-    def step(self, theta_l_per_matrix, stream=None):
-        """theta_l_per_matrix[a][i]: local replica i of matrix a after this round's inner steps."""
+    def step(self, theta_l_per_matrix):
+        """theta_l_per_matrix[a][i]: local replica i of matrix a after this round's inner steps.
+        Work is issued on the current stream (and the side streams, joined before returning)."""
         self.t += 1
-        for M, tl in zip(self.mats, theta_l_per_matrix):
-            self.step_matrix(M, tl, stream=stream)
+        if self.nstreams == 1:
+            for a in range(len(self.mats)):
+                self.step_matrix(a, theta_l_per_matrix[a])
+            return
+        main = torch.cuda.current_stream()
+        start = torch.cuda.Event()
+        start.record(main)
+        for s in self.side:
+            s.wait_event(start)
+        for a in range(len(self.mats)):
+            lane = a % self.nstreams
+            self.step_matrix(a, theta_l_per_matrix[a], lane=lane, stream=self.side[lane])
+        for s in self.side:
+            done = torch.cuda.Event()
+            done.record(s)
+            main.wait_event(done)
 
 
 class RankSelector:
-    """Alg. 3 for a stage: measures r' on the latest Q_bar of every matrix, keeps the window."""
+    """Alg. 3 for a stage: window rule over the r' values the stage measured (measure_rank)."""
 
-    def __init__(self, stage, c, r1, rmin, rmax, H1, tau=0.99):
-        self.stage, self.c, self.r1, self.rmin, self.rmax, self.H1, self.tau = \
-            stage, c, r1, rmin, rmax, H1, tau
+    def __init__(self, stage, c, r1, rmin, rmax, H1):
+        self.stage, self.c, self.r1, self.rmin, self.rmax, self.H1 = stage, c, r1, rmin, rmax, H1
         self.hist = (C.c_int32 * c)()
-        descs = [M.desc(M.r_max) for M in stage.mats]
-        nbytes = dlcx_select_rank_workspace_bytes(descs)
-        self.workspace = torch.empty(nbytes, device=stage.mats[0].theta_g.device,
-                                     dtype=torch.uint8)
 
     def first(self):
         """t = 1: r'_1 is defined as r_1."""
-        return dlcx_select_rank([], [], self.tau, self.hist, 1, self.c, self.r1, self.rmin,
-                                self.rmax, self.H1, rprime=self.r1)
+        return dlcx_select_rank_from(None, 0, self.hist, 1, self.c, self.r1, self.rmin, self.rmax,
+                                     self.H1, rprime=self.r1)
 
-    def next(self, t, stream=None):
-        """Rank for outer step t >= 2 from the averages of step t-1."""
-        descs = [M.desc(M.r_prev) for M in self.stage.mats]
-        q_bars = [M.q_bar for M in self.stage.mats]
-        return dlcx_select_rank(descs, q_bars, self.tau, self.hist, t, self.c, self.r1,
-                                self.rmin, self.rmax, self.H1, workspace=self.workspace,
-                                stream=stream)
+    def next(self, t):
+        """Rank for outer step t >= 2 from the averages of step t-1 (synchronises)."""
+        return dlcx_select_rank_from(self.stage.rprime_dev, len(self.stage.mats), self.hist, t,
+                                     self.c, self.r1, self.rmin, self.rmax, self.H1)

@@ -145,7 +145,7 @@ def test_free_running_stage_driver(case, mma, fused):
                              theta_l=kind)
     orc = pipeline.MatrixOracle(inp.theta_g, K, inp.q_in, qbits, group, synth.LR, synth.MU)
     M = MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), qbits, group, mma)
-    st = Stage([M], synth.LR, synth.MU, fused=fused, warm_start=True)
+    st = Stage([M], synth.LR, synth.MU, fused=fused, warm_start=True, measure_rank=True)
     tol = TOL[mma]
     flipped = False
     sum_g = [np.zeros((m, n)) for _ in range(K)]
@@ -177,7 +177,37 @@ def test_free_running_stage_driver(case, mma, fused):
         assert rel_l2(to_np(M.theta_g), orc.theta) <= 2e-2, (name, t)  # sanity bar after a flip
         orc.set_basis(orc.q_bar)
     assert st.t == T and orc.n_applied == T - 1
+    if not flipped:
+        assert int(st.rprime_dev[0].item()) == ref.effective_rank(orc.q_bar, 0.99)
     # error feedback telescopes on the GPU's own outputs, flips or not
     for i in range(K):
         e_next = to_np(M.ef[i]).astype(np.float64) - to_np(d_hat)
         assert rel_l2(sum_d + e_next, sum_g[i]) <= 1e-6 * T
+
+
+def test_multi_stream_stage_equals_single_stream():
+    # dealing the matrices of a stage to several HIP streams changes nothing: bitwise-equal state
+    shapes = [(256, 384), (512, 256), (384, 640), (256, 256), (640, 384)]
+    K, r = 3, 16
+
+    def run(streams):
+        mats, tls = [], []
+        for a, (m, n) in enumerate(shapes):
+            inp = synth.MatrixInputs(m, n, K, r, seed=500 + a, sigma=1e-3, alpha=1.0, theta_l="bf16")
+            mats.append(MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), 4, 64, dlcx.MMA_BF16))
+            tls.append([to_dev(inp.theta_local(inp.theta_g, 1, i)) for i in range(K)])
+        st = Stage(mats, synth.LR, synth.MU, fused=True, warm_start=True, streams=streams,
+                   measure_rank=True)
+        for _ in range(3):
+            st.step(tls)
+        torch.cuda.synchronize()
+        return st
+
+    one, three = run(1), run(3)
+    assert three.nstreams == 3
+    for A, B in zip(one.mats, three.mats):
+        assert torch.equal(A.theta_g, B.theta_g) and torch.equal(A.v, B.v)
+        assert torch.equal(A.q_bar, B.q_bar) and torch.equal(A.p_hat, B.p_hat)
+        for x, y in zip(A.ef, B.ef):
+            assert torch.equal(x, y)
+    assert torch.equal(one.rprime_dev, three.rprime_dev)
