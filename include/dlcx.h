@@ -172,6 +172,17 @@ int dlcx_dequant_average(int K, const uint8_t *const *codes_host,
  * in place.  A column whose component orthogonal to the earlier columns is at most 1e-6 of
  * its norm (or that is zero) becomes the zero column. */
 int dlcx_orthonormalize(int64_t L, int32_t r, float *p_inout, void *workspace, void *stream);
+/* The orthonormalisation and the effective rank for ALL matrices of a stage at once (these
+ * steps are short and latency-bound per matrix; batched, each matrix gets its own workgroups of
+ * one launch).  Matrix i has shape descs_host[i]; p_inout_host[i] is its r x m factor,
+ * q_bars_host[i] its r x n factor; rprime_out_dev receives n_matrices ints.  The workspace
+ * (dlcx_batched_workspace_bytes) serves either call. */
+size_t dlcx_batched_workspace_bytes(const dlcx_desc *descs_host, int n_matrices);
+int dlcx_orthonormalize_batched(const dlcx_desc *descs_host, float *const *p_inout_host,
+                                int n_matrices, void *workspace, void *stream);
+int dlcx_effective_rank_batched(const dlcx_desc *descs_host, const float *const *q_bars_host,
+                                int n_matrices, double tau, int32_t *rprime_out_dev,
+                                void *workspace, void *stream);
 /* r' of one matrix, written to a DEVICE int32 (0 when Q_bar is all zero); asynchronous. */
 int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,
                         int32_t *rprime_out_dev, void *workspace, void *stream);

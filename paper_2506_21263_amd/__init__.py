@@ -55,6 +55,9 @@ SYMBOLS = {
                                 _i32, _vp, _vp, _vp, _vp, _vp]),
     "dlcx_select_rank_from": (_int, [_vp, _int, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp,
                                      _vp]),
+    "dlcx_batched_workspace_bytes": (C.c_size_t, [_dp, _int]),
+    "dlcx_orthonormalize_batched": (_int, [_dp, _vp, _int, _vp, _vp]),
+    "dlcx_effective_rank_batched": (_int, [_dp, _vp, _int, C.c_double, _vp, _vp, _vp]),
     "dlcx_payload_bytes": (C.c_size_t, [_dp, _int, _vp, _vp]),
     "dlcx_workspace_bytes": (C.c_size_t, [_dp, _int]),
     "dlcx_select_rank_workspace_bytes": (C.c_size_t, [_dp, _int]),
@@ -215,6 +218,26 @@ def dlcx_select_rank_from(rprime_dev, n, rprime_hist, t, c, r1, rmin, rmax, H1, 
                                        C.addressof(rp), C.addressof(r_next), C.addressof(h_next),
                                        _stream(stream) if n else None), "dlcx_select_rank_from")
     return rp.value, r_next.value, h_next.value
+
+
+def dlcx_batched_workspace_bytes(descs):
+    arr = (Desc * max(len(descs), 1))(*descs)
+    return lib().dlcx_batched_workspace_bytes(arr, len(descs))
+
+
+def dlcx_orthonormalize_batched(descs, p_inout, workspace, stream=None):
+    arr = (Desc * max(len(descs), 1))(*descs)
+    pp, keep = _ptr_array(list(p_inout))
+    _check(lib().dlcx_orthonormalize_batched(arr, pp, len(descs), _ptr(workspace), _stream(stream)),
+           "dlcx_orthonormalize_batched")
+
+
+def dlcx_effective_rank_batched(descs, q_bars, tau, rprime_out_dev, workspace, stream=None):
+    arr = (Desc * max(len(descs), 1))(*descs)
+    qp, keep = _ptr_array(list(q_bars))
+    _check(lib().dlcx_effective_rank_batched(arr, qp, len(descs), tau, _ptr(rprime_out_dev),
+                                             _ptr(workspace), _stream(stream)),
+           "dlcx_effective_rank_batched")
 
 
 def dlcx_project(d, phase, deltas, basis, factors_out, workspace, stream=None):

@@ -85,13 +85,34 @@ size_t project_workspace_bytes(int mma, int64_t m, int64_t n, int r, int K);
 size_t reconstruct_workspace_bytes(int mma, int64_t m, int64_t n, int r);
 
 // ---- orthonormalisation and effective rank (k_orth.hip, k_rank.hip) ---------------------
+inline size_t a256x(size_t x) { return (x + 255) & ~(size_t)255; }
+// One r x L factor and its fp64 scratch; a batch of them is passed to a kernel by value.
+constexpr int kMaxBatch = 64;
+struct FactorItem {
+    float *f;        // the factor (read by the Gram kernel, rewritten by apply_w)
+    int64_t L;
+    int32_t r, nchunks;
+    double *part;    // nchunks x r x r partial Gram sums (upper triangles)
+    double *g;       // r x (r + 1): Cholesky scratch, or the Jacobi matrix
+    double *w;       // r x r: inverse factor (orthonormalisation only)
+    int32_t *out;    // r' (effective rank only)
+};
+struct FactorBatch {
+    int n;
+    FactorItem it[kMaxBatch];
+};
 size_t orth_workspace_bytes(int64_t L, int r);
+void orth_item(FactorItem *it, float *p, int64_t L, int r, void *workspace);
 int launch_orthonormalize(int64_t L, int r, float *p_inout, void *workspace, hipStream_t st);
+int launch_orthonormalize_batch(const FactorBatch &batch, hipStream_t st);
 size_t effrank_workspace_bytes(int64_t L, int r);
+void effrank_item(FactorItem *it, const float *q_bar, int64_t L, int r, int32_t *out,
+                  void *workspace);
 int launch_effective_rank(int64_t L, int r, const float *q_bar, double tau, int32_t *rprime_dev,
                           void *workspace, hipStream_t st);
-// fp64 Gram matrix partials of an r x L factor: part[chunk][a][b] for a <= b (others untouched)
+int launch_effective_rank_batch(const FactorBatch &batch, double tau, hipStream_t st);
+// fp64 Gram matrix partials of r x L factors: part[chunk][a][b] for a <= b (others untouched)
 int gram_chunks(int64_t L);
-int launch_gram_partials(int64_t L, int r, const float *f, double *partials, hipStream_t st);
+int launch_gram_partials_batch(const FactorBatch &batch, hipStream_t st);
 
 }  // namespace dlcx

@@ -196,7 +196,7 @@ size_t dlcx_select_rank_workspace_bytes(const dlcx_desc *descs, int n_matrices) 
     size_t total = align256((size_t)(n_matrices > 0 ? n_matrices : 1) * sizeof(int32_t));
     for (int i = 0; i < n_matrices; ++i) {
         if (check_desc(&descs[i]) != DLCX_OK) return 0;
-        total += align256(effrank_workspace_bytes(descs[i].n, descs[i].r));
+        total += effrank_workspace_bytes(descs[i].n, descs[i].r);
     }
     return total;
 }
@@ -414,6 +414,70 @@ int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,
     return launch_effective_rank(L, r, q_bar, tau, rprime_out_dev, workspace, as_stream(stream));
 }
 
+size_t dlcx_batched_workspace_bytes(const dlcx_desc *descs_host, int n_matrices) {
+    if (n_matrices < 0 || (n_matrices > 0 && !descs_host)) return 0;
+    size_t total = 0;
+    for (int i = 0; i < n_matrices; ++i) {
+        if (check_desc(&descs_host[i]) != DLCX_OK) return 0;
+        const size_t a = orth_workspace_bytes(descs_host[i].m, descs_host[i].r);
+        const size_t b = effrank_workspace_bytes(descs_host[i].n, descs_host[i].r);
+        total += a > b ? a : b;
+    }
+    return total;
+}
+
+int dlcx_orthonormalize_batched(const dlcx_desc *descs_host, float *const *p_inout_host,
+                                int n_matrices, void *workspace, void *stream) {
+    if (n_matrices < 0) return DLCX_EINVAL;
+    if (n_matrices == 0) return DLCX_OK;
+    if (!descs_host || !p_inout_host || !workspace || !aligned16(workspace)) return DLCX_EINVAL;
+    for (int i = 0; i < n_matrices; ++i) {
+        if (check_desc(&descs_host[i]) != DLCX_OK) return DLCX_EINVAL;
+        if (!p_inout_host[i] || !aligned16(p_inout_host[i])) return DLCX_EINVAL;
+    }
+    char *ws = reinterpret_cast<char *>(workspace);
+    for (int i0 = 0; i0 < n_matrices; i0 += kMaxBatch) {
+        FactorBatch b;
+        b.n = n_matrices - i0 < kMaxBatch ? n_matrices - i0 : kMaxBatch;
+        for (int i = 0; i < b.n; ++i) {
+            const dlcx_desc &d = descs_host[i0 + i];
+            orth_item(&b.it[i], p_inout_host[i0 + i], d.m, d.r, ws);
+            b.it[i].out = nullptr;
+            ws += orth_workspace_bytes(d.m, d.r);
+        }
+        int rc = launch_orthonormalize_batch(b, as_stream(stream));
+        if (rc != DLCX_OK) return rc;
+    }
+    return DLCX_OK;
+}
+
+int dlcx_effective_rank_batched(const dlcx_desc *descs_host, const float *const *q_bars_host,
+                                int n_matrices, double tau, int32_t *rprime_out_dev,
+                                void *workspace, void *stream) {
+    if (n_matrices < 0) return DLCX_EINVAL;
+    if (n_matrices == 0) return DLCX_OK;
+    if (!descs_host || !q_bars_host || !rprime_out_dev || !workspace || !aligned16(workspace))
+        return DLCX_EINVAL;
+    if (!(tau > 0.0 && tau <= 1.0)) return DLCX_EINVAL;
+    for (int i = 0; i < n_matrices; ++i) {
+        if (check_desc(&descs_host[i]) != DLCX_OK) return DLCX_EINVAL;
+        if (!q_bars_host[i] || !aligned16(q_bars_host[i])) return DLCX_EINVAL;
+    }
+    char *ws = reinterpret_cast<char *>(workspace);
+    for (int i0 = 0; i0 < n_matrices; i0 += kMaxBatch) {
+        FactorBatch b;
+        b.n = n_matrices - i0 < kMaxBatch ? n_matrices - i0 : kMaxBatch;
+        for (int i = 0; i < b.n; ++i) {
+            const dlcx_desc &d = descs_host[i0 + i];
+            effrank_item(&b.it[i], q_bars_host[i0 + i], d.n, d.r, rprime_out_dev + i0 + i, ws);
+            ws += effrank_workspace_bytes(d.n, d.r);
+        }
+        int rc = launch_effective_rank_batch(b, tau, as_stream(stream));
+        if (rc != DLCX_OK) return rc;
+    }
+    return DLCX_OK;
+}
+
 static int window_rule(int32_t rprime, int32_t *hist, int32_t t, int32_t c, int32_t r1,
                        int32_t rmin, int32_t rmax, int32_t H1, int32_t *r_next, int32_t *H_next) {
     hist[(t - 1) % c] = rprime;
@@ -480,12 +544,9 @@ int dlcx_select_rank(const dlcx_desc *descs_host, const float *const *q_bars_hos
         }
         out_dev = reinterpret_cast<int32_t *>(workspace);
         char *ws = reinterpret_cast<char *>(workspace) + align256((size_t)n_matrices * sizeof(int32_t));
-        for (int i = 0; i < n_matrices; ++i) {
-            int rc = launch_effective_rank(descs_host[i].n, descs_host[i].r, q_bars_host[i], tau,
-                                           out_dev + i, ws, as_stream(stream));
-            if (rc != DLCX_OK) return rc;
-            ws += align256(effrank_workspace_bytes(descs_host[i].n, descs_host[i].r));
-        }
+        int rc = dlcx_effective_rank_batched(descs_host, q_bars_host, n_matrices, tau, out_dev, ws,
+                                             stream);
+        if (rc != DLCX_OK) return rc;
     }
     return dlcx_select_rank_from(out_dev, n_matrices, rprime_hist_host, t, c, r1, rmin, rmax, H1,
                                  rprime_inout_host, r_next_out_host, H_next_out_host, stream);

@@ -8,6 +8,10 @@
 // insensitive to the very different column norms a warm-started basis produces.  A pivot of the
 // scaled matrix is (residual norm / column norm)^2, so the rule "residual <= 1e-6 of the column
 // norm => zero column" is a comparison of the pivot with 1e-12.
+//
+// Every kernel here takes a batch of factors (one descriptor per matrix, passed by value): the
+// work per matrix is small and latency-bound, so the matrices of a stage go through each step
+// together, one workgroup (or one slice of the grid) per matrix.
 #include "common.h"
 
 namespace dlcx {
@@ -18,12 +22,17 @@ constexpr int kGT = 256;
 int gram_chunks(int64_t L) { return (int)ceil_div(L, kGramChunk); }
 
 // part[chunk][a][b] = sum_{i in chunk} f[a][i] * f[b][i] for the 64 x 64 tile (ta, tb), ta <= tb.
-__global__ __launch_bounds__(kGT) void gram_partial_kernel(const float *__restrict__ f, int64_t L,
-                                                           int r, double *__restrict__ part) {
+__global__ __launch_bounds__(kGT) void gram_partial_kernel(FactorBatch batch) {
     __shared__ float at[16][64 + 4];
     __shared__ float bt[16][64 + 4];
+    const FactorItem it = batch.it[blockIdx.z];
+    const float *__restrict__ f = it.f;
+    const int64_t L = it.L;
+    const int r = it.r;
+    const int nt = (r + 63) / 64;
+    if ((int)blockIdx.x >= it.nchunks || (int)blockIdx.y >= nt * (nt + 1) / 2) return;
     // tile index -> (ta, tb) with ta <= tb
-    int t = blockIdx.y, ta = 0, nt = (r + 63) / 64;
+    int t = blockIdx.y, ta = 0;
     while (t >= nt - ta) {
         t -= nt - ta;
         ++ta;
@@ -70,7 +79,7 @@ __global__ __launch_bounds__(kGT) void gram_partial_kernel(const float *__restri
         }
         __syncthreads();
     }
-    double *dst = part + (int64_t)blockIdx.x * r * r;
+    double *dst = it.part + (int64_t)blockIdx.x * r * r;
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
@@ -80,27 +89,36 @@ __global__ __launch_bounds__(kGT) void gram_partial_kernel(const float *__restri
         }
 }
 
-int launch_gram_partials(int64_t L, int r, const float *f, double *partials, hipStream_t st) {
-    const int nt = (r + 63) / 64;
-    const dim3 grid((unsigned)gram_chunks(L), (unsigned)(nt * (nt + 1) / 2));
+int launch_gram_partials_batch(const FactorBatch &batch, hipStream_t st) {
+    int max_chunks = 1, max_tiles = 1;
+    for (int i = 0; i < batch.n; ++i) {
+        const int nt = (batch.it[i].r + 63) / 64;
+        if (batch.it[i].nchunks > max_chunks) max_chunks = batch.it[i].nchunks;
+        if (nt * (nt + 1) / 2 > max_tiles) max_tiles = nt * (nt + 1) / 2;
+    }
+    const dim3 grid((unsigned)max_chunks, (unsigned)max_tiles, (unsigned)batch.n);
     Timed timed(KID_GRAM, st);
-    hipLaunchKernelGGL(gram_partial_kernel, grid, dim3(kGT), 0, st, f, L, r, partials);
+    hipLaunchKernelGGL(gram_partial_kernel, grid, dim3(kGT), 0, st, batch);
     return check_launch("gram_partials");
 }
 
-// One workgroup.  g (r rows of pitch r + 1, fp64, LDS or global) <- sum of the partials (upper
-// triangle), scaled to unit diagonal; right-looking Cholesky G = R^T R in place; in-place
-// inversion of R column by column; w <- diag(scale) R^-1.  A dead column (pivot <= 1e-12, i.e.
-// residual <= 1e-6 of the column norm, or zero norm) gives a zero row of R and a zero column of w.
+// One workgroup per matrix.  g (r rows of pitch r + 1, fp64, LDS or global) <- sum of the
+// partials (upper triangle), scaled to unit diagonal; right-looking Cholesky G = R^T R in place;
+// in-place inversion of R column by column; w <- diag(scale) R^-1.  A dead column (pivot <=
+// 1e-12, i.e. residual <= 1e-6 of the column norm, or zero norm) gives a zero row of R and a zero
+// column of w.
 constexpr int kCT = 256;
+constexpr size_t kCholLdsMax = 140 * 1024;
 
-__global__ __launch_bounds__(kCT) void chol_inverse_kernel(const double *__restrict__ part,
-                                                           int nchunks, int r,
-                                                           double *__restrict__ g_global,
-                                                           double *__restrict__ w, int g_in_lds) {
+__global__ __launch_bounds__(kCT) void chol_inverse_kernel(FactorBatch batch) {
     extern __shared__ double smem[];
-    double *g = g_in_lds ? smem : g_global;
-    const int rp = r + 1;                                // pitch: odd multiple avoids bank conflicts
+    const FactorItem it = batch.it[blockIdx.x];
+    const int r = it.r, nchunks = it.nchunks;
+    const int rp = r + 1;                                // odd pitch avoids LDS bank conflicts
+    const bool in_lds = (size_t)r * rp * sizeof(double) <= kCholLdsMax;
+    double *g = in_lds ? smem : it.g;
+    const double *__restrict__ part = it.part;
+    double *__restrict__ w = it.w;
     __shared__ double dscale[DLCX_MAX_RANK];             // 1 / column norm (0 for a zero column)
     __shared__ double dinv[DLCX_MAX_RANK];               // 1 / R_cc (0 for a dead column)
     __shared__ double colbuf[DLCX_MAX_RANK];
@@ -158,10 +176,15 @@ __global__ __launch_bounds__(kCT) void chol_inverse_kernel(const double *__restr
 // P <- P W in place, fp64 accumulation.  Workgroup: 64 rows of P (= 64 consecutive elements of
 // every factor column) staged in LDS; thread (row, wave) produces the columns c = wave, wave+4,..
 // W is upper triangular: column c needs rows k <= c only.
-__global__ __launch_bounds__(kGT) void apply_w_kernel(float *__restrict__ p, int64_t L, int r,
-                                                      const double *__restrict__ w) {
+__global__ __launch_bounds__(kGT) void apply_w_kernel(FactorBatch batch) {
     extern __shared__ float fl[];  // [r][64]
+    const FactorItem it = batch.it[blockIdx.y];
+    float *__restrict__ p = it.f;
+    const double *__restrict__ w = it.w;
+    const int64_t L = it.L;
+    const int r = it.r;
     const int64_t i0 = (int64_t)blockIdx.x * 64;
+    if (i0 >= L) return;
     for (int idx = threadIdx.x; idx < r * 16; idx += kGT) {
         const int c = idx >> 4, c4 = idx & 15;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -180,49 +203,73 @@ __global__ __launch_bounds__(kGT) void apply_w_kernel(float *__restrict__ p, int
 
 size_t orth_workspace_bytes(int64_t L, int r) {
     // partials + g (pitch r + 1) + w
-    return ((size_t)gram_chunks(L) * r * r + (size_t)r * (r + 1) + (size_t)r * r) * sizeof(double);
+    return a256x(((size_t)gram_chunks(L) * r * r + (size_t)r * (r + 1) + (size_t)r * r) *
+                 sizeof(double));
 }
 
-static int cholqr_pass(int64_t L, int r, float *p, double *part, double *g, double *w,
-                       hipStream_t st) {
-    int rc = launch_gram_partials(L, r, p, part, st);
+static int set_lds_limit(const void *kernel, size_t bytes, size_t *granted, const char *what) {
+    if (bytes <= 48 * 1024 || bytes <= *granted) return DLCX_OK;
+    int rc = note_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)bytes), what);
+    if (rc == DLCX_OK) *granted = bytes;
+    return rc;
+}
+
+static int cholqr_pass(const FactorBatch &batch, hipStream_t st) {
+    int rc = launch_gram_partials_batch(batch, st);
     if (rc != DLCX_OK) return rc;
-    const size_t g_bytes = (size_t)r * (r + 1) * sizeof(double);
-    const int in_lds = g_bytes <= 140 * 1024 ? 1 : 0;
-    if (in_lds && g_bytes > 48 * 1024) {
-        rc = note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(chol_inverse_kernel),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize,
-                                          (int)g_bytes),
-                      "chol_inverse attribute");
-        if (rc != DLCX_OK) return rc;
+    size_t g_bytes = 0, a_bytes = 0;
+    int64_t max_rows = 1;
+    for (int i = 0; i < batch.n; ++i) {
+        const size_t r = (size_t)batch.it[i].r;
+        const size_t gb = r * (r + 1) * sizeof(double);
+        if (gb <= kCholLdsMax && gb > g_bytes) g_bytes = gb;
+        if (r * 64 * sizeof(float) > a_bytes) a_bytes = r * 64 * sizeof(float);
+        if (ceil_div(batch.it[i].L, 64) > max_rows) max_rows = ceil_div(batch.it[i].L, 64);
     }
+    static size_t chol_granted = 0, apply_granted = 0;
+    rc = set_lds_limit(reinterpret_cast<const void *>(chol_inverse_kernel), g_bytes, &chol_granted,
+                       "chol_inverse attribute");
+    if (rc != DLCX_OK) return rc;
     {
         Timed timed(KID_CHOL, st);
-        hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(kCT), in_lds ? g_bytes : 0, st, part,
-                           gram_chunks(L), r, g, w, in_lds);
+        hipLaunchKernelGGL(chol_inverse_kernel, dim3((unsigned)batch.n), dim3(kCT), g_bytes, st,
+                           batch);
         rc = check_launch("chol_inverse");
     }
     if (rc != DLCX_OK) return rc;
-    const size_t lds = (size_t)r * 64 * sizeof(float);
-    if (lds > 48 * 1024) {
-        rc = note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(apply_w_kernel),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
-                      "apply_w attribute");
-        if (rc != DLCX_OK) return rc;
-    }
+    rc = set_lds_limit(reinterpret_cast<const void *>(apply_w_kernel), a_bytes, &apply_granted,
+                       "apply_w attribute");
+    if (rc != DLCX_OK) return rc;
     Timed timed(KID_APPLY_W, st);
-    hipLaunchKernelGGL(apply_w_kernel, dim3((unsigned)ceil_div(L, 64)), dim3(kGT), lds, st, p, L, r,
-                       w);
+    hipLaunchKernelGGL(apply_w_kernel, dim3((unsigned)max_rows, (unsigned)batch.n), dim3(kGT),
+                       a_bytes, st, batch);
     return check_launch("apply_w");
 }
 
-int launch_orthonormalize(int64_t L, int r, float *p_inout, void *workspace, hipStream_t st) {
-    double *part = reinterpret_cast<double *>(workspace);
-    double *g = part + (size_t)gram_chunks(L) * r * r;
-    double *w = g + (size_t)r * (r + 1);
-    int rc = cholqr_pass(L, r, p_inout, part, g, w, st);
+// Fills the scratch pointers of item i from a workspace of orth_workspace_bytes(L, r) bytes.
+void orth_item(FactorItem *it, float *p, int64_t L, int r, void *workspace) {
+    it->f = p;
+    it->L = L;
+    it->r = r;
+    it->nchunks = gram_chunks(L);
+    it->part = reinterpret_cast<double *>(workspace);
+    it->g = it->part + (size_t)it->nchunks * r * r;
+    it->w = it->g + (size_t)r * (r + 1);
+}
+
+int launch_orthonormalize_batch(const FactorBatch &batch, hipStream_t st) {
+    if (batch.n == 0) return DLCX_OK;
+    int rc = cholqr_pass(batch, st);
     if (rc != DLCX_OK) return rc;
-    return cholqr_pass(L, r, p_inout, part, g, w, st);
+    return cholqr_pass(batch, st);
+}
+
+int launch_orthonormalize(int64_t L, int r, float *p_inout, void *workspace, hipStream_t st) {
+    FactorBatch b;
+    b.n = 1;
+    orth_item(&b.it[0], p_inout, L, r, workspace);
+    return launch_orthonormalize_batch(b, st);
 }
 
 }  // namespace dlcx

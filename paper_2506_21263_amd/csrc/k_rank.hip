@@ -18,14 +18,17 @@ __device__ __forceinline__ double team_sum(double v) {
     return v;
 }
 
-__global__ __launch_bounds__(kJT) void jacobi_rank_kernel(const double *__restrict__ part,
-                                                          int nchunks, int r, double tau,
-                                                          double *__restrict__ a_global,
-                                                          int a_in_lds,
-                                                          int32_t *__restrict__ rprime_out) {
+constexpr size_t kJacobiLdsMax = 140 * 1024;
+
+__global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, double tau) {
     extern __shared__ double smem[];
+    const FactorItem it = batch.it[blockIdx.x];
+    const int r = it.r, nchunks = it.nchunks;
+    const double *__restrict__ part = it.part;
+    int32_t *__restrict__ rprime_out = it.out;
     const int re = (r + 1) & ~1;                     // even number of columns (pad with zeros)
-    double *a = a_in_lds ? smem : a_global;          // column-major re x re: a[col * re + row]
+    const bool a_in_lds = (size_t)re * re * sizeof(double) <= kJacobiLdsMax;
+    double *a = a_in_lds ? smem : it.g;              // column-major re x re: a[col * re + row]
     __shared__ double eig[DLCX_MAX_RANK];
     __shared__ double sorted[DLCX_MAX_RANK];
     __shared__ int rotated;
@@ -120,28 +123,51 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(const double *__restri
 
 size_t effrank_workspace_bytes(int64_t L, int r) {
     const size_t re = (size_t)((r + 1) & ~1);
-    return (size_t)gram_chunks(L) * r * r * sizeof(double) + re * re * sizeof(double);
+    return a256x(((size_t)gram_chunks(L) * r * r + re * re) * sizeof(double));
 }
 
-int launch_effective_rank(int64_t L, int r, const float *q_bar, double tau, int32_t *rprime_dev,
-                          void *workspace, hipStream_t st) {
-    double *part = reinterpret_cast<double *>(workspace);
-    double *a = part + (size_t)gram_chunks(L) * r * r;
-    int rc = launch_gram_partials(L, r, q_bar, part, st);
+void effrank_item(FactorItem *it, const float *q_bar, int64_t L, int r, int32_t *out,
+                  void *workspace) {
+    it->f = const_cast<float *>(q_bar);  // only read
+    it->L = L;
+    it->r = r;
+    it->nchunks = gram_chunks(L);
+    it->part = reinterpret_cast<double *>(workspace);
+    it->g = it->part + (size_t)it->nchunks * r * r;
+    it->w = nullptr;
+    it->out = out;
+}
+
+int launch_effective_rank_batch(const FactorBatch &batch, double tau, hipStream_t st) {
+    if (batch.n == 0) return DLCX_OK;
+    int rc = launch_gram_partials_batch(batch, st);
     if (rc != DLCX_OK) return rc;
-    const size_t re = (size_t)((r + 1) & ~1);
-    const size_t bytes = re * re * sizeof(double);
-    const int in_lds = bytes <= 128 * 1024 ? 1 : 0;
-    if (in_lds && bytes > 48 * 1024) {
+    size_t bytes = 0;
+    for (int i = 0; i < batch.n; ++i) {
+        const size_t re = (size_t)((batch.it[i].r + 1) & ~1);
+        const size_t b = re * re * sizeof(double);
+        if (b <= kJacobiLdsMax && b > bytes) bytes = b;
+    }
+    static size_t granted = 0;
+    if (bytes > 48 * 1024 && bytes > granted) {
         rc = note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(jacobi_rank_kernel),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes),
                       "jacobi attribute");
         if (rc != DLCX_OK) return rc;
+        granted = bytes;
     }
     Timed timed(KID_JACOBI, st);
-    hipLaunchKernelGGL(jacobi_rank_kernel, dim3(1), dim3(kJT), in_lds ? bytes : 0, st, part,
-                       gram_chunks(L), r, tau, a, in_lds, rprime_dev);
+    hipLaunchKernelGGL(jacobi_rank_kernel, dim3((unsigned)batch.n), dim3(kJT), bytes, st, batch,
+                       tau);
     return check_launch("jacobi_rank");
+}
+
+int launch_effective_rank(int64_t L, int r, const float *q_bar, double tau, int32_t *rprime_dev,
+                          void *workspace, hipStream_t st) {
+    FactorBatch b;
+    b.n = 1;
+    effrank_item(&b.it[0], q_bar, L, r, rprime_dev, workspace);
+    return launch_effective_rank_batch(b, tau, st);
 }
 
 }  // namespace dlcx

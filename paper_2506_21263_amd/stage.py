@@ -20,9 +20,11 @@ import ctypes as C
 
 import torch
 
-from . import (PHASE_P, PHASE_Q, desc, dlcx_average, dlcx_compress_batched, dlcx_decompress,
-               dlcx_delta_ef, dlcx_effective_rank, dlcx_ef_delta_apply, dlcx_outer_nesterov,
-               dlcx_payload_bytes, dlcx_select_rank_from, dlcx_workspace_bytes)
+from . import (PHASE_P, PHASE_Q, desc, dlcx_average, dlcx_batched_workspace_bytes,
+               dlcx_compress_batched, dlcx_decompress, dlcx_delta_ef, dlcx_dequant_average,
+               dlcx_effective_rank, dlcx_effective_rank_batched, dlcx_ef_delta_apply,
+               dlcx_orthonormalize_batched, dlcx_outer_nesterov, dlcx_payload_bytes,
+               dlcx_select_rank_from, dlcx_workspace_bytes)
 
 
 class MatrixState:
@@ -63,10 +65,12 @@ class Stage:
     points.  warm_start=True takes Q_bar of the previous round as the basis of the P phase.
     streams > 1 deals the matrices to that many HIP streams.  measure_rank=True also launches
     the effective-rank kernel of Alg. 3 for every matrix (results in self.rprime_dev).
+    batched=True orthonormalises (and measures) all matrices of the stage in one batch between
+    the two compression phases instead of matrix by matrix.
     """
 
     def __init__(self, matrices, lr, mu, fused=False, warm_start=False, streams=1,
-                 measure_rank=False, tau=0.99):
+                 measure_rank=False, tau=0.99, batched=True):
         self.mats = matrices
         self.lr, self.mu = lr, mu
         self.fused, self.warm_start = fused, warm_start
@@ -86,11 +90,17 @@ class Stage:
         self.side = [torch.cuda.Stream(device=dev) for _ in range(self.nstreams)] \
             if self.nstreams > 1 else []
         self.rprime_dev = torch.zeros(len(matrices), device=dev, dtype=torch.int32)
+        self.batched = batched
+        self.batch_ws = None
+        if batched:
+            nbytes = dlcx_batched_workspace_bytes([M.desc(M.r_max) for M in matrices])
+            self.batch_ws = torch.empty(nbytes, device=dev, dtype=torch.uint8)
 
     def params(self):
         return sum(m.m * m.n for m in self.mats)
 
-    def step_matrix(self, a, theta_l, lane=0, stream=None):
+    def _begin(self, a, theta_l, lane, stream):
+        """Everything of Alg. 2 between two compressions, for matrix a."""
         M, t = self.mats[a], self.t
         ws, d_hat = self.workspaces[lane], self.delta_hats[lane]
         if t >= 2 and self.fused:
@@ -105,37 +115,80 @@ class Stage:
             if t >= 2:
                 dlcx_outer_nesterov(M.theta_g, M.v, d_hat, self.lr, self.mu, numel=M.m * M.n,
                                     stream=stream)
-        d = M.desc()
+
+    def _p_phase(self, a, lane, stream, orthonormalize):
+        M, t = self.mats[a], self.t
+        ws, d = self.workspaces[lane], M.desc()
         basis = M.q_bar if (self.warm_start and t >= 2 and M.r_prev == M.r) else M.q_in
         dlcx_compress_batched(d, PHASE_P, M.ef, basis, M.codes_p, M.scales_p, ws, stream=stream)
-        dlcx_average(d, PHASE_P, M.codes_p, M.scales_p, M.p_hat, ws, stream=stream)
+        if orthonormalize:
+            dlcx_average(d, PHASE_P, M.codes_p, M.scales_p, M.p_hat, ws, stream=stream)
+        else:  # mean only; the stage orthonormalises all matrices in one batch afterwards
+            dlcx_dequant_average(M.codes_p, M.scales_p, M.r * M.m, M.qbits, M.group, M.p_hat,
+                                 stream=stream)
+
+    def _q_phase(self, a, lane, stream, rank):
+        M = self.mats[a]
+        ws, d = self.workspaces[lane], M.desc()
         dlcx_compress_batched(d, PHASE_Q, M.ef, M.p_hat, M.codes_q, M.scales_q, ws, stream=stream)
         dlcx_average(d, PHASE_Q, M.codes_q, M.scales_q, M.q_bar, ws, stream=stream)
         M.r_prev = M.r
-        if self.measure_rank:
+        if rank:
             dlcx_effective_rank(M.n, M.r, M.q_bar, self.tau, self.rprime_dev[a:], ws,
                                 stream=stream)
 
-    def step(self, theta_l_per_matrix):
-        """theta_l_per_matrix[a][i]: local replica i of matrix a after this round's inner steps.
-        Work is issued on the current stream (and the side streams, joined before returning)."""
-        self.t += 1
-        if self.nstreams == 1:
-            for a in range(len(self.mats)):
-                self.step_matrix(a, theta_l_per_matrix[a])
-            return
+    def _fork(self):
+        if not self.side:
+            return None
         main = torch.cuda.current_stream()
         start = torch.cuda.Event()
         start.record(main)
         for s in self.side:
             s.wait_event(start)
-        for a in range(len(self.mats)):
-            lane = a % self.nstreams
-            self.step_matrix(a, theta_l_per_matrix[a], lane=lane, stream=self.side[lane])
+        return main
+
+    def _join(self, main):
+        if main is None:
+            return
         for s in self.side:
             done = torch.cuda.Event()
             done.record(s)
             main.wait_event(done)
+
+    def _lane(self, a):
+        lane = a % self.nstreams
+        return lane, (self.side[lane] if self.side else None)
+
+    def step(self, theta_l_per_matrix):
+        """theta_l_per_matrix[a][i]: local replica i of matrix a after this round's inner steps.
+        Work is issued on the current stream (and the side streams, joined before returning)."""
+        self.t += 1
+        n = len(self.mats)
+        if not self.batched:
+            main = self._fork()
+            for a in range(n):
+                lane, st = self._lane(a)
+                self._begin(a, theta_l_per_matrix[a], lane, st)
+                self._p_phase(a, lane, st, orthonormalize=True)
+                self._q_phase(a, lane, st, rank=self.measure_rank)
+            self._join(main)
+            return
+        main = self._fork()
+        for a in range(n):
+            lane, st = self._lane(a)
+            self._begin(a, theta_l_per_matrix[a], lane, st)
+            self._p_phase(a, lane, st, orthonormalize=False)
+        self._join(main)
+        descs = [M.desc() for M in self.mats]
+        dlcx_orthonormalize_batched(descs, [M.p_hat for M in self.mats], self.batch_ws)
+        main = self._fork()
+        for a in range(n):
+            lane, st = self._lane(a)
+            self._q_phase(a, lane, st, rank=False)
+        self._join(main)
+        if self.measure_rank:
+            dlcx_effective_rank_batched(descs, [M.q_bar for M in self.mats], self.tau,
+                                        self.rprime_dev, self.batch_ws)
 
 
 class RankSelector:

@@ -190,24 +190,25 @@ def test_multi_stream_stage_equals_single_stream():
     shapes = [(256, 384), (512, 256), (384, 640), (256, 256), (640, 384)]
     K, r = 3, 16
 
-    def run(streams):
+    def run(streams, batched=True):
         mats, tls = [], []
         for a, (m, n) in enumerate(shapes):
             inp = synth.MatrixInputs(m, n, K, r, seed=500 + a, sigma=1e-3, alpha=1.0, theta_l="bf16")
             mats.append(MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), 4, 64, dlcx.MMA_BF16))
             tls.append([to_dev(inp.theta_local(inp.theta_g, 1, i)) for i in range(K)])
         st = Stage(mats, synth.LR, synth.MU, fused=True, warm_start=True, streams=streams,
-                   measure_rank=True)
+                   measure_rank=True, batched=batched)
         for _ in range(3):
             st.step(tls)
         torch.cuda.synchronize()
         return st
 
-    one, three = run(1), run(3)
+    one, three, loose = run(1), run(3), run(2, batched=False)
     assert three.nstreams == 3
-    for A, B in zip(one.mats, three.mats):
-        assert torch.equal(A.theta_g, B.theta_g) and torch.equal(A.v, B.v)
-        assert torch.equal(A.q_bar, B.q_bar) and torch.equal(A.p_hat, B.p_hat)
-        for x, y in zip(A.ef, B.ef):
-            assert torch.equal(x, y)
-    assert torch.equal(one.rprime_dev, three.rprime_dev)
+    for other in (three, loose):
+        for A, B in zip(one.mats, other.mats):
+            assert torch.equal(A.theta_g, B.theta_g) and torch.equal(A.v, B.v)
+            assert torch.equal(A.q_bar, B.q_bar) and torch.equal(A.p_hat, B.p_hat)
+            for x, y in zip(A.ef, B.ef):
+                assert torch.equal(x, y)
+        assert torch.equal(one.rprime_dev, other.rprime_dev)
