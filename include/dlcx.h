@@ -118,6 +118,21 @@ int dlcx_ef_delta_apply(const dlcx_desc *desc, const float *p_hat, const float *
                         float *const *ef_inout_host, float *theta_g, float *v, float lr, float mu,
                         void *workspace, void *stream);
 
+/* dlcx_ef_delta_apply followed by the P phase of dlcx_compress_batched, with the new
+ * pseudo-gradients read once for both: while a tile of delta_i is on chip it is also multiplied
+ * with the basis Q_in (r x n), so P_i = delta_i Q_in costs no second sweep over the matrix.
+ * desc->r is the rank of the compression that starts; r_prev the rank of p_hat / q_bar
+ * (r_prev == 0: outer step 1, there is no previous average: only delta_i <- (theta_g -
+ * theta_l,i) + e_i and the projection; p_hat, q_bar and v are then unused).  On return the
+ * workspace starts with the K fp32 factors, as after dlcx_compress_batched.  The workspace must
+ * be sized (dlcx_workspace_bytes) for a descriptor whose r is the larger of the two ranks. */
+int dlcx_ef_delta_apply_compress(const dlcx_desc *desc, int32_t r_prev, const float *p_hat,
+                                 const float *q_bar, int K, const void *const *theta_l_host,
+                                 int theta_l_dtype, float *const *ef_inout_host, float *theta_g,
+                                 float *v, float lr, float mu, const float *basis,
+                                 uint8_t *const *codes_out_host, float *const *scales_out_host,
+                                 void *workspace, void *stream);
+
 /* OuterOpt of Alg. 2 / Appendix A.3: SGD with Nesterov momentum on the averaged
  * pseudo-gradient,  v <- mu v + g ;  theta_g <- theta_g - lr (g + mu v).  In place. */
 int dlcx_outer_nesterov(float *theta_g, float *v, const float *delta_hat, int64_t numel,

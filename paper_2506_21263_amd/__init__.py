@@ -50,6 +50,8 @@ SYMBOLS = {
                                      _vp]),
     "dlcx_ef_delta_apply": (_int, [_dp, _vp, _vp, _int, _vp, _int, _vp, _vp, _vp, C.c_float,
                                    C.c_float, _vp, _vp]),
+    "dlcx_ef_delta_apply_compress": (_int, [_dp, _i32, _vp, _vp, _int, _vp, _int, _vp, _vp, _vp,
+                                            C.c_float, C.c_float, _vp, _vp, _vp, _vp, _vp]),
     "dlcx_outer_nesterov": (_int, [_vp, _vp, _vp, _i64, C.c_float, C.c_float, _vp]),
     "dlcx_select_rank": (_int, [_dp, _vp, _int, C.c_double, _vp, _i32, _i32, _i32, _i32, _i32,
                                 _i32, _vp, _vp, _vp, _vp, _vp]),
@@ -180,6 +182,19 @@ def dlcx_ef_delta_apply(d, p_hat, q_bar, theta_l, ef_inout, theta_g, v, lr, mu, 
     _check(lib().dlcx_ef_delta_apply(C.byref(d), _ptr(p_hat), _ptr(q_bar), len(ef_inout), tp, dt,
                                      ep, _ptr(theta_g), _ptr(v), lr, mu, _ptr(workspace),
                                      _stream(stream)), "dlcx_ef_delta_apply")
+
+
+def dlcx_ef_delta_apply_compress(d, r_prev, p_hat, q_bar, theta_l, ef_inout, theta_g, v, lr, mu,
+                                 basis, codes_out, scales_out, workspace, stream=None):
+    dt = BF16 if theta_l[0].dtype == torch.bfloat16 else F32
+    tp, k1 = _ptr_array(list(theta_l))
+    ep, k2 = _ptr_array(list(ef_inout))
+    cp, k3 = _ptr_array(list(codes_out))
+    sp, k4 = _ptr_array(list(scales_out))
+    _check(lib().dlcx_ef_delta_apply_compress(
+        C.byref(d), r_prev, _ptr(p_hat), _ptr(q_bar), len(ef_inout), tp, dt, ep, _ptr(theta_g),
+        _ptr(v), lr, mu, _ptr(basis), cp, sp, _ptr(workspace), _stream(stream)),
+        "dlcx_ef_delta_apply_compress")
 
 
 def dlcx_outer_nesterov(theta_g, v, delta_hat, lr, mu, numel=None, stream=None):

@@ -24,7 +24,7 @@ inline int check_launch(const char *where) { return note_hip(hipGetLastError(), 
 enum KernelId {
     KID_DELTA_EF = 0, KID_NESTEROV, KID_QUANTIZE, KID_DEQUANT_AVG, KID_PACK, KID_PROJECT_P,
     KID_PROJECT_Q, KID_SUM_SLABS, KID_RECONSTRUCT, KID_GRAM, KID_CHOL, KID_APPLY_W, KID_JACOBI,
-    KID_COUNT
+    KID_ROUND, KID_COUNT
 };
 struct Timed {
     Timed(int kid, hipStream_t st);

@@ -55,6 +55,9 @@ int launch_reconstruct_mfma(int, int64_t, int64_t, int, const float *, const flo
                             const ReconEpilogue &, void *, hipStream_t);
 size_t mfma_project_workspace_bytes(int, int64_t, int64_t, int, int);
 size_t mfma_reconstruct_workspace_bytes(int, int64_t, int64_t, int);
+size_t mfma_round_workspace_bytes(int, int64_t, int64_t, int, int, int);
+int launch_round_mfma(int, int64_t, int64_t, int, int, const float *, const float *, const float *,
+                      const ReconEpilogue &, const PtrPack<float *> &, void *, hipStream_t);
 
 static bool group_ok(int g) { return g == 16 || g == 32 || g == 64 || g == 128 || g == 256; }
 
@@ -128,7 +131,7 @@ const char *dlcx_last_hip_error(void) { return g_last_error.c_str(); }
 static const char *const kKernelNames[KID_COUNT] = {
     "delta_ef", "outer_nesterov", "quantize", "dequant_average", "pack_fragments", "project_p",
     "project_q", "sum_slabs", "reconstruct", "gram_partials", "chol_inverse", "apply_w",
-    "jacobi_rank"};
+    "jacobi_rank", "round_fused"};
 
 int dlcx_profile_enable(int on) {
     for (auto &r : g_prof) {
@@ -184,7 +187,12 @@ size_t dlcx_workspace_bytes(const dlcx_desc *desc, int K) {
                         project_workspace_bytes(desc->mma, desc->m, desc->n, desc->r, K);
     const size_t orth = orth_workspace_bytes(lmax, desc->r);
     const size_t rank = effrank_workspace_bytes(lmax, desc->r);
-    const size_t rec = reconstruct_workspace_bytes(desc->mma, desc->m, desc->n, desc->r);
+    size_t rec = reconstruct_workspace_bytes(desc->mma, desc->m, desc->n, desc->r);
+    if (desc->mma != DLCX_MMA_FMA) {
+        const size_t rnd = factor_region_bytes(desc, K) +
+                           mfma_round_workspace_bytes(desc->mma, desc->m, desc->n, desc->r, desc->r, K);
+        if (rnd > rec) rec = rnd;
+    }
     size_t w = proj > orth ? proj : orth;
     if (rank > w) w = rank;
     if (rec > w) w = rec;
@@ -403,6 +411,80 @@ int dlcx_ef_delta_apply(const dlcx_desc *desc, const float *p_hat, const float *
     if (K < 1 || !theta_l_host) return DLCX_EINVAL;
     return decompress_common(desc, p_hat, q_bar, nullptr, K, ef_inout_host, theta_l_host,
                              theta_l_dtype, theta_g, v, 1, lr, mu, workspace, stream);
+}
+
+int dlcx_ef_delta_apply_compress(const dlcx_desc *desc, int32_t r_prev, const float *p_hat,
+                                 const float *q_bar, int K, const void *const *theta_l_host,
+                                 int theta_l_dtype, float *const *ef_inout_host, float *theta_g,
+                                 float *v, float lr, float mu, const float *basis,
+                                 uint8_t *const *codes_out_host, float *const *scales_out_host,
+                                 void *workspace, void *stream) {
+    int rc = check_desc(desc);
+    if (rc != DLCX_OK) return rc;
+    if (r_prev < 0 || r_prev > DLCX_MAX_RANK || r_prev > desc->m || r_prev > desc->n)
+        return DLCX_EINVAL;
+    if (K < 1 || K > DLCX_MAX_WORKERS || !theta_l_host || !ef_inout_host || !theta_g || !basis ||
+        !codes_out_host || !scales_out_host || !workspace)
+        return DLCX_EINVAL;
+    if (theta_l_dtype != DLCX_F32 && theta_l_dtype != DLCX_BF16) return DLCX_EINVAL;
+    if (!aligned16(theta_g) || !aligned16(basis) || !aligned16(workspace)) return DLCX_EINVAL;
+    if (r_prev > 0) {
+        if (!p_hat || !q_bar || !v || !aligned16(p_hat) || !aligned16(q_bar) || !aligned16(v))
+            return DLCX_EINVAL;
+        if (!(lr == lr) || !(mu == mu)) return DLCX_EINVAL;
+    }
+    for (int k = 0; k < K; ++k) {
+        if (!theta_l_host[k] || !ef_inout_host[k] || !codes_out_host[k] || !scales_out_host[k])
+            return DLCX_EINVAL;
+        if (!aligned16(theta_l_host[k]) || !aligned16(ef_inout_host[k]) ||
+            !aligned16(codes_out_host[k]) || !aligned16(scales_out_host[k]))
+            return DLCX_EINVAL;
+    }
+    if (desc->mma == DLCX_MMA_FMA) {  // no fused kernel in this mode: the same steps one by one
+        if (r_prev > 0) {
+            dlcx_desc dp = *desc;
+            dp.r = r_prev;
+            rc = dlcx_ef_delta_apply(&dp, p_hat, q_bar, K, theta_l_host, theta_l_dtype,
+                                     ef_inout_host, theta_g, v, lr, mu, workspace, stream);
+            if (rc != DLCX_OK) return rc;
+        } else {
+            for (int k = 0; k < K; ++k) {
+                rc = dlcx_delta_ef(theta_g, theta_l_host[k], theta_l_dtype, ef_inout_host[k],
+                                   desc->m * desc->n, stream);
+                if (rc != DLCX_OK) return rc;
+            }
+        }
+        return dlcx_compress_batched(desc, DLCX_PHASE_P, K, ef_inout_host, basis, codes_out_host,
+                                     scales_out_host, workspace, stream);
+    }
+    const int64_t count = (int64_t)desc->r * desc->m;
+    ReconEpilogue ep;
+    memset(&ep, 0, sizeof ep);
+    ep.K = K;
+    ep.tl_on = 1;
+    ep.tl_bf16 = theta_l_dtype == DLCX_BF16;
+    ep.theta = theta_g;
+    ep.vel = v;
+    ep.apply = r_prev > 0;
+    ep.lr = lr;
+    ep.mu = mu;
+    PtrPack<float *> factors;
+    PtrPack<const float *> xs;
+    PtrPack<uint8_t *> cs;
+    PtrPack<float *> ss;
+    for (int k = 0; k < K; ++k) {
+        ep.ef.p[k] = ef_inout_host[k];
+        ep.tl.p[k] = theta_l_host[k];
+        factors.p[k] = reinterpret_cast<float *>(workspace) + (int64_t)k * count;
+        xs.p[k] = factors.p[k];
+        cs.p[k] = codes_out_host[k];
+        ss.p[k] = scales_out_host[k];
+    }
+    void *inner = reinterpret_cast<char *>(workspace) + factor_region_bytes(desc, K);
+    rc = launch_round_mfma(desc->mma, desc->m, desc->n, desc->r, r_prev, p_hat, q_bar, basis, ep,
+                           factors, inner, as_stream(stream));
+    if (rc != DLCX_OK) return rc;
+    return launch_quantize(K, xs, count, desc->qbits, desc->group, cs, ss, as_stream(stream));
 }
 
 int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,

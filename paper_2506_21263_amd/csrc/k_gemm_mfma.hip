@@ -19,6 +19,8 @@
 // 1 KB of consecutive memory; fragments are read straight from L2 into registers.  The big
 // operand delta is staged through LDS (P phase, reduction along a row) or loaded straight into
 // the operand layout with 128-byte row segments (Q phase, reduction down a column).
+#include <type_traits>
+
 #include "common.h"
 
 namespace dlcx {
@@ -271,28 +273,48 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
 
 // ---------------------------------------------------------------------------------------------
 // Q phase:  Q_k[j][c] = sum_i delta_k[i][j] P_hat[c][i].
-// Wavefront: JB column blocks of 32 x all CB basis blocks over its own range of rows; the B
-// operand (N = j, reduction down the column) is loaded straight into the operand layout: lane
-// (j, half) reads delta[i0 + 8 half + e][j], e = 0..7, i.e. 128-byte row segments.  The 4
-// wavefronts of a workgroup take consecutive quarters of the workgroup's rows and are added in
-// wavefront order at the end; blockIdx.z splits the rows further into slabs.
+// Wavefront: 32 JB columns x all CB basis blocks over its own range of rows.  The B operand
+// (N = column, reduction down the column) is loaded straight from HBM into the operand layout:
+// lane (x, half) reads the JB consecutive columns j0 + JB x .. of the rows i0 + 8 half + e,
+// e = 0..7, and column JB x + q feeds MFMA block q (the column blocks are interleaved, which an
+// MFMA does not care about), so one load instruction covers 2 rows x 128 JB contiguous bytes.
+// The 4 wavefronts of a workgroup take consecutive quarters of the workgroup's rows and are added
+// in wavefront order at the end; blockIdx.z splits the rows further into slabs.
 // ---------------------------------------------------------------------------------------------
-constexpr int kQDepth = 4;  // k-steps of delta in flight per wavefront
+template <int JB> struct VecOf;
+template <> struct VecOf<1> { typedef float type; };
+template <> struct VecOf<2> { typedef float2 type; };
+template <> struct VecOf<4> { typedef float4 type; };
 
-template <int NS, int CB, int JB>
+template <int JB>
+__device__ __forceinline__ void vec_to_array(const typename VecOf<JB>::type &v, float (&out)[JB]);
+template <>
+__device__ __forceinline__ void vec_to_array<1>(const float &v, float (&out)[1]) { out[0] = v; }
+template <>
+__device__ __forceinline__ void vec_to_array<2>(const float2 &v, float (&out)[2]) {
+    out[0] = v.x; out[1] = v.y;
+}
+template <>
+__device__ __forceinline__ void vec_to_array<4>(const float4 &v, float (&out)[4]) {
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+
+template <int NS, int CB, int JB, int DEPTH>
 __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float *> deltas,
                                                             const uint4 *__restrict__ afrags,
                                                             PtrPack<float *> outs, int64_t m,
                                                             int64_t n, int r,
                                                             int64_t ksteps_per_wave,
                                                             int64_t slab_stride) {
+    typedef typename VecOf<JB>::type vec_t;
     __shared__ float red[CB * JB * 16 * 64];
     const float *__restrict__ delta = deltas.p[blockIdx.y];
     float *__restrict__ out = outs.p[blockIdx.y] + (int64_t)blockIdx.z * slab_stride;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t j0 = (int64_t)blockIdx.x * (32 * JB);
+    const int64_t jcol = (int64_t)blockIdx.x * (32 * JB) + JB * (lane & 31);
+    const bool col_ok = jcol < n;  // n is a multiple of 16: the JB columns are in or out together
     const int64_t s_begin = ((int64_t)blockIdx.z * 4 + wave) * ksteps_per_wave;
-    const int64_t s_end = s_begin + ksteps_per_wave;  // multiple of kQDepth k-steps
+    const int64_t s_end = s_begin + ksteps_per_wave;  // a multiple of DEPTH k-steps
 
     f32x16_t acc[CB][JB];
 #pragma unroll
@@ -302,24 +324,23 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    float breg[kQDepth][JB][8];
+    float breg[DEPTH][8][JB];
     auto load_kstep = [&](int d, int64_t s) {
         const int64_t ibase = s * 16 + (lane >> 5) * 8;
 #pragma unroll
-        for (int jb = 0; jb < JB; ++jb) {
-            const int64_t j = j0 + jb * 32 + (lane & 31);
+        for (int e = 0; e < 8; ++e) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                breg[d][jb][e] = 0.f;
-                if (ibase + e < m && j < n) breg[d][jb][e] = delta[(ibase + e) * n + j];
-            }
+            for (int q = 0; q < JB; ++q) breg[d][e][q] = 0.f;
+            if (ibase + e < m && col_ok)
+                vec_to_array<JB>(*reinterpret_cast<const vec_t *>(delta + (ibase + e) * n + jcol),
+                                 breg[d][e]);
         }
     };
 #pragma unroll
-    for (int d = 0; d < kQDepth; ++d) load_kstep(d, s_begin + d);
-    for (int64_t s = s_begin; s < s_end; s += kQDepth) {
+    for (int d = 0; d < DEPTH; ++d) load_kstep(d, s_begin + d);
+    for (int64_t s = s_begin; s < s_end; s += DEPTH) {
 #pragma unroll
-        for (int d = 0; d < kQDepth; ++d) {
+        for (int d = 0; d < DEPTH; ++d) {
             uint4 a[CB][NS];
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
@@ -328,12 +349,17 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
                     a[cb][h] = afrags[(((s + d) * CB + cb) * NS + h) * 64 + lane];
             uint4 b[JB][NS];
 #pragma unroll
-            for (int jb = 0; jb < JB; ++jb) split8<NS>(breg[d][jb], b[jb]);
-            if (s + d + kQDepth < s_end) load_kstep(d, s + d + kQDepth);
+            for (int q = 0; q < JB; ++q) {
+                float x[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = breg[d][e][q];
+                split8<NS>(x, b[q]);
+            }
+            if (s + d + DEPTH < s_end) load_kstep(d, s + d + DEPTH);
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                for (int jb = 0; jb < JB; ++jb) mfma_split<NS>(a[cb], b[jb], acc[cb][jb]);
+                for (int q = 0; q < JB; ++q) mfma_split<NS>(a[cb], b[q], acc[cb][q]);
         }
     }
     // wavefronts 3, 2, 1 hand their sums to wavefront 0, in that order
@@ -342,33 +368,32 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                for (int jb = 0; jb < JB; ++jb)
+                for (int q = 0; q < JB; ++q)
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
-                        red[((cb * JB + jb) * 16 + v) * 64 + lane] = acc[cb][jb][v];
+                        red[((cb * JB + q) * 16 + v) * 64 + lane] = acc[cb][q][v];
         }
         __syncthreads();
         if (wave == 0) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                for (int jb = 0; jb < JB; ++jb)
+                for (int q = 0; q < JB; ++q)
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
-                        acc[cb][jb][v] += red[((cb * JB + jb) * 16 + v) * 64 + lane];
+                        acc[cb][q][v] += red[((cb * JB + q) * 16 + v) * 64 + lane];
         }
         __syncthreads();
     }
-    if (wave != 0) return;
+    if (wave != 0 || !col_ok) return;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int jb = 0; jb < JB; ++jb) {
-            const int64_t j = j0 + jb * 32 + (lane & 31);
+        for (int v = 0; v < 16; ++v) {
+            const int c = cb * 32 + d_row(v, lane);
+            if (c < r) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int c = cb * 32 + d_row(v, lane);
-                if (c < r && j < n) out[(int64_t)c * n + j] = acc[cb][jb][v];
+                for (int q = 0; q < JB; ++q) out[(int64_t)c * n + jcol + q] = acc[cb][q][v];
             }
         }
 }
@@ -495,6 +520,257 @@ __global__ __launch_bounds__(kW) void reconstruct_mfma_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// The whole pass between two compressions, fused with the P phase of the next one (outer step
+// t >= 2), for up to KC workers:
+//   d        = P_hat_prev Q_bar_prev^T             (tile by tile, never written)
+//   e_k      = delta_k - d ;  delta_k = (theta - theta_l,k) + e_k     -> stored over delta_k
+//   P_k     += delta_k Q_in                        (accumulated while the tile is on chip)
+//   apply    : v <- mu v + d ; theta <- theta - lr (d + mu v)
+// Same tiling as the reconstruction kernel (32 rows x 256 columns per iteration, wavefront w owns
+// 64 columns).  After the elementwise step the new delta_k tile is written to LDS as bf16 pieces
+// in the layout of the P-phase kernel (row-major, reduction index contiguous) and multiplied with
+// the basis fragments of its 64 columns: delta is read from HBM once for all of this.  A
+// workgroup leaves the partial P_k of its rows and column range in slab blockIdx.x; the slabs of
+// a row block are added afterwards in slab order.
+// ---------------------------------------------------------------------------------------------
+// LDS written by some lanes of a wavefront and read by others: the data share unit executes one
+// wavefront's instructions in order, so only the compiler has to be kept from reordering.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int NS, int CB, int KC, bool TLBF16>
+__global__ __launch_bounds__(kW) void round_mfma_kernel(
+    const uint4 *__restrict__ pfrags, const uint4 *__restrict__ qfrags, int KS,
+    const uint4 *__restrict__ bfrags, ReconEpilogue ep, PtrPack<float *> pslab, int64_t m,
+    int64_t n, int r, int64_t cols_per_wg, int64_t slab_stride) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int kTileBytes = 32 * kRPitch * 4;      // fp32 staging tile of one wavefront
+    constexpr int kBBytes = NS * 32 * kPPitch;        // bf16 pieces of one wavefront's delta tile
+    constexpr bool kBasisInLds = NS == 2 && CB <= 2;  // basis fragments of the 64 columns staged
+    constexpr int kBasisBytes = kBasisInLds ? 4 * CB * NS * 1024 : 0;
+    float *tile = reinterpret_cast<float *>(smem) + (threadIdx.x >> 6) * (32 * kRPitch);
+    unsigned char *btile = smem + 4 * kTileBytes + (threadIdx.x >> 6) * kBBytes;
+    uint4 *basis_lds = reinterpret_cast<uint4 *>(smem + 4 * kTileBytes + 4 * kBBytes +
+                                                 (threadIdx.x >> 6) * kBasisBytes);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t ib = blockIdx.y;
+    const int64_t jbegin = (int64_t)blockIdx.x * cols_per_wg;
+    int64_t jend = jbegin + cols_per_wg;
+    if (jend > n) jend = n;
+    const int64_t nblk = (n + 31) >> 5;
+    const int prow = lane >> 4, pc4 = lane & 15;
+    const int64_t row0 = ib * 32 + prow;  // pass p covers row row0 + 4 p
+    typedef typename std::conditional<TLBF16, uint2, float4>::type traw_t;
+
+    f32x16_t acc[KC][CB];
+#pragma unroll
+    for (int k = 0; k < KC; ++k)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[k][cb][v] = 0.f;
+
+    // operands of the item (column tile, worker) in flight
+    float4 x[8], tv[8], vv[8];
+    traw_t lraw[8];
+    auto issue = [&](int64_t jt, int k, bool with_theta, bool with_vel) {
+        const int64_t j = jt + pc4 * 4;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const bool okp = j < n && row0 + 4 * p < m;
+            const int64_t off = (row0 + 4 * p) * n + j;
+            x[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (TLBF16) lraw[p] = *reinterpret_cast<const traw_t *>(&x[p]);
+            else lraw[p] = *reinterpret_cast<const traw_t *>(&x[p]);
+            if (okp) {
+                x[p] = *reinterpret_cast<const float4 *>(ep.ef.p[k] + off);
+                if (TLBF16)
+                    lraw[p] = *reinterpret_cast<const traw_t *>(
+                        reinterpret_cast<const uint16_t *>(ep.tl.p[k]) + off);
+                else
+                    lraw[p] = *reinterpret_cast<const traw_t *>(
+                        reinterpret_cast<const float *>(ep.tl.p[k]) + off);
+            }
+            if (with_theta) {
+                tv[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (okp) tv[p] = *reinterpret_cast<const float4 *>(ep.theta + off);
+            }
+            if (with_vel) {
+                vv[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (okp) vv[p] = *reinterpret_cast<const float4 *>(ep.vel + off);
+            }
+        }
+    };
+    const int Kw = ep.K;
+    int64_t jt = jbegin + wave * 64;
+    if (jt < jend) issue(jt, 0, true, ep.apply && Kw == 1);
+    for (; jt < jend; jt += 256) {
+        // ---- d = P_hat_prev Q_bar_prev^T for this wavefront's 32 x 64 tile
+        f32x16_t d[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) d[nb][v] = 0.f;
+        {
+            const int64_t jb0 = jt >> 5;
+            const bool two = jb0 + 1 < nblk;
+#pragma unroll 2
+            for (int s = 0; s < KS; ++s) {
+                uint4 a[NS], b0[NS], b1[NS];
+#pragma unroll
+                for (int h = 0; h < NS; ++h) {
+                    a[h] = pfrags[((ib * KS + s) * NS + h) * 64 + lane];
+                    b0[h] = qfrags[((jb0 * KS + s) * NS + h) * 64 + lane];
+                    b1[h] = two ? qfrags[(((jb0 + 1) * KS + s) * NS + h) * 64 + lane]
+                                : make_uint4(0u, 0u, 0u, 0u);
+                }
+                mfma_split<NS>(a, b0, d[0]);
+                mfma_split<NS>(a, b1, d[1]);
+            }
+        }
+        wave_lds_sync();  // earlier readers of the staging tile and of the basis are done
+        if (kBasisInLds) {  // this tile's basis fragments: 4 k-steps x CB blocks x NS pieces
+#pragma unroll
+            for (int f = 0; f < 4 * CB * NS; ++f)
+                basis_lds[f * 64 + lane] = bfrags[((jt >> 4) * CB * NS + f) * 64 + lane];
+        }
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                tile[d_row(v, lane) * kRPitch + nb * 32 + (lane & 31)] = d[nb][v];
+        wave_lds_sync();
+        float4 dv[8];
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            dv[p] = *reinterpret_cast<const float4 *>(&tile[(p * 4 + prow) * kRPitch + pc4 * 4]);
+        const int64_t j = jt + pc4 * 4;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            if (k < Kw) {
+                const bool last = k == Kw - 1;
+                float *__restrict__ e = ep.ef.p[k];
+                wave_lds_sync();  // the previous item's fragments have been read
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const bool okp = j < n && row0 + 4 * p < m;
+                    const int64_t off = (row0 + 4 * p) * n + j;
+                    float4 l;
+                    if (TLBF16) {
+                        const uint2 bits = *reinterpret_cast<const uint2 *>(&lraw[p]);
+                        l = make_float4(__uint_as_float(bits.x << 16),
+                                        __uint_as_float(bits.x & 0xFFFF0000u),
+                                        __uint_as_float(bits.y << 16),
+                                        __uint_as_float(bits.y & 0xFFFF0000u));
+                    } else {
+                        l = *reinterpret_cast<const float4 *>(&lraw[p]);
+                    }
+                    float4 g;
+                    g.x = (tv[p].x - l.x) + (x[p].x - dv[p].x);
+                    g.y = (tv[p].y - l.y) + (x[p].y - dv[p].y);
+                    g.z = (tv[p].z - l.z) + (x[p].z - dv[p].z);
+                    g.w = (tv[p].w - l.w) + (x[p].w - dv[p].w);
+                    if (okp) {
+                        *reinterpret_cast<float4 *>(e + off) = g;
+                    } else {
+                        g = make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+                    uint32_t lo[NS], hi[NS];
+                    split2<NS>(g.x, g.y, lo);
+                    split2<NS>(g.z, g.w, hi);
+#pragma unroll
+                    for (int h = 0; h < NS; ++h)
+                        *reinterpret_cast<uint2 *>(btile + (h * 32 + p * 4 + prow) * kPPitch +
+                                                   pc4 * 8) = make_uint2(lo[h], hi[h]);
+                    if (last && ep.apply && okp) {
+                        float4 vn, tn;
+                        vn.x = fmaf(ep.mu, vv[p].x, dv[p].x); vn.y = fmaf(ep.mu, vv[p].y, dv[p].y);
+                        vn.z = fmaf(ep.mu, vv[p].z, dv[p].z); vn.w = fmaf(ep.mu, vv[p].w, dv[p].w);
+                        tn.x = fmaf(-ep.lr, fmaf(ep.mu, vn.x, dv[p].x), tv[p].x);
+                        tn.y = fmaf(-ep.lr, fmaf(ep.mu, vn.y, dv[p].y), tv[p].y);
+                        tn.z = fmaf(-ep.lr, fmaf(ep.mu, vn.z, dv[p].z), tv[p].z);
+                        tn.w = fmaf(-ep.lr, fmaf(ep.mu, vn.w, dv[p].w), tv[p].w);
+                        *reinterpret_cast<float4 *>(ep.vel + off) = vn;
+                        *reinterpret_cast<float4 *>(ep.theta + off) = tn;
+                    }
+                }
+                // operands of the next item, in flight while this one is multiplied
+                if (!last) {
+                    issue(jt, k + 1, false, ep.apply && k + 1 == Kw - 1);
+                } else if (jt + 256 < jend) {
+                    issue(jt + 256, 0, true, ep.apply && Kw == 1);
+                }
+                wave_lds_sync();
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    uint4 b[NS];
+#pragma unroll
+                    for (int h = 0; h < NS; ++h)
+                        b[h] = *reinterpret_cast<const uint4 *>(
+                            btile + (h * 32 + (lane & 31)) * kPPitch + s * 32 + (lane >> 5) * 16);
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) {
+                        uint4 a[NS];
+#pragma unroll
+                        for (int h = 0; h < NS; ++h) {
+                            if (kBasisInLds)
+                                a[h] = basis_lds[((s * CB + cb) * NS + h) * 64 + lane];
+                            else
+                                a[h] = bfrags[((((jt >> 4) + s) * CB + cb) * NS + h) * 64 + lane];
+                        }
+                        mfma_split<NS>(a, b, acc[k][cb]);
+                    }
+                }
+            }
+        }
+    }
+    // add the four wavefronts' partial P_k (wavefronts 3, 2, 1 hand over to 0, in that order)
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(smem);
+    for (int w = 3; w >= 1; --w) {
+        if (wave == w) {
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        red[((k * CB + cb) * 16 + v) * 64 + lane] = acc[k][cb][v];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[k][cb][v] += red[((k * CB + cb) * 16 + v) * 64 + lane];
+        }
+        __syncthreads();
+    }
+    if (wave != 0) return;
+    const int64_t i = ib * 32 + (lane & 31);
+    if (i >= m) return;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        if (k < Kw) {
+            float *__restrict__ out = pslab.p[k] + (int64_t)blockIdx.x * slab_stride;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int c = cb * 32 + d_row(v, lane);
+                    if (c < r) out[(int64_t)c * m + i] = acc[k][cb][v];
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 static inline int ns_of(int mma) { return mma == DLCX_MMA_F32 ? 3 : 2; }
@@ -502,23 +778,24 @@ static inline int cb_of(int r) { return r <= 32 ? 1 : r <= 64 ? 2 : r <= 128 ? 4
 static inline size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct QPlan {
-    int JB, S;
+    int JB, S, depth;
     int64_t ksteps_per_wave, KS;
 };
 
 static QPlan q_plan(int64_t m, int64_t n, int r, int K) {
     QPlan p;
     const int cb = cb_of(r);
-    p.JB = cb <= 2 ? 2 : 1;
+    p.JB = cb <= 2 ? 4 : cb == 4 ? 2 : 1;  // accumulators: CB * JB * 16 registers
+    p.depth = cb <= 2 ? 2 : 4;             // k-steps (16 rows) of delta in flight per wavefront
     const int64_t col_wgs = ceil_div(n, 32 * p.JB) * K;
-    int64_t S = ceil_div(1024, col_wgs);
-    const int64_t smax = ceil_div(m, 64 * kQDepth * 2);  // at least 2 pipeline rounds per wave
+    int64_t S = ceil_div(512, col_wgs);
+    const int64_t smax = ceil_div(m, 64 * p.depth * 2);  // at least 2 pipeline rounds per wave
     if (S > smax) S = smax;
     if (S < 1) S = 1;
     if (S > 64) S = 64;
     p.S = (int)S;
     int64_t kpw = ceil_div(ceil_div(m, 16), (int64_t)p.S * 4);
-    p.ksteps_per_wave = ceil_div(kpw, kQDepth) * kQDepth;
+    p.ksteps_per_wave = ceil_div(kpw, p.depth) * p.depth;
     p.KS = p.ksteps_per_wave * 4 * p.S;
     return p;
 }
@@ -586,10 +863,10 @@ static int project_q_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
     {
     Timed timed(KID_PROJECT_Q, st);
     switch (cb) {
-        case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        case 2: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 2, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        case 4: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 4, 1>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        default: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 8, 1>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 2: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 2, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 4: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 4, 2, 4>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        default: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 8, 1, 4>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
     }
     rc = check_launch("project_q_mfma");
     }
@@ -667,6 +944,143 @@ int launch_reconstruct_mfma(int mma, int64_t m, int64_t n, int r, const float *p
                             hipStream_t st) {
     if (mma == DLCX_MMA_F32) return reconstruct_ns<3>(m, n, r, p_hat, q_bar, ep, workspace, st);
     return reconstruct_ns<2>(m, n, r, p_hat, q_bar, ep, workspace, st);
+}
+
+// ---- fused round: workspace layout and launch ------------------------------------------------
+struct RoundPlan {
+    int chunks;        // column ranges per row block = slabs per worker
+    int64_t cols;      // columns per workgroup (multiple of 256)
+    int kc;            // workers per launch
+};
+
+static RoundPlan round_plan(int64_t m, int64_t n, int r) {
+    RoundPlan p;
+    const int cb = cb_of(r);
+    p.kc = cb <= 2 ? 4 : cb == 4 ? 2 : 1;
+    const int64_t rows = ceil_div(m, 32);
+    int64_t chunks = ceil_div(512, rows);
+    const int64_t max_chunks = ceil_div(n, 256);
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks > 4) chunks = 4;
+    if (chunks < 1) chunks = 1;
+    p.cols = ceil_div(ceil_div(n, chunks), 256) * 256;
+    p.chunks = (int)ceil_div(n, p.cols);
+    return p;
+}
+
+// [basis fragments | P_hat_prev fragments | Q_bar_prev fragments | slabs (K x chunks x r x m)]
+size_t mfma_round_workspace_bytes(int mma, int64_t m, int64_t n, int r, int r_prev, int K) {
+    const int ns = ns_of(mma);
+    const RoundPlan pl = round_plan(m, n, r);
+    const size_t ksp = (size_t)(r_prev + 15) / 16;
+    size_t total = a256((size_t)ceil_div(n, 64) * 4 * cb_of(r) * ns * 1024);
+    total += a256((size_t)ceil_div(m, 32) * ksp * ns * 1024);
+    total += a256((size_t)ceil_div(n, 32) * ksp * ns * 1024);
+    if (pl.chunks > 1) total += a256((size_t)K * pl.chunks * r * m * sizeof(float));
+    return total;
+}
+
+template <int NS, int CB, int KC, bool TLBF16>
+static int round_launch_t(const uint4 *pf, const uint4 *qf, int ks, const uint4 *bf,
+                        const ReconEpilogue &ep, const PtrPack<float *> &pslab, int64_t m,
+                        int64_t n, int r, const RoundPlan &pl, int64_t slab_stride,
+                        hipStream_t st) {
+    const size_t basis = (NS == 2 && CB <= 2) ? (size_t)4 * CB * NS * 1024 : 0;
+    const size_t tiles = 4 * (32 * kRPitch * 4) + 4 * (size_t)(NS * 32 * kPPitch) + 4 * basis;
+    const size_t red = (size_t)KC * CB * 16 * 64 * 4;
+    const size_t lds = tiles > red ? tiles : red;
+    static size_t granted = 0;
+    if (lds > 48 * 1024 && lds > granted) {
+        int rc = note_hip(hipFuncSetAttribute(
+                              reinterpret_cast<const void *>(round_mfma_kernel<NS, CB, KC, TLBF16>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
+                          "round kernel attribute");
+        if (rc != DLCX_OK) return rc;
+        granted = lds;
+    }
+    const dim3 grid((unsigned)pl.chunks, (unsigned)ceil_div(m, 32));
+    Timed timed(KID_ROUND, st);
+    hipLaunchKernelGGL((round_mfma_kernel<NS, CB, KC, TLBF16>), grid, dim3(kW), lds, st, pf, qf, ks,
+                       bf, ep, pslab, m, n, r, pl.cols, slab_stride);
+    return check_launch("round_mfma");
+}
+
+template <int NS, int CB, int KC>
+static int round_launch(const uint4 *pf, const uint4 *qf, int ks, const uint4 *bf,
+                        const ReconEpilogue &ep, const PtrPack<float *> &pslab, int64_t m,
+                        int64_t n, int r, const RoundPlan &pl, int64_t slab_stride,
+                        hipStream_t st) {
+    if (ep.tl_bf16)
+        return round_launch_t<NS, CB, KC, true>(pf, qf, ks, bf, ep, pslab, m, n, r, pl, slab_stride, st);
+    return round_launch_t<NS, CB, KC, false>(pf, qf, ks, bf, ep, pslab, m, n, r, pl, slab_stride, st);
+}
+
+template <int NS>
+static int round_ns(int64_t m, int64_t n, int r, int r_prev, const float *p_hat, const float *q_bar,
+                    const float *basis, const ReconEpilogue &ep_all, const PtrPack<float *> &factors,
+                    void *workspace, hipStream_t st) {
+    const int cb = cb_of(r);
+    const RoundPlan pl = round_plan(m, n, r);
+    const int ks = (r_prev + 15) / 16;
+    const int64_t xbm = ceil_div(m, 32), xbn = ceil_div(n, 32);
+    char *ws = reinterpret_cast<char *>(workspace);
+    uint4 *bf = reinterpret_cast<uint4 *>(ws);
+    ws += a256((size_t)ceil_div(n, 64) * 4 * cb * NS * 1024);
+    uint4 *pf = reinterpret_cast<uint4 *>(ws);
+    ws += a256((size_t)xbm * ks * NS * 1024);
+    uint4 *qf = reinterpret_cast<uint4 *>(ws);
+    ws += a256((size_t)xbn * ks * NS * 1024);
+    float *slabs = reinterpret_cast<float *>(ws);
+    int rc = pack_kcontig<NS>(basis, r, n, cb, ceil_div(n, 64) * 4, bf, st);
+    if (rc != DLCX_OK) return rc;
+    if (ks > 0) {
+        {
+            Timed timed(KID_PACK, st);
+            hipLaunchKernelGGL(pack_kstrided_kernel<NS>, dim3((unsigned)ceil_div(xbm * ks, 4)),
+                               dim3(kW), 0, st, p_hat, r_prev, m, ks, xbm, pf);
+            rc = check_launch("pack p_hat");
+        }
+        if (rc != DLCX_OK) return rc;
+        {
+            Timed timed(KID_PACK, st);
+            hipLaunchKernelGGL(pack_kstrided_kernel<NS>, dim3((unsigned)ceil_div(xbn * ks, 4)),
+                               dim3(kW), 0, st, q_bar, r_prev, n, ks, xbn, qf);
+            rc = check_launch("pack q_bar");
+        }
+        if (rc != DLCX_OK) return rc;
+    }
+    const int64_t slab = (int64_t)r * m;
+    for (int k0 = 0; k0 < ep_all.K; k0 += pl.kc) {
+        ReconEpilogue ep = ep_all;
+        ep.K = ep_all.K - k0 < pl.kc ? ep_all.K - k0 : pl.kc;
+        ep.apply = ep_all.apply && (k0 + pl.kc >= ep_all.K);  // theta moves with the last group
+        PtrPack<float *> dst;
+        for (int k = 0; k < ep.K; ++k) {
+            ep.ef.p[k] = ep_all.ef.p[k0 + k];
+            ep.tl.p[k] = ep_all.tl.p[k0 + k];
+            dst.p[k] = pl.chunks > 1 ? slabs + (int64_t)(k0 + k) * pl.chunks * slab
+                                     : factors.p[k0 + k];
+        }
+        switch (cb) {
+            case 1: rc = round_launch<NS, 1, 4>(pf, qf, ks, bf, ep, dst, m, n, r, pl, slab, st); break;
+            case 2: rc = round_launch<NS, 2, 4>(pf, qf, ks, bf, ep, dst, m, n, r, pl, slab, st); break;
+            case 4: rc = round_launch<NS, 4, 2>(pf, qf, ks, bf, ep, dst, m, n, r, pl, slab, st); break;
+            default: rc = round_launch<NS, 8, 1>(pf, qf, ks, bf, ep, dst, m, n, r, pl, slab, st); break;
+        }
+        if (rc != DLCX_OK) return rc;
+    }
+    if (pl.chunks == 1) return DLCX_OK;
+    PtrPack<const float *> src;
+    for (int k = 0; k < ep_all.K; ++k) src.p[k] = slabs + (int64_t)k * pl.chunks * slab;
+    return launch_sum_slabs(ep_all.K, src, factors, slab, pl.chunks, slab, st);
+}
+
+int launch_round_mfma(int mma, int64_t m, int64_t n, int r, int r_prev, const float *p_hat,
+                      const float *q_bar, const float *basis, const ReconEpilogue &ep,
+                      const PtrPack<float *> &factors, void *workspace, hipStream_t st) {
+    if (mma == DLCX_MMA_F32)
+        return round_ns<3>(m, n, r, r_prev, p_hat, q_bar, basis, ep, factors, workspace, st);
+    return round_ns<2>(m, n, r, r_prev, p_hat, q_bar, basis, ep, factors, workspace, st);
 }
 
 }  // namespace dlcx

@@ -5,7 +5,7 @@ which HIP stream, in the order of Alg. 2 with the one-step delay.  Every arithme
 kernel of libdlcx_hip.so.
 
     t >= 2 :  e_i <- delta_i - Delta_hat^{t-1}                 \\
-              delta_i <- (theta_g - theta_l,i) + e_i            > dlcx_ef_delta_apply (fused), or
+              delta_i <- (theta_g - theta_l,i) + e_i            > dlcx_ef_delta_apply_compress, or
     t >= 2 :  theta_g <- OuterOpt(theta_g, Delta_hat^{t-1})    /  dlcx_decompress, dlcx_delta_ef,
                                                                   dlcx_outer_nesterov
               P phase: compress, average (+ orthonormalise)     dlcx_compress_batched, dlcx_average
@@ -22,7 +22,7 @@ import torch
 
 from . import (PHASE_P, PHASE_Q, desc, dlcx_average, dlcx_batched_workspace_bytes,
                dlcx_compress_batched, dlcx_decompress, dlcx_delta_ef, dlcx_dequant_average,
-               dlcx_effective_rank, dlcx_effective_rank_batched, dlcx_ef_delta_apply,
+               dlcx_effective_rank, dlcx_effective_rank_batched, dlcx_ef_delta_apply_compress,
                dlcx_orthonormalize_batched, dlcx_outer_nesterov, dlcx_payload_bytes,
                dlcx_select_rank_from, dlcx_workspace_bytes)
 
@@ -60,9 +60,9 @@ class MatrixState:
 class Stage:
     """All matrices of one pipeline stage plus shared scratch; `step` is one outer step.
 
-    fused=True uses dlcx_ef_delta_apply (one pass for error buffers, pseudo-gradients and the
-    outer update, the decompressed average never written); fused=False runs the separate entry
-    points.  warm_start=True takes Q_bar of the previous round as the basis of the P phase.
+    fused=True uses dlcx_ef_delta_apply_compress (one pass for error buffers, pseudo-gradients,
+    outer update and the P-phase projection, the decompressed average never written);
+    fused=False runs the separate entry points.  warm_start=True takes Q_bar of the previous round as the basis of the P phase.
     streams > 1 deals the matrices to that many HIP streams.  measure_rank=True also launches
     the effective-rank kernel of Alg. 3 for every matrix (results in self.rprime_dev).
     batched=True orthonormalises (and measures) all matrices of the stage in one batch between
@@ -99,13 +99,15 @@ class Stage:
     def params(self):
         return sum(m.m * m.n for m in self.mats)
 
-    def _begin(self, a, theta_l, lane, stream):
-        """Everything of Alg. 2 between two compressions, for matrix a."""
+    def _begin_and_p_phase(self, a, theta_l, lane, stream, orthonormalize):
+        """Everything of Alg. 2 between two compressions, then the P phase, for matrix a."""
         M, t = self.mats[a], self.t
-        ws, d_hat = self.workspaces[lane], self.delta_hats[lane]
-        if t >= 2 and self.fused:
-            dlcx_ef_delta_apply(M.desc(M.r_prev), M.p_hat, M.q_bar, theta_l, M.ef, M.theta_g, M.v,
-                                self.lr, self.mu, workspace=ws, stream=stream)
+        ws, d_hat, d = self.workspaces[lane], self.delta_hats[lane], M.desc()
+        basis = M.q_bar if (self.warm_start and t >= 2 and M.r_prev == M.r) else M.q_in
+        if self.fused:
+            dlcx_ef_delta_apply_compress(d, M.r_prev if t >= 2 else 0, M.p_hat, M.q_bar, theta_l,
+                                         M.ef, M.theta_g, M.v, self.lr, self.mu, basis,
+                                         M.codes_p, M.scales_p, ws, stream=stream)
         else:
             if t >= 2:
                 dlcx_decompress(M.desc(M.r_prev), M.p_hat, M.q_bar, d_hat, M.ef, workspace=ws,
@@ -115,12 +117,8 @@ class Stage:
             if t >= 2:
                 dlcx_outer_nesterov(M.theta_g, M.v, d_hat, self.lr, self.mu, numel=M.m * M.n,
                                     stream=stream)
-
-    def _p_phase(self, a, lane, stream, orthonormalize):
-        M, t = self.mats[a], self.t
-        ws, d = self.workspaces[lane], M.desc()
-        basis = M.q_bar if (self.warm_start and t >= 2 and M.r_prev == M.r) else M.q_in
-        dlcx_compress_batched(d, PHASE_P, M.ef, basis, M.codes_p, M.scales_p, ws, stream=stream)
+            dlcx_compress_batched(d, PHASE_P, M.ef, basis, M.codes_p, M.scales_p, ws,
+                                  stream=stream)
         if orthonormalize:
             dlcx_average(d, PHASE_P, M.codes_p, M.scales_p, M.p_hat, ws, stream=stream)
         else:  # mean only; the stage orthonormalises all matrices in one batch afterwards
@@ -168,16 +166,14 @@ class Stage:
             main = self._fork()
             for a in range(n):
                 lane, st = self._lane(a)
-                self._begin(a, theta_l_per_matrix[a], lane, st)
-                self._p_phase(a, lane, st, orthonormalize=True)
+                self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st, orthonormalize=True)
                 self._q_phase(a, lane, st, rank=self.measure_rank)
             self._join(main)
             return
         main = self._fork()
         for a in range(n):
             lane, st = self._lane(a)
-            self._begin(a, theta_l_per_matrix[a], lane, st)
-            self._p_phase(a, lane, st, orthonormalize=False)
+            self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st, orthonormalize=False)
         self._join(main)
         descs = [M.desc() for M in self.mats]
         dlcx_orthonormalize_batched(descs, [M.p_hat for M in self.mats], self.batch_ws)

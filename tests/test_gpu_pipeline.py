@@ -114,6 +114,24 @@ def test_lockstep_rounds(case, mma):
         for k in range(K):
             assert rel_l2(factors[k], orc.trace["P"][k]) <= tol, (name, t, "P", k)
             total_flips += _check_codes(name, t, "P", k, codes[k], orc, r * m, qbits, group)
+        # --- the same through the single fused call (error buffers, pseudo-gradients, outer
+        #     update and P-phase compression in one sweep); r_prev = 0 at t = 1
+        efs4 = [to_dev(e) for e in ef0]
+        th4, v4 = to_dev(theta0), to_dev(v0)
+        codes4, scales4 = payload_buffers(d, dlcx.PHASE_P, K)
+        dlcx.dlcx_ef_delta_apply_compress(
+            d, r if t >= 2 else 0, None if p_prev is None else to_dev(p_prev),
+            None if q_prev is None else to_dev(q_prev), [to_dev(x) for x in tl], efs4, th4, v4,
+            synth.LR, synth.MU, to_dev(orc.trace["q_in"]), codes4, scales4, ws)
+        torch.cuda.synchronize()
+        assert rel_l2(to_np(th4), orc.theta) <= tol and rel_l2(to_np(v4), orc.v) <= tol
+        factors4 = to_np(ws[: K * r * m * 4].view(torch.float32)).reshape(K, r, m)
+        for k in range(K):
+            assert rel_l2(to_np(efs4[k]), orc.trace["delta"][k]) <= tol, (name, t, k)
+            assert rel_l2(factors4[k], orc.trace["P"][k]) <= 2 * tol, (name, t, "P fused", k)
+            cw, sw = ref.quantize(factors4[k], qbits, group)
+            assert np.array_equal(to_np(codes4[k]), cw)
+            assert np.array_equal(to_np(scales4[k]).view(np.uint32), sw.view(np.uint32))
         p_hat = torch.zeros(r, m, device=DEV)
         dlcx.dlcx_average(d, dlcx.PHASE_P, [to_dev(c) for c in orc.trace["P_codes"]],
                           [to_dev(s) for s in orc.trace["P_scales"]], p_hat, ws)
