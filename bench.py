@@ -19,13 +19,20 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# HBM bytes per matrix element and launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs of
+# `bench.py --probe --layers 1 --streams 1` (config 2), scaled by a 1 GiB copy in the same run
+# (FETCH_SIZE reads 0.5 KiB per KiB copied, WRITE_SIZE 1.0): profiles/pmc_hbm_traffic_cfg2.txt
+MEASURED_TRAFFIC_BPP = {"round_fused": 58.07, "project_q": 16.48}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_stage(cfg_id, mma, layers, device, fused, streams):
+def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False):
+    """plain=True draws i.i.d. Gaussian replicas instead of the low-rank-plus-noise recipe (no
+    library QR/GEMM kernels in the process: used for hardware-counter runs, where only the
+    traffic of this library's kernels is of interest)."""
     import torch
 
     import synth
@@ -44,9 +51,16 @@ def build_stage(cfg_id, mma, layers, device, fused, streams):
             if alpha is None or alpha == "per-round":
                 alpha = float(0.5 + 1.5 * torch.rand(1, generator=gen).item())
             sigma = float(synth.noise_sigma(cfg_id, m, n))
-            t = synth.torch_matrix_inputs(m, n, K, r, seed=synth.seed_for(cfg_id, layer, idx),
-                                          sigma=sigma, alpha=alpha, theta_l=cfg["theta_l"],
-                                          device=device)
+            if plain:
+                th = 0.02 * torch.randn(m, n, device=device)
+                dt = torch.bfloat16 if cfg["theta_l"] == "bf16" else torch.float32
+                t = dict(theta_g=th, q_in=torch.randn(r, n, device=device),
+                         theta_l=[(th - sigma * torch.randn(m, n, device=device)).to(dt)
+                                  for _ in range(K)])
+            else:
+                t = synth.torch_matrix_inputs(m, n, K, r, seed=synth.seed_for(cfg_id, layer, idx),
+                                              sigma=sigma, alpha=alpha, theta_l=cfg["theta_l"],
+                                              device=device)
             mats.append(MatrixState(t["theta_g"], K, t["q_in"], cfg["qbits"], cfg["group"], mma))
             locals_.append(t["theta_l"])
             idx += 1
@@ -67,6 +81,8 @@ def algorithmic_bytes_per_param(kernel, K, tl_bytes, fused):
         "outer_nesterov": 20,                       # theta, v in/out; delta_hat in
         # fused: e_k in, theta_l,k in, delta_k out per worker + theta, v in/out
         "reconstruct": ((8 + tl_bytes) * K + 16) if fused else (4 + 8 * K),
+        # the fused round kernel: the same, the P-phase projection rides along for free
+        "round_fused": (8 + tl_bytes) * K + 16,
     }
     return table.get(kernel)
 
@@ -113,6 +129,8 @@ def main():
     ap.add_argument("--unfused", action="store_true", help="separate decompress / Nesterov kernels")
     ap.add_argument("--streams", type=int, default=2, help="HIP streams the matrices are dealt to")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe", action="store_true",
+                    help="counter run: plain random inputs, one 1 GiB copy, two steps, no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE MI355X; --gpus %d is not supported "
@@ -131,7 +149,17 @@ def main():
     cfg = synth.CONFIGS[args.config]
     layers = args.layers or cfg["layers"]
     fused = not args.unfused
-    stage, locals_ = build_stage(args.config, args.mma, layers, device, fused, args.streams)
+    stage, locals_ = build_stage(args.config, args.mma, layers, device, fused, args.streams,
+                                 plain=args.probe)
+    if args.probe:
+        x = torch.empty(1 << 28, dtype=torch.float32, device=device)
+        y = torch.empty_like(x)
+        y.copy_(x)  # the plain copy of known size (1 GiB in, 1 GiB out) the counters are scaled by
+        for _ in range(2):
+            stage.step(locals_)
+        torch.cuda.synchronize()
+        print("probe done: %d matrices, 2 steps" % len(stage.mats), file=sys.stderr)
+        return
     K = cfg["K"]
     params = stage.params()
     selector = RankSelector(stage, c=5, r1=cfg["r"], rmin=4, rmax=cfg["r"], H1=125)
@@ -139,8 +167,8 @@ def main():
     log("stage: %d matrices, %.3f G params, K=%d, %.1f GB allocated" %
         (len(stage.mats), params / 1e9, K, torch.cuda.memory_allocated() / 1e9))
 
-    def one_step():
-        stage.step(locals_)
+    def one_step(serial=False):
+        stage.step(locals_, serial=serial)
         # Alg. 3: measure r' on this round's averages (the configuration keeps the rank fixed,
         # so the window rule's output is computed and not applied)
         selector.next(stage.t + 1)
@@ -156,12 +184,13 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     value = params / (dt / args.steps)
 
-    # per-kernel durations: the same steps again with HIP events around every launch
+    # per-kernel durations: the same steps again with HIP events around every launch, all on
+    # one stream so that a kernel's events bracket that kernel alone
     dlcx.dlcx_profile_enable(True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for _ in range(args.steps):
-        one_step()
+        one_step(serial=True)
     torch.cuda.synchronize()
     dt_prof = time.perf_counter() - t1
     prof = dlcx.dlcx_profile_read()
@@ -180,7 +209,9 @@ def main():
         total_bytes = bpp * params * (K if per_worker else 1)
         achieved = total_bytes / (kernels[dom]["ms_per_step"] * 1e-3) / 1e9
         roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": (MEASURED_TRAFFIC_BPP[dom] * params / launches
+                                if dom in MEASURED_TRAFFIC_BPP and args.config == 2 else None),
                     "algorithmic_bytes_per_param_per_launch": bpp,
                     "avg_launch_ms": kernels[dom]["ms_per_step"] / launches,
                     "launches_per_step": launches}
@@ -202,7 +233,7 @@ def main():
                       "achieved_GBps": b_alg * params / (dt / args.steps) / 1e9,
                       "frac_of_8TBps": b_alg * params / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
         "kernels": kernels,
-        "ms_per_step_with_events": dt_prof / args.steps * 1e3,
+        "ms_per_step_serial_with_events": dt_prof / args.steps * 1e3,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(stage, locals_, args.config)

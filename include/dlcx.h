@@ -51,9 +51,11 @@ enum { DLCX_PHASE_P = 0, DLCX_PHASE_Q = 1 };
 enum { DLCX_F32 = 0, DLCX_BF16 = 1 };
 /* arithmetic of the three rank-r products (projections and reconstruction) */
 enum {
-    DLCX_MMA_FMA = 0,      /* fp32 operands, fp64 accumulation on the vector ALU  */
-    DLCX_MMA_F32 = 1,      /* fp32 MFMA, fp32 accumulation                        */
-    DLCX_MMA_BF16 = 2      /* operands rounded to bf16, bf16 MFMA, fp32 accumulate */
+    DLCX_MMA_FMA = 0,  /* fp32 operands, fp64 accumulation on the vector ALU                   */
+    DLCX_MMA_F32 = 1,  /* fp32-accurate on the bf16 matrix cores: operands split into three
+                          bf16 pieces, six piece products, fp32 accumulation (rel-L2 <= 1e-5) */
+    DLCX_MMA_BF16 = 2  /* bf16 matrix cores, operands split into two bf16 pieces, three piece
+                          products, fp32 accumulation (rel-L2 <= 2e-3 with a wide margin)     */
 };
 
 typedef struct {

@@ -91,6 +91,7 @@ class Stage:
             if self.nstreams > 1 else []
         self.rprime_dev = torch.zeros(len(matrices), device=dev, dtype=torch.int32)
         self.batched = batched
+        self.serial = False
         self.batch_ws = None
         if batched:
             nbytes = dlcx_batched_workspace_bytes([M.desc(M.r_max) for M in matrices])
@@ -136,7 +137,7 @@ class Stage:
                                 stream=stream)
 
     def _fork(self):
-        if not self.side:
+        if not self.side or self.serial:
             return None
         main = torch.cuda.current_stream()
         start = torch.cuda.Event()
@@ -154,13 +155,17 @@ class Stage:
             main.wait_event(done)
 
     def _lane(self, a):
+        if self.serial:
+            return 0, None
         lane = a % self.nstreams
         return lane, (self.side[lane] if self.side else None)
 
-    def step(self, theta_l_per_matrix):
+    def step(self, theta_l_per_matrix, serial=False):
         """theta_l_per_matrix[a][i]: local replica i of matrix a after this round's inner steps.
-        Work is issued on the current stream (and the side streams, joined before returning)."""
+        Work is issued on the current stream (and the side streams, joined before returning);
+        serial=True keeps everything on the current stream (kernels then run one at a time)."""
         self.t += 1
+        self.serial = serial
         n = len(self.mats)
         if not self.batched:
             main = self._fork()

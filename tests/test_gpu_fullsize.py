@@ -1,0 +1,198 @@
+"""Parity at the benchmark's full matrix sizes, in the launch configuration bench.py times
+(bf16 MFMA mode, fused round kernel, K = 4, r = 64, int4 / 128, bf16 local replicas).
+
+A full matrix of the ~100B-class stage is too large for the oracle to sweep step by step in a
+test, so the oracle computes (with its unchanged single-threaded routines, called from a thread
+pool on disjoint outputs) the full factors of one round, and every GPU entry point is then fed
+the ORACLE's inputs and checked on sampled outputs: whole quantisation groups of the factors
+(codes bit for bit, boundary flips by one step allowed), and sampled rows of delta, theta and v.
+"""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_21263_amd as dlcx
+import synth
+from oracle import ref
+from gpu_util import DEV, code_mismatch_report, payload_buffers, rel_l2, to_dev, to_np, ws_for
+
+pytestmark = pytest.mark.gpu
+
+POOL = 16
+K, R, QBITS, GROUP, MMA = 4, 64, 4, 128, dlcx.MMA_BF16
+TOL = 2e-3
+
+
+def _bits(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _oracle_full_p(deltas, q_in):
+    """P_k = delta_k Q_in for all rows: row chunks in parallel, each output from one oracle call."""
+    m = deltas[0].shape[0]
+    step = max(128, m // (2 * POOL) // 128 * 128)
+    jobs = [(k, i0) for k in range(len(deltas)) for i0 in range(0, m, step)]
+    out = [np.empty((q_in.shape[0], m), np.float32) for _ in deltas]
+
+    def run(job):
+        k, i0 = job
+        out[k][:, i0:i0 + step] = ref.project_p(np.ascontiguousarray(deltas[k][i0:i0 + step]), q_in)
+
+    with ThreadPoolExecutor(POOL) as ex:
+        list(ex.map(run, jobs))
+    return out
+
+
+def _oracle_q_columns(deltas, p_hat, cols):
+    """Q_k[:, j] for the given columns j (one oracle call per column and worker)."""
+    out = [np.empty((p_hat.shape[0], len(cols)), np.float32) for _ in deltas]
+    jobs = [(k, a) for k in range(len(deltas)) for a in range(len(cols))]
+
+    def run(job):
+        k, a = job
+        out[k][:, a] = ref.project_q_row(deltas[k], p_hat, int(cols[a]))
+
+    with ThreadPoolExecutor(POOL) as ex:
+        list(ex.map(run, jobs))
+    return out
+
+
+def _check_groups(codes_gpu, scales_gpu, factor_ref, L, groups, what):
+    """Bit-compare the payload of whole groups (along L) of every factor column."""
+    G = GROUP
+    flips = 0
+    for g in groups:
+        blk = np.ascontiguousarray(factor_ref[:, g * G:(g + 1) * G])          # (r, G)
+        cw, sw = ref.quantize(blk.reshape(-1), QBITS, G)
+        got_c = np.stack([codes_gpu[(c * L + g * G) // 2:(c * L + (g + 1) * G) // 2]
+                          for c in range(R)]).reshape(-1)
+        got_s = np.array([scales_gpu[(c * L) // G + g] for c in range(R)], np.float32)
+        assert rel_l2(got_s, sw) <= TOL, what
+        nb, ok = code_mismatch_report(got_c, cw, blk, sw, R * G, QBITS, G, ref.unpack_codes)
+        assert ok, (what, g, "code mismatch that is not a one-step boundary flip")
+        flips += nb
+    return flips
+
+
+@pytest.mark.timeout(400)
+@pytest.mark.parametrize("m,n", [(8192, 1024), (8192, 8192), (8192, 28672), (28672, 8192)])
+def test_full_size_matrix_sampled(m, n):
+    print("full-size case %dx%d" % (m, n), flush=True)
+    rs = np.random.default_rng(m + n)
+    sigma = float(synth.noise_sigma(2, m, n))
+    t = synth.torch_matrix_inputs(m, n, K, R, seed=synth.seed_for(77, m, n), sigma=sigma, alpha=1.2,
+                                  theta_l="bf16", device=DEV)
+    theta0 = t["theta_g"].cpu().numpy()
+    tl_bits = [_bits(x) for x in t["theta_l"]]
+    q_in = t["q_in"].cpu().numpy()
+    d = dlcx.desc(m, n, R, QBITS, GROUP, MMA)
+    ws = ws_for(d, K)
+
+    # ---------------- round 1 on the oracle: delta, P, P_hat, sampled Q, (full Q_bar later)
+    zeros = np.zeros(m * n, np.float32)
+    deltas = [ref.delta_ef(theta0.reshape(-1), b.reshape(-1), zeros).reshape(m, n) for b in tl_bits]
+    P = _oracle_full_p(deltas, q_in)
+    payload_p = [ref.quantize(p, QBITS, GROUP) for p in P]
+    p_bar = ref.dequant_average([c for c, _ in payload_p], [s for _, s in payload_p], R * m, QBITS,
+                                GROUP).reshape(R, m)
+    p_hat = ref.orthonormalize(p_bar)
+
+    # ---------------- GPU round 1, the fused entry point the bench uses (r_prev = 0)
+    efs = [torch.zeros(m, n, device=DEV) for _ in range(K)]
+    th, v = t["theta_g"].clone(), torch.zeros(m, n, device=DEV)
+    codes, scales = payload_buffers(d, dlcx.PHASE_P, K)
+    dlcx.dlcx_ef_delta_apply_compress(d, 0, None, None, t["theta_l"], efs, th, v, synth.LR, synth.MU,
+                                      t["q_in"], codes, scales, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(th, t["theta_g"]) and not bool(v.any())       # nothing applied at t = 1
+    rows = np.sort(rs.choice(m, 24, replace=False))
+    for k in range(K):
+        got = efs[k][torch.from_numpy(rows).to(DEV)].cpu().numpy()
+        assert rel_l2(got, deltas[k][rows]) <= 1e-6, ("delta", k)
+    groups_m = rs.choice(m // GROUP, 6, replace=False)
+    flips = 0
+    for k in range(K):
+        flips += _check_groups(to_np(codes[k]), to_np(scales[k]), P[k], m, groups_m, ("P", k))
+    # average + orthonormalisation from the oracle's payloads
+    d_p_hat = torch.zeros(R, m, device=DEV)
+    dlcx.dlcx_average(d, dlcx.PHASE_P, [to_dev(c) for c, _ in payload_p],
+                      [to_dev(s) for _, s in payload_p], d_p_hat, ws)
+    cond = np.linalg.cond(p_bar.astype(np.float64))
+    assert rel_l2(to_np(d_p_hat), p_hat) <= max(1e-5, 4e-7 * cond), cond
+    # Q phase from the oracle's basis: whole groups of columns
+    codes_q, scales_q = payload_buffers(d, dlcx.PHASE_Q, K)
+    efs_oracle = [to_dev(x) for x in deltas]
+    dlcx.dlcx_compress_batched(d, dlcx.PHASE_Q, efs_oracle, to_dev(p_hat), codes_q, scales_q, ws)
+    torch.cuda.synchronize()
+    groups_n = rs.choice(n // GROUP, 3, replace=False)
+    cols = np.concatenate([np.arange(g * GROUP, (g + 1) * GROUP) for g in groups_n])
+    Qs = _oracle_q_columns(deltas, p_hat, cols)
+    for k in range(K):
+        cg, sg = to_np(codes_q[k]), to_np(scales_q[k])
+        for a, g in enumerate(groups_n):
+            blk = np.ascontiguousarray(Qs[k][:, a * GROUP:(a + 1) * GROUP])
+            cw, sw = ref.quantize(blk.reshape(-1), QBITS, GROUP)
+            got_c = np.stack([cg[(c * n + g * GROUP) // 2:(c * n + (g + 1) * GROUP) // 2]
+                              for c in range(R)]).reshape(-1)
+            got_s = np.array([sg[(c * n) // GROUP + g] for c in range(R)], np.float32)
+            assert rel_l2(got_s, sw) <= TOL, ("Q scales", k)
+            nb, ok = code_mismatch_report(got_c, cw, blk, sw, R * GROUP, QBITS, GROUP,
+                                          ref.unpack_codes)
+            assert ok, ("Q", k, g)
+            flips += nb
+    assert flips <= 2e-3 * K * R * GROUP * (len(groups_m) + len(groups_n)), flips
+    del efs_oracle
+
+    # ---------------- round 2, fused: error buffers, new delta, outer update, sampled
+    # The previous average for the check is any rank-r pair: the oracle's P_hat and a Q_bar made
+    # of the sampled columns' structure is not available in full, so use a seeded Q_bar instead.
+    q_bar = (rs.standard_normal((R, n)) * (np.arange(1, R + 1)[:, None] ** -1.0) * 1e-2).astype(np.float32)
+    tl2 = [synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(b) + np.float32(1e-4) * rs.standard_normal((m, n)).astype(np.float32))
+           for b in tl_bits[:K]]
+    efs2 = [to_dev(x) for x in deltas]
+    th2, v2 = t["theta_g"].clone(), torch.zeros(m, n, device=DEV)
+    v_host = (1e-4 * rs.standard_normal((m, n))).astype(np.float32)
+    v2.copy_(to_dev(v_host))
+    codes2, scales2 = payload_buffers(d, dlcx.PHASE_P, K)
+    dlcx.dlcx_ef_delta_apply_compress(d, R, to_dev(p_hat), to_dev(q_bar), [to_dev(x) for x in tl2],
+                                      efs2, th2, v2, synth.LR, synth.MU, to_dev(q_bar), codes2,
+                                      scales2, ws)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(rows).to(DEV)
+    d_hat_rows = ref.reconstruct(np.ascontiguousarray(p_hat[:, rows]), q_bar)          # (24, n)
+    th_w, v_w = theta0[rows].copy(), v_host[rows].copy()
+    new_delta = []
+    for k in range(K):
+        e = deltas[k][rows].copy()
+        ref.ef_update(e.reshape(-1), d_hat_rows.reshape(-1))
+        new_delta.append(ref.delta_ef(theta0[rows].reshape(-1), np.ascontiguousarray(tl2[k][rows]).reshape(-1),
+                                      e.reshape(-1)).reshape(len(rows), n))
+    ref.outer_nesterov(th_w.reshape(-1), v_w.reshape(-1), d_hat_rows.reshape(-1), synth.LR, synth.MU)
+    for k in range(K):
+        got = efs2[k][idx].cpu().numpy()
+        assert rel_l2(got, new_delta[k]) <= TOL, ("delta round 2", k)
+        # the part the kernel subtracts is the decompressed average: check it at the MFMA bar
+        base = deltas[k][rows] + (theta0[rows] - synth.bf16_bits_to_f32(tl2[k][rows]))
+        assert rel_l2(base - got, d_hat_rows) <= TOL, ("delta_hat via delta", k)
+    assert rel_l2(theta0[rows] - th2[idx].cpu().numpy(), theta0[rows] - th_w) <= TOL
+    assert rel_l2(v2[idx].cpu().numpy(), v_w) <= TOL
+    # P phase of round 2 on the sampled groups needs the full new delta: rows of whole groups
+    g0 = int(groups_m[0])
+    grp_rows = np.arange(g0 * GROUP, (g0 + 1) * GROUP)
+    d_hat_g = ref.reconstruct(np.ascontiguousarray(p_hat[:, grp_rows]), q_bar)
+    for k in range(K):
+        e = deltas[k][grp_rows].copy()
+        ref.ef_update(e.reshape(-1), d_hat_g.reshape(-1))
+        nd = ref.delta_ef(theta0[grp_rows].reshape(-1), np.ascontiguousarray(tl2[k][grp_rows]).reshape(-1),
+                          e.reshape(-1)).reshape(GROUP, n)
+        p_rows = ref.project_p(nd, q_bar)                                             # (r, 128)
+        cw, sw = ref.quantize(np.ascontiguousarray(p_rows).reshape(-1), QBITS, GROUP)
+        cg, sg = to_np(codes2[k]), to_np(scales2[k])
+        got_s = np.array([sg[(c * m) // GROUP + g0] for c in range(R)], np.float32)
+        got_c = np.stack([cg[(c * m + g0 * GROUP) // 2:(c * m + (g0 + 1) * GROUP) // 2]
+                          for c in range(R)]).reshape(-1)
+        assert rel_l2(got_s, sw) <= TOL, ("P round 2 scales", k)
+        nb, ok = code_mismatch_report(got_c, cw, p_rows, sw, R * GROUP, QBITS, GROUP, ref.unpack_codes)
+        assert ok and nb <= 0.02 * R * GROUP, ("P round 2 payload", k, nb)
