@@ -127,8 +127,10 @@ def main():
     ap.add_argument("--mma", type=int, default=2, help="0 fma/fp64-acc, 1 fp32-accurate MFMA, 2 bf16 MFMA")
     ap.add_argument("--layers", type=int, default=0, help="layers resident (0 = the whole stage)")
     ap.add_argument("--unfused", action="store_true", help="separate decompress / Nesterov kernels")
-    ap.add_argument("--streams", type=int, default=2, help="HIP streams the matrices are dealt to")
+    ap.add_argument("--streams", type=int, default=3, help="HIP streams the matrices are dealt to")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-load", type=int, default=0,
+                    help="bf16 8192^3 GEMMs issued on a second stream per outer step (config 4)")
     ap.add_argument("--probe", action="store_true",
                     help="counter run: plain random inputs, one 1 GiB copy, two steps, no timing")
     args = ap.parse_args()
@@ -148,6 +150,10 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
     layers = args.layers or cfg["layers"]
+    if args.config == 4 and not args.layers:
+        # K = 8 replicas of the full stage need 479 GB: time a window of 5 of the 10 identical,
+        # independent layers with persistent state (value stays parameters per second)
+        layers = 5
     fused = not args.unfused
     stage, locals_ = build_stage(args.config, args.mma, layers, device, fused, args.streams,
                                  plain=args.probe)
@@ -162,16 +168,39 @@ def main():
         return
     K = cfg["K"]
     params = stage.params()
-    selector = RankSelector(stage, c=5, r1=cfg["r"], rmin=4, rmax=cfg["r"], H1=125)
+    selector = RankSelector(stage, c=cfg.get("window", 5), r1=cfg["r"], rmin=cfg.get("rmin", 4),
+                            rmax=cfg.get("rmax", cfg["r"]), H1=125)
     selector.first()
+    adaptive = args.config == 3
+    ranks = []
+    load = None
+    if args.gemm_load:
+        # synthetic inner-step load: bf16 GEMMs 8192^3 on a stream of their own
+        load = {"stream": torch.cuda.Stream(device=device),
+                "a": torch.randn(8192, 8192, device=device, dtype=torch.bfloat16),
+                "b": torch.randn(8192, 8192, device=device, dtype=torch.bfloat16),
+                "c": torch.empty(8192, 8192, device=device, dtype=torch.bfloat16), "n": 0}
     log("stage: %d matrices, %.3f G params, K=%d, %.1f GB allocated" %
         (len(stage.mats), params / 1e9, K, torch.cuda.memory_allocated() / 1e9))
 
     def one_step(serial=False):
+        if load is not None:
+            with torch.cuda.stream(load["stream"]):
+                for _ in range(args.gemm_load):
+                    torch.matmul(load["a"], load["b"], out=load["c"])
+            load["n"] += args.gemm_load
         stage.step(locals_, serial=serial)
-        # Alg. 3: measure r' on this round's averages (the configuration keeps the rank fixed,
-        # so the window rule's output is computed and not applied)
-        selector.next(stage.t + 1)
+        # Alg. 3: measure r' on this round's averages and apply the window rule; only the
+        # adaptive configuration lets the result change the rank of the next compression
+        rp, r_next, _ = selector.next(stage.t + 1)
+        ranks.append((rp, r_next))
+        if adaptive:
+            for M in stage.mats:
+                if r_next > M.r:  # fresh seeded columns for a basis that grows
+                    M.q_bar[M.r:r_next].normal_()
+                M.r = r_next
+        if load is not None:
+            torch.cuda.current_stream().wait_stream(load["stream"])
 
     for _ in range(args.warmup):
         one_step()
@@ -234,6 +263,7 @@ def main():
                       "frac_of_8TBps": b_alg * params / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
         "kernels": kernels,
         "ms_per_step_serial_with_events": dt_prof / args.steps * 1e3,
+        "rank_trace": ranks[-(2 * args.steps):][:args.steps],
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(stage, locals_, args.config)

@@ -30,12 +30,12 @@ Timed::Timed(int kid, hipStream_t s) : slot(-1), st(s) {
     ProfRec r;
     r.kid = kid;
     if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
-    hipEventRecord(r.a, st);
+    if (hipEventRecord(r.a, st) != hipSuccess) return;
     g_prof.push_back(r);
     slot = (int)g_prof.size() - 1;
 }
 Timed::~Timed() {
-    if (slot >= 0) hipEventRecord(g_prof[slot].b, st);
+    if (slot >= 0) (void)hipEventRecord(g_prof[slot].b, st);
 }
 
 // k_gemm_fma.hip
@@ -135,8 +135,8 @@ static const char *const kKernelNames[KID_COUNT] = {
 
 int dlcx_profile_enable(int on) {
     for (auto &r : g_prof) {
-        hipEventDestroy(r.a);
-        hipEventDestroy(r.b);
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
     }
     g_prof.clear();
     g_prof_on = on != 0;

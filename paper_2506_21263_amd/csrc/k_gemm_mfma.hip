@@ -947,6 +947,7 @@ int launch_reconstruct_mfma(int mma, int64_t m, int64_t n, int r, const float *p
 }
 
 // ---- fused round: workspace layout and launch ------------------------------------------------
+static int kRoundWgTarget = 512;  // workgroups wanted per launch (column ranges per row block)
 struct RoundPlan {
     int chunks;        // column ranges per row block = slabs per worker
     int64_t cols;      // columns per workgroup (multiple of 256)
@@ -958,7 +959,7 @@ static RoundPlan round_plan(int64_t m, int64_t n, int r) {
     const int cb = cb_of(r);
     p.kc = cb <= 2 ? 4 : cb == 4 ? 2 : 1;
     const int64_t rows = ceil_div(m, 32);
-    int64_t chunks = ceil_div(512, rows);
+    int64_t chunks = ceil_div(kRoundWgTarget, rows);
     const int64_t max_chunks = ceil_div(n, 256);
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks > 4) chunks = 4;

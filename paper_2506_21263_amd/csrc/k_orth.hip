@@ -256,6 +256,7 @@ void orth_item(FactorItem *it, float *p, int64_t L, int r, void *workspace) {
     it->part = reinterpret_cast<double *>(workspace);
     it->g = it->part + (size_t)it->nchunks * r * r;
     it->w = it->g + (size_t)r * (r + 1);
+    it->out = nullptr;
 }
 
 int launch_orthonormalize_batch(const FactorBatch &batch, hipStream_t st) {

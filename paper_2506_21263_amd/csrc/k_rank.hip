@@ -9,7 +9,7 @@
 
 namespace dlcx {
 
-constexpr int kJT = 256;        // threads: 16 teams of 16 lanes, one column pair per team
+constexpr int kJT = 1024;       // at most 64 teams of 16 lanes, one column pair per team
 constexpr int kMaxSweeps = 40;
 
 __device__ __forceinline__ double team_sum(double v) {
@@ -21,6 +21,7 @@ __device__ __forceinline__ double team_sum(double v) {
 constexpr size_t kJacobiLdsMax = 140 * 1024;
 
 __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, double tau) {
+    const int nthreads = blockDim.x;  // 256 for small matrices, 1024 when r > 128
     extern __shared__ double smem[];
     const FactorItem it = batch.it[blockIdx.x];
     const int r = it.r, nchunks = it.nchunks;
@@ -33,7 +34,7 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, dou
     __shared__ double sorted[DLCX_MAX_RANK];
     __shared__ int rotated;
     const int tid = threadIdx.x;
-    for (int x = tid; x < re * re; x += kJT) {
+    for (int x = tid; x < re * re; x += nthreads) {
         const int col = x / re, row = x % re;
         double s = 0.0;
         if (col < r && row < r) {
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, dou
         if (tid == 0) rotated = 0;
         __syncthreads();
         for (int step = 0; step < re - 1; ++step) {
-            for (int pr = team; pr < npairs; pr += kJT / 16) {
+            for (int pr = team; pr < npairs; pr += nthreads / 16) {
                 // round-robin tournament: pair 0 is (re-1, step); pair k is
                 // ((step + k) mod (re-1), (step - k) mod (re-1))
                 int p, q;
@@ -89,13 +90,13 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, dou
         __syncthreads();
         if (!any) break;
     }
-    for (int c = tid; c < r; c += kJT) {
+    for (int c = tid; c < r; c += nthreads) {
         double s = 0.0;
         for (int i = 0; i < re; ++i) s = fma(a[c * re + i], a[c * re + i], s);
         eig[c] = sqrt(s);
     }
     __syncthreads();
-    for (int c = tid; c < r; c += kJT) {  // rank sort, descending, ties by index
+    for (int c = tid; c < r; c += nthreads) {  // rank sort, descending, ties by index
         const double e = eig[c];
         int pos = 0;
         for (int u = 0; u < r; ++u) pos += (eig[u] > e) || (eig[u] == e && u < c);
@@ -157,8 +158,10 @@ int launch_effective_rank_batch(const FactorBatch &batch, double tau, hipStream_
         granted = bytes;
     }
     Timed timed(KID_JACOBI, st);
-    hipLaunchKernelGGL(jacobi_rank_kernel, dim3((unsigned)batch.n), dim3(kJT), bytes, st, batch,
-                       tau);
+    int rmax = 0;
+    for (int i = 0; i < batch.n; ++i) rmax = batch.it[i].r > rmax ? batch.it[i].r : rmax;
+    hipLaunchKernelGGL(jacobi_rank_kernel, dim3((unsigned)batch.n), dim3(rmax > 128 ? 1024 : 256),
+                       bytes, st, batch, tau);
     return check_launch("jacobi_rank");
 }
 

@@ -104,7 +104,9 @@ class Stage:
         """Everything of Alg. 2 between two compressions, then the P phase, for matrix a."""
         M, t = self.mats[a], self.t
         ws, d_hat, d = self.workspaces[lane], self.delta_hats[lane], M.desc()
-        basis = M.q_bar if (self.warm_start and t >= 2 and M.r_prev == M.r) else M.q_in
+        # warm start: Q_bar of the previous round; after a rank change its first M.r columns
+        # (the caller has filled columns beyond the previous rank with fresh draws)
+        basis = M.q_bar if (self.warm_start and t >= 2) else M.q_in
         if self.fused:
             dlcx_ef_delta_apply_compress(d, M.r_prev if t >= 2 else 0, M.p_hat, M.q_bar, theta_l,
                                          M.ef, M.theta_g, M.v, self.lr, self.mu, basis,

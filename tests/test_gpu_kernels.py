@@ -298,3 +298,32 @@ def test_select_rank_stage_value_and_window():
     assert rp == 19
     want_r, want_H = ref.adagradcmp([256, 256, 256, 256, 19], 5, 5, 256, 4, 256, 125)
     assert (r_next, H) == (want_r, want_H)
+
+
+def test_batched_orthonormalize_and_rank_mixed_shapes():
+    # 70 factors of different lengths and ranks in one call (more than one launch chunk of 64):
+    # same results as the one-matrix entry points, which are checked against the oracle above.
+    g = rng(4242)
+    shapes = [(256 + 16 * (i % 9), 8 + (i * 7) % 57) for i in range(70)]      # (L, r)
+    shapes[3] = (2048, 200)                                                   # global-memory path
+    descs, ps, qs, ps_single = [], [], [], []
+    for L, r in shapes:
+        descs.append(dlcx.desc(L, L, r, 4, 16))
+        a = (g.standard_normal((r, L)) * (np.arange(1, r + 1)[:, None] ** -1.0)).astype(np.float32)
+        ps.append(to_dev(a))
+        ps_single.append(to_dev(a))
+        qs.append(to_dev(a))
+    ws = torch.empty(dlcx.dlcx_batched_workspace_bytes(descs), device=DEV, dtype=torch.uint8)
+    out = torch.zeros(len(descs), device=DEV, dtype=torch.int32)
+    dlcx.dlcx_effective_rank_batched(descs, qs, 0.9, out, ws)
+    dlcx.dlcx_orthonormalize_batched(descs, ps, ws)
+    one = torch.zeros(1, device=DEV, dtype=torch.int32)
+    for i, (L, r) in enumerate(shapes):
+        w1 = torch.empty(dlcx.dlcx_workspace_bytes(descs[i], 1), device=DEV, dtype=torch.uint8)
+        dlcx.dlcx_orthonormalize(L, r, ps_single[i], w1)
+        assert torch.equal(ps[i], ps_single[i]), i
+        dlcx.dlcx_effective_rank(L, r, qs[i], 0.9, one, w1)
+        assert int(one.item()) == int(out[i].item()), i
+    for i in (0, 3, 17, 69):
+        assert int(out[i].item()) == ref.effective_rank(to_np(qs[i]), 0.9)
+        assert rel_l2(to_np(ps[i]), ref.orthonormalize(to_np(qs[i]))) <= 1e-5

@@ -15,6 +15,8 @@ of test follow from that:
   well defined is checked (the flip is by one step on a boundary value, theta_g at a loose bar,
   and the error-feedback telescoping identity of the GPU's own outputs).
 """
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -230,3 +232,70 @@ def test_multi_stream_stage_equals_single_stream():
             for x, y in zip(A.ef, B.ef):
                 assert torch.equal(x, y)
         assert torch.equal(one.rprime_dev, other.rprime_dev)
+
+
+def test_adaptive_rank_rounds_config3_like():
+    # Alg. 3 end to end on a small stage: 3 matrices, r_1 = 32, window c = 3, bounds [4, 32],
+    # spectra that decay faster every round, so the measured r' and with it the rank shrink and
+    # every width of the MFMA tiles is exercised.  The GPU is re-seeded with the oracle's state
+    # at the start of each round (lockstep at round granularity); r', r_t and H_t are integers
+    # and must agree exactly.
+    shapes = [(256, 384), (384, 256), (512, 512)]
+    K, r1, c, rmin, H1, qbits, group = 2, 32, 3, 4, 125, 4, 64
+    T = 7
+    alphas = [0.5, 0.75, 1.0, 1.5, 2.0, 2.5, 3.0]
+    inps = [synth.MatrixInputs(m, n, K, r1, seed=900 + a, sigma=2e-4, alpha=1.0, theta_l="bf16")
+            for a, (m, n) in enumerate(shapes)]
+    orcs = [pipeline.MatrixOracle(inp.theta_g, K, inp.q_in, qbits, group, synth.LR, synth.MU)
+            for inp in inps]
+    hist_o = [r1]
+    hist_g = (ctypes.c_int32 * c)()
+    rp, r_t, H = dlcx.dlcx_select_rank_from(None, 0, hist_g, 1, c, r1, rmin, r1, H1, rprime=r1)
+    assert (r_t, H) == ref.adagradcmp(hist_o, 1, c, r1, rmin, r1, H1)
+    r_now = r1
+    for t in range(1, T + 1):
+        mats, tls = [], []
+        for inp, orc in zip(inps, orcs):
+            M = MatrixState(to_dev(orc.theta), K, to_dev(orc.q_in), qbits, group, dlcx.MMA_BF16,
+                            r_max=r1)
+            M.v.copy_(to_dev(orc.v))
+            for k in range(K):
+                M.ef[k].copy_(to_dev(orc.ef[k]))
+            if orc.p_hat is not None:
+                M.r_prev = orc.p_hat.shape[0]
+                M.p_hat.view(-1)[: orc.p_hat.size].copy_(to_dev(orc.p_hat).view(-1))
+                M.q_bar.view(-1)[: orc.q_bar.size].copy_(to_dev(orc.q_bar).view(-1))
+            mats.append(M)
+            tls.append([inp.theta_local(orc.theta, t, i, alpha=alphas[t - 1]) for i in range(K)])
+        st = Stage(mats, synth.LR, synth.MU, fused=True, warm_start=False, measure_rank=True)
+        st.t = t - 1
+        for orc, tl in zip(orcs, tls):
+            orc.step(tl)
+        st.step([[to_dev(x) for x in tl] for tl in tls])
+        torch.cuda.synchronize()
+        for M, orc in zip(mats, orcs):
+            assert M.r == r_now and orc.q_bar.shape[0] == r_now
+            assert rel_l2(to_np(M.theta_g), orc.theta) <= 2e-3
+            for k in range(K):
+                assert rel_l2(to_np(M.ef[k]), orc.trace["delta"][k]) <= 2e-3
+        # r' per matrix on each side's own average, then the stage value and the window rule
+        want_rp = [ref.effective_rank(orc.q_bar, 0.99) for orc in orcs]
+        got_rp = to_np(st.rprime_dev).tolist()
+        # the GPU's Q_bar differs from the oracle's after code flips: re-measure on the oracle's
+        ws = torch.empty(dlcx.dlcx_batched_workspace_bytes([M.desc() for M in mats]), device=DEV,
+                         dtype=torch.uint8)
+        out = torch.zeros(len(mats), device=DEV, dtype=torch.int32)
+        dlcx.dlcx_effective_rank_batched([M.desc() for M in mats],
+                                         [to_dev(orc.q_bar) for orc in orcs], 0.99, out, ws)
+        assert to_np(out).tolist() == want_rp, (t, got_rp, want_rp)
+        hist_o.append(pipeline.stage_rprime(want_rp, rmin))
+        want_r, want_H = ref.adagradcmp(hist_o, t + 1, c, r1, rmin, r1, H1)
+        rp, r_next, H_next = dlcx.dlcx_select_rank_from(out, len(mats), hist_g, t + 1, c, r1, rmin,
+                                                        r1, H1)
+        assert (rp, r_next, H_next) == (hist_o[-1], want_r, want_H), t
+        # next round's basis: warm start, resized to the new rank, on the oracle side
+        for inp, orc in zip(inps, orcs):
+            fresh = inp.fresh_basis_columns(t, max(0, r_next - r_now))
+            orc.set_basis(pipeline.next_basis(orc.q_bar, r_next, fresh))
+        r_now = r_next
+    assert r_now < r1, "the rank was expected to shrink with the steeper spectra"
