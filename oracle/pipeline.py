@@ -30,8 +30,10 @@ def _mean64(factors):
 
 
 class MatrixOracle:
-    def __init__(self, theta_g, K, q_in, qbits, group, lr=0.7, mu=0.9):
-        """qbits None switches the quantiser off (factors averaged exactly)."""
+    def __init__(self, theta_g, K, q_in, qbits, group, lr=0.7, mu=0.9, requant=False):
+        """qbits None switches the quantiser off (factors averaged exactly); requant re-encodes
+        each averaged factor to q bits, as a low-bit reduction would hand it on."""
+        self.requant = requant
         self.m, self.n = theta_g.shape
         self.K = K
         self.theta = np.ascontiguousarray(theta_g, np.float32).copy()
@@ -59,6 +61,8 @@ class MatrixOracle:
         self.trace[tag + "_codes"] = codes
         self.trace[tag + "_scales"] = scales
         flat = ref.dequant_average(codes, scales, factors[0].size, self.qbits, self.group)
+        if self.requant:
+            flat = requantize(flat, self.qbits, self.group)
         return flat.reshape(factors[0].shape)
 
     def step(self, theta_l):
@@ -99,6 +103,74 @@ class MatrixOracle:
 
     def set_basis(self, q_in):
         self.q_in = np.ascontiguousarray(q_in, np.float32).copy()
+
+
+class TensorOracle:
+    """The outer step of Alg. 2 with the compressor reduced to its quantiser.
+
+    Alg. 1 with the LOWRANK step left out, C(delta) = QUANTIZE(delta | q), is the setting the
+    paper reports for its smaller model (Sec. 4.1: Int4 only, no rank adaptation) and the only
+    one that applies to tensors that are not matrices (norm weights, biases).  The tensor is a
+    flat array whose length is a multiple of the group size; groups are runs of `group`
+    consecutive elements.  Same schedule as MatrixOracle:
+
+      t >= 2 :  e_i      <- delta_i^{t-1} - Delta^{t-1}
+                delta_i  <- (theta^{t-1} - theta_i^t) + e_i
+      t >= 2 :  theta^t  <- OuterOpt(theta^{t-1}, Delta^{t-1})
+                Delta^t  <- mean_i dequant(QUANTIZE(delta_i^t))   [re-encoded to q bits if requant]
+    """
+
+    def __init__(self, theta_g, K, qbits, group, lr=0.7, mu=0.9, requant=False):
+        self.theta = np.ascontiguousarray(theta_g, np.float32).reshape(-1).copy()
+        self.numel = self.theta.size
+        assert self.numel % group == 0
+        self.K, self.qbits, self.group = K, qbits, group
+        self.lr, self.mu, self.requant = lr, mu, requant
+        self.v = np.zeros_like(self.theta)
+        self.ef = [np.zeros_like(self.theta) for _ in range(K)]
+        self.codes, self.scales = None, None
+        self.t = 0
+        self.n_applied = 0
+        self.trace = {}
+
+    def delta_hat(self):
+        """Delta of the last completed compression (what the next round applies and feeds back)."""
+        mean = ref.dequant_average(self.codes, self.scales, self.numel, self.qbits, self.group)
+        if self.requant:
+            mean = requantize(mean, self.qbits, self.group)
+        return mean
+
+    def step(self, theta_l):
+        self.t += 1
+        self.trace = {}
+        d_hat_prev = None
+        if self.t >= 2:
+            d_hat_prev = self.delta_hat()
+            self.trace["delta_hat_prev"] = d_hat_prev
+            for i in range(self.K):
+                ref.ef_update(self.ef[i], d_hat_prev)
+            self.trace["e"] = [e.copy() for e in self.ef]
+        for i in range(self.K):
+            tl = np.ascontiguousarray(theta_l[i]).reshape(-1)
+            self.ef[i] = ref.delta_ef(self.theta, tl, self.ef[i])
+        self.trace["delta"] = [d.copy() for d in self.ef]
+        if self.t >= 2:
+            ref.outer_nesterov(self.theta, self.v, d_hat_prev, self.lr, self.mu)
+            self.n_applied += 1
+        self.codes, self.scales = [], []
+        for i in range(self.K):
+            c, s = ref.quantize(self.ef[i], self.qbits, self.group)
+            self.codes.append(c)
+            self.scales.append(s)
+        return self.codes, self.scales
+
+
+def requantize(x, qbits, group):
+    """A mean re-encoded to q bits, as a low-bit reduction would hand it on: the quantiser
+    followed by its decoder."""
+    shape = x.shape
+    c, s = ref.quantize(np.ascontiguousarray(x, np.float32).reshape(-1), qbits, group)
+    return ref.dequantize(c, s, x.size, qbits, group).reshape(shape)
 
 
 def next_basis(q_bar, r_new, fresh):

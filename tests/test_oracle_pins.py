@@ -413,3 +413,170 @@ def test_compression_error_is_a_contraction():
     mean_delta = np.mean([d.astype(np.float64) for d in orc.trace["delta"]], axis=0)
     err = np.sum((orc.delta_hat() - mean_delta) ** 2)
     assert err < np.sum(mean_delta ** 2)
+
+
+# --------------------------------------------------------------------------- quantise-only step
+def _tensor_rounds(numel, K, T, qbits, group, seed, requant=False, kind="f32"):
+    rng = np.random.default_rng(seed)
+    theta0 = (0.02 * rng.standard_normal(numel)).astype(np.float32)
+    orc = pipeline.TensorOracle(theta0, K, qbits, group, synth.LR, synth.MU, requant=requant)
+    sum_g = [np.zeros(numel, np.float64) for _ in range(K)]
+    sum_dhat = np.zeros(numel, np.float64)
+    thetas = [orc.theta.copy()]
+    for t in range(1, T + 1):
+        tl = []
+        for i in range(K):
+            g = 1e-2 * rng.standard_normal(numel) * (1.0 + rng.uniform(0, 3, numel) ** 4)
+            x = (orc.theta.astype(np.float64) - g).astype(np.float32)
+            if kind == "bf16":
+                x = synth.f32_to_bf16_bits(x)
+                sum_g[i] += orc.theta.astype(np.float64) - synth.bf16_bits_to_f32(x)
+            else:
+                sum_g[i] += orc.theta.astype(np.float64) - x
+            tl.append(x)
+        orc.step(tl)
+        sum_dhat += orc.delta_hat()
+        thetas.append(orc.theta.copy())
+    return orc, sum_g, sum_dhat, thetas
+
+
+@pytest.mark.parametrize("requant", [False, True])
+def test_tensor_step_telescoping_and_delay(requant):
+    # The error-feedback identity holds for any compressor, so it pins the order of the
+    # error-buffer update and the pseudo-gradient of Alg. 2 without reference to the quantiser.
+    T, K = 4, 3
+    orc, sum_g, sum_dhat, thetas = _tensor_rounds(1024, K, T, 4, 64, seed=11, requant=requant,
+                                                  kind="bf16")
+    d_hat = orc.delta_hat().astype(np.float64)
+    for i in range(K):
+        e_next = orc.ef[i].astype(np.float64) - d_hat
+        assert rel(sum_dhat + e_next, sum_g[i]) < 1e-6 * T
+    assert np.array_equal(thetas[1], thetas[0])      # nothing applied at t = 1
+    assert not np.array_equal(thetas[2], thetas[1])
+    assert orc.n_applied == T - 1
+
+
+@pytest.mark.parametrize("qbits,group", [(4, 64), (8, 16)])
+def test_tensor_step_single_worker_half_step_bound(qbits, group):
+    # K = 1: Delta is the decoded payload, so the error buffer of the next round is the
+    # quantisation residual, at most half a step of its group.
+    orc, _, _, _ = _tensor_rounds(512, 1, 2, qbits, group, seed=12)
+    delta = orc.ef[0]
+    resid = np.abs(delta.astype(np.float64) - orc.delta_hat())
+    qmax = 2 ** (qbits - 1) - 1
+    amax = np.abs(delta).reshape(-1, group).max(axis=1)
+    bound = np.repeat(amax / qmax / 2 * (1 + 2.0 ** -20), group)
+    assert np.all(resid <= bound)
+    assert resid.max() > 0
+
+
+def test_tensor_step_exact_grid_follows_nesterov_closed_form():
+    # Pseudo-gradients that sit exactly on the int8 grid (multiples of 2^-7, one element at
+    # 127 * 2^-7 per group) pass the quantiser unchanged: e stays 0 and theta follows the closed
+    # form of SGD with Nesterov momentum for a constant gradient, one round late.
+    g = read_golden("nesterov_closed_form.txt")
+    lr, mu = g["lr"][0], g["mu"][0]
+    numel, group = 64, 16
+    grad = (RNG.integers(-126, 127, numel) / 128.0).astype(np.float32)
+    grad[::group] = 127.0 / 128.0
+    theta0 = np.zeros(numel, np.float32)
+    orc = pipeline.TensorOracle(theta0, 1, 8, group, lr, mu)
+    for t in range(1, 5):
+        tl = (orc.theta.astype(np.float64) - grad).astype(np.float32)
+        orc.step([tl])
+        # from round 3 on theta is off the grid, so the replica difference carries one fp32
+        # rounding of theta; the codes are unchanged and the residual stays at that level
+        assert np.allclose(orc.trace["delta"][0], grad, rtol=0, atol=1e-6)
+        applied = t - 1
+        closed = -lr * (applied / (1 - mu) - mu ** 2 * (1 - mu ** applied) / (1 - mu) ** 2)
+        assert np.allclose(orc.theta, closed * grad, rtol=3e-6, atol=1e-6)
+    # first round on an all-zero state is exact: Delta == grad bit for bit, residual zero
+    orc = pipeline.TensorOracle(theta0, 1, 8, group, lr, mu)
+    orc.step([(-grad).astype(np.float32)])
+    assert np.array_equal(orc.delta_hat(), grad)
+
+
+def test_tensor_step_mean_is_taken_over_workers_hand_example():
+    # two workers, int8, one group of 16: worker 0 moves element 0 by -1, worker 1 by -3
+    # (replica = theta - g) => delta = (1, 3), each exactly representable => Delta[0] = 2.
+    theta0 = np.zeros(16, np.float32)
+    tl0, tl1 = theta0.copy(), theta0.copy()
+    tl0[0], tl1[0] = -1.0, -3.0
+    orc = pipeline.TensorOracle(theta0, 2, 8, 16, lr=0.5, mu=0.0)
+    orc.step([tl0, tl1])
+    assert orc.delta_hat()[0] == 2.0
+    assert np.all(orc.delta_hat()[1:] == 0.0)
+    orc.step([theta0.copy(), theta0.copy()])       # replicas did not move in round 2
+    assert orc.theta[0] == -1.0                      # theta^2 = theta^1 - 0.5 * 2
+    # e_i = delta_i - Delta = (-1, +1); round 2 forms delta against theta^1 = 0
+    assert orc.trace["delta"][0][0] == -1.0 and orc.trace["delta"][1][0] == 1.0
+
+
+def test_requantized_mean_is_a_fixed_point_and_within_half_a_step():
+    # Re-encoding a mean to q bits: the decoder output is a fixed point of the quantiser, the
+    # error is at most half a step of the mean's own group, and with one worker (the mean is
+    # already a decoded payload) nothing changes.
+    x = RNG.standard_normal(4096).astype(np.float32)
+    for qbits, group in ((4, 128), (8, 64)):
+        y = pipeline.requantize(x, qbits, group)
+        assert np.array_equal(pipeline.requantize(y, qbits, group), y)
+        qmax = 2 ** (qbits - 1) - 1
+        step = np.repeat(np.abs(x).reshape(-1, group).max(axis=1) / qmax, group)
+        assert np.all(np.abs(x.astype(np.float64) - y) <= step / 2 * (1 + 2.0 ** -20))
+    a, _, _, _ = _tensor_rounds(512, 1, 3, 4, 64, seed=13, requant=False)
+    b, _, _, _ = _tensor_rounds(512, 1, 3, 4, 64, seed=13, requant=True)
+    assert np.array_equal(a.theta, b.theta) and np.array_equal(a.ef[0], b.ef[0])
+
+
+def test_requantized_factor_average_changes_only_within_the_bound():
+    inp = synth.MatrixInputs(64, 128, 3, 4, seed=21, sigma=1e-3, alpha=1.0)
+    tl = [inp.theta_local(inp.theta_g, 1, i) for i in range(3)]
+    plain = pipeline.MatrixOracle(inp.theta_g, 3, inp.q_in, 4, 64)
+    req = pipeline.MatrixOracle(inp.theta_g, 3, inp.q_in, 4, 64, requant=True)
+    plain.step(tl)
+    req.step(tl)
+    # P phase: same payloads, the re-encoded mean differs from the mean by <= half a step
+    pb, rb = plain.trace["p_bar"], req.trace["p_bar"]
+    step = np.repeat(np.abs(pb).reshape(-1, 64).max(axis=1) / 7, 64).reshape(pb.shape)
+    assert np.all(np.abs(pb.astype(np.float64) - rb) <= step / 2 * (1 + 2.0 ** -20))
+    assert not np.array_equal(pb, rb)
+
+
+# --------------------------------------------------------------------------- communication model
+def test_comm_model_reproduces_the_papers_worked_example():
+    # Sec. 3.3.1: 100B parameters in FP32, 3 clusters, 1 Gbps, H = 500 steps of 1 s.
+    from oracle import planner
+    g = read_golden("compression_accounting.txt")
+    payload = 100e9 * 4
+    between_gb = 2 * (3 - 1) * payload / 3 / 1e9
+    assert abs(between_gb - g["allreduce_gb"][0]) < 0.05
+    hours = planner.comm_seconds(payload, 3, 1e9) / 3600
+    assert abs(hours - g["allreduce_hours"][0]) < 0.01
+    local = g["local_steps"][0] * g["step_seconds"][0] / 3600
+    assert abs(local - g["local_hours"][0]) < 0.01
+    assert abs((hours - local) - g["idle_hours"][0]) < 0.01
+    assert planner.comm_seconds(payload, 1, 1e9) == 0.0          # one cluster: nothing crosses
+    # the paper's own remedy: at 1000x compression the same exchange hides behind 125 steps
+    assert planner.comm_seconds(payload / 1000 * 4, 3, 1e9) < 125 * 1.0 * 3600
+
+
+def test_overlap_plan_is_the_largest_rank_that_hides():
+    from oracle import planner
+    shapes = [(8192, 8192), (8192, 1024), (8192, 28672), (28672, 8192)]
+    args = dict(qbits=4, group=128, extra_bytes=0, rmin=4, rmax=256, clusters=3,
+                bits_per_second=1e9)
+    r, H, t = planner.plan_overlap(shapes, step_seconds=0.05, H=1, **args)
+    assert H == 1 and 4 <= r < 256 and t <= 0.05
+    # one rank more would not fit
+    over = planner.comm_seconds(planner.stage_payload_bytes(shapes, r + 1, 4, 128), 3, 1e9)
+    assert over > 0.05
+    # payload is monotone in r, so a longer budget never lowers the rank
+    r2, _, _ = planner.plan_overlap(shapes, step_seconds=0.05, H=2, **args)
+    assert r2 > r
+    # nothing fits: rmin and the smallest H that hides it
+    r3, H3, t3 = planner.plan_overlap(shapes, step_seconds=1e-3, H=1, **args)
+    assert r3 == 4 and (H3 - 1) * 1e-3 < t3 <= H3 * 1e-3
+    # factor payload accounting against the transmitted-factors reading (r = 2048 is about 2x)
+    full = 8192 * 8192 * 2                       # FP16 bytes of one 8192 x 8192 matrix
+    fac = planner.factor_payload_bytes(8192, 8192, 2048, 8, 128)
+    assert 0.5 < fac / full * 2 < 0.52           # int8 codes: half the elements, one byte each
