@@ -135,6 +135,58 @@ int dlcx_ef_delta_apply_compress(const dlcx_desc *desc, int32_t r_prev, const fl
                                  uint8_t *const *codes_out_host, float *const *scales_out_host,
                                  void *workspace, void *stream);
 
+/* Outer step t of Alg. 2 for one tensor whose compressor is the quantiser alone: Alg. 1 with
+ * the LOWRANK step left out, C(delta) = QUANTIZE(delta | q), the Int4-only setting the paper
+ * reports for its smaller model (Sec. 4.1) and the only form that applies to tensors that are
+ * not matrices.  The tensor is `numel` consecutive elements (a multiple of `group`); a group is
+ * `group` consecutive elements.  In the order of Alg. 2, in one sweep:
+ *   Delta^{t-1} = mean_k dequant(prev payload_k), workers in index order; with requant != 0
+ *                 re-encoded to q bits first (what a q-bit reduction would hand on);
+ *   e_k <- delta_k - Delta^{t-1} ;  delta_k <- (theta_g - theta_l,k) + e_k   (in place over
+ *                 ef_inout_host[k], theta_g still the value of step t-1);
+ *   payload_k <- QUANTIZE(delta_k) into codes_out_host[k] / scales_out_host[k];
+ *   theta_g <- OuterOpt(theta_g, Delta^{t-1}), v likewise.
+ * prev_codes_host == NULL is outer step 1: no feedback, no update, v is not touched.  The new
+ * payload of a worker may be written over its previous one (codes_out_host[k] ==
+ * prev_codes_host[k] and the same for the scales).  All pointer arrays are host arrays of K
+ * device pointers; payload sizes are numel/2 (q = 4) or numel (q = 8) bytes of codes and
+ * numel/group fp32 scales.  The averaged pseudo-gradient is never written to memory.  The mean,
+ * the sum (theta_g - theta_l) + e and the OuterOpt step (lr, mu as doubles) are evaluated in
+ * fp64 and rounded to fp32 once each; the results do not depend on the launch shape. */
+int dlcx_quant_round(int64_t numel, int qbits, int group, int K,
+                     const void *const *theta_l_host, int theta_l_dtype,
+                     float *const *ef_inout_host, float *theta_g, float *v, double lr, double mu,
+                     const uint8_t *const *prev_codes_host, const float *const *prev_scales_host,
+                     int requant, uint8_t *const *codes_out_host, float *const *scales_out_host,
+                     void *stream);
+
+/* Error buffers of Alg. 2 against a materialised average: e_k <- delta_k - Delta for K workers,
+ * in place, `numel` elements each. */
+int dlcx_ef_update(int K, float *const *ef_inout_host, const float *delta_hat, int64_t numel,
+                   void *stream);
+
+/* x <- dequant(QUANTIZE(x | q)) in place on `count` floats in consecutive groups: an averaged
+ * factor (or tensor) re-encoded to q bits, as a reduction that carries q-bit values between its
+ * hops would deliver it, instead of the fp32 mean that dlcx_average leaves. */
+int dlcx_requantize(float *x_inout, int64_t count, int qbits, int group, void *stream);
+
+/* Communication model of Sec. 3.3.1 (host only).  A ring all-reduce between `clusters` clusters
+ * moves 2 (clusters - 1) / clusters of the payload over the link between two of them;
+ * returns the seconds that takes at `bits_per_second`.  Negative on bad arguments. */
+double dlcx_comm_seconds(double payload_bytes, int clusters, double bits_per_second);
+
+/* Choice of (rank, local steps) that just hides the exchange of one outer step behind local
+ * training (the one-step-delay overlap of Sec. 3.2 needs comm <= H * step time).  The payload
+ * of a worker at rank r is the sum over the n_matrices descriptors of both quantised factors
+ * (r clipped to each matrix's smaller side) plus extra_bytes (tensors sent without low-rank).
+ * *r_out is the largest rank in [rmin, rmax] whose exchange fits H * step_seconds and *H_out = H;
+ * if not even rmin fits, *r_out = rmin and *H_out is the smallest H that hides it.
+ * *comm_seconds_out is the exchange time at the chosen rank.  Host only. */
+int dlcx_plan_overlap(const dlcx_desc *descs_host, int n_matrices, double extra_bytes,
+                      int32_t rmin, int32_t rmax, int clusters, double bits_per_second,
+                      double step_seconds, int32_t H, int32_t *r_out, int32_t *H_out,
+                      double *comm_seconds_out);
+
 /* OuterOpt of Alg. 2 / Appendix A.3: SGD with Nesterov momentum on the averaged
  * pseudo-gradient,  v <- mu v + g ;  theta_g <- theta_g - lr (g + mu v).  In place. */
 int dlcx_outer_nesterov(float *theta_g, float *v, const float *delta_hat, int64_t numel,

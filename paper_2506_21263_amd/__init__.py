@@ -53,6 +53,13 @@ SYMBOLS = {
     "dlcx_ef_delta_apply_compress": (_int, [_dp, _i32, _vp, _vp, _int, _vp, _int, _vp, _vp, _vp,
                                             C.c_float, C.c_float, _vp, _vp, _vp, _vp, _vp]),
     "dlcx_outer_nesterov": (_int, [_vp, _vp, _vp, _i64, C.c_float, C.c_float, _vp]),
+    "dlcx_quant_round": (_int, [_i64, _int, _int, _int, _vp, _int, _vp, _vp, _vp, C.c_double,
+                                C.c_double, _vp, _vp, _int, _vp, _vp, _vp]),
+    "dlcx_ef_update": (_int, [_int, _vp, _vp, _i64, _vp]),
+    "dlcx_requantize": (_int, [_vp, _i64, _int, _int, _vp]),
+    "dlcx_comm_seconds": (C.c_double, [C.c_double, _int, C.c_double]),
+    "dlcx_plan_overlap": (_int, [_dp, _int, C.c_double, _i32, _i32, _int, C.c_double, C.c_double,
+                                 _i32, _vp, _vp, _vp]),
     "dlcx_select_rank": (_int, [_dp, _vp, _int, C.c_double, _vp, _i32, _i32, _i32, _i32, _i32,
                                 _i32, _vp, _vp, _vp, _vp, _vp]),
     "dlcx_select_rank_from": (_int, [_vp, _int, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp,
@@ -201,6 +208,48 @@ def dlcx_outer_nesterov(theta_g, v, delta_hat, lr, mu, numel=None, stream=None):
     n = theta_g.numel() if numel is None else numel
     _check(lib().dlcx_outer_nesterov(_ptr(theta_g), _ptr(v), _ptr(delta_hat), n, lr, mu,
                                      _stream(stream)), "dlcx_outer_nesterov")
+
+
+def dlcx_quant_round(numel, qbits, group, theta_l, ef_inout, theta_g, v, lr, mu, prev_codes,
+                     prev_scales, codes_out, scales_out, requant=False, stream=None):
+    """prev_codes / prev_scales None: outer step 1."""
+    dt = BF16 if theta_l[0].dtype == torch.bfloat16 else F32
+    tp, k1 = _ptr_array(list(theta_l))
+    ep, k2 = _ptr_array(list(ef_inout))
+    pc, k3 = _ptr_array(list(prev_codes)) if prev_codes is not None else (None, None)
+    ps, k4 = _ptr_array(list(prev_scales)) if prev_scales is not None else (None, None)
+    cp, k5 = _ptr_array(list(codes_out))
+    sp, k6 = _ptr_array(list(scales_out))
+    _check(lib().dlcx_quant_round(numel, qbits, group, len(ef_inout), tp, dt, ep, _ptr(theta_g),
+                                  _ptr(v), lr, mu, pc, ps, 1 if requant else 0, cp, sp,
+                                  _stream(stream)), "dlcx_quant_round")
+
+
+def dlcx_ef_update(ef_inout, delta_hat, numel=None, stream=None):
+    n = delta_hat.numel() if numel is None else numel
+    ep, keep = _ptr_array(list(ef_inout))
+    _check(lib().dlcx_ef_update(len(ef_inout), ep, _ptr(delta_hat), n, _stream(stream)),
+           "dlcx_ef_update")
+
+
+def dlcx_requantize(x_inout, count, qbits, group, stream=None):
+    _check(lib().dlcx_requantize(_ptr(x_inout), count, qbits, group, _stream(stream)),
+           "dlcx_requantize")
+
+
+def dlcx_comm_seconds(payload_bytes, clusters, bits_per_second):
+    return lib().dlcx_comm_seconds(payload_bytes, clusters, bits_per_second)
+
+
+def dlcx_plan_overlap(descs, extra_bytes, rmin, rmax, clusters, bits_per_second, step_seconds, H):
+    """Returns (rank, H, seconds of the exchange at that rank).  Host only."""
+    n = len(descs)
+    arr = (Desc * max(n, 1))(*descs)
+    r, h, t = _i32(0), _i32(0), C.c_double(0.0)
+    _check(lib().dlcx_plan_overlap(arr, n, extra_bytes, rmin, rmax, clusters, bits_per_second,
+                                   step_seconds, H, C.addressof(r), C.addressof(h),
+                                   C.addressof(t)), "dlcx_plan_overlap")
+    return r.value, h.value, t.value
 
 
 def dlcx_select_rank_workspace_bytes(descs):

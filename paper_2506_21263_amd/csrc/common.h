@@ -24,7 +24,7 @@ inline int check_launch(const char *where) { return note_hip(hipGetLastError(), 
 enum KernelId {
     KID_DELTA_EF = 0, KID_NESTEROV, KID_QUANTIZE, KID_DEQUANT_AVG, KID_PACK, KID_PROJECT_P,
     KID_PROJECT_Q, KID_SUM_SLABS, KID_RECONSTRUCT, KID_GRAM, KID_CHOL, KID_APPLY_W, KID_JACOBI,
-    KID_ROUND, KID_COUNT
+    KID_ROUND, KID_QUANT_ROUND, KID_REQUANT, KID_EF_UPDATE, KID_COUNT
 };
 struct Timed {
     Timed(int kid, hipStream_t st);
@@ -53,6 +53,17 @@ int launch_quantize(int K, const PtrPack<const float *> &x, int64_t count, int q
 int launch_dequant_average(int K, const PtrPack<const uint8_t *> &codes,
                            const PtrPack<const float *> &scales, int64_t count, int qbits,
                            int group, float *mean_out, hipStream_t st);
+
+// ---- quantise-only outer step (k_qround.hip) ------------------------------------------
+int launch_quant_round(int64_t numel, int qbits, int group, int K, const PtrPack<const void *> &tl,
+                       int tl_dtype, const PtrPack<float *> &ef, float *theta, float *vel, double lr,
+                       double mu, bool has_prev, const PtrPack<const uint8_t *> &pcodes,
+                       const PtrPack<const float *> &pscales, bool requant,
+                       const PtrPack<uint8_t *> &codes, const PtrPack<float *> &scales,
+                       hipStream_t st);
+int launch_requantize(float *x, int64_t count, int qbits, int group, hipStream_t st);
+int launch_ef_update(int K, const PtrPack<float *> &ef, const float *d, int64_t numel,
+                     hipStream_t st);
 
 // ---- rank-r products ------------------------------------------------------------------
 // P_k = delta_k * Q_in   (delta m x n, q_in r x n, out r x m)

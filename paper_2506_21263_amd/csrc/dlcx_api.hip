@@ -131,7 +131,7 @@ const char *dlcx_last_hip_error(void) { return g_last_error.c_str(); }
 static const char *const kKernelNames[KID_COUNT] = {
     "delta_ef", "outer_nesterov", "quantize", "dequant_average", "pack_fragments", "project_p",
     "project_q", "sum_slabs", "reconstruct", "gram_partials", "chol_inverse", "apply_w",
-    "jacobi_rank", "round_fused"};
+    "jacobi_rank", "round_fused", "quant_round", "requantize", "ef_update"};
 
 int dlcx_profile_enable(int on) {
     for (auto &r : g_prof) {
@@ -227,6 +227,134 @@ int dlcx_outer_nesterov(float *theta_g, float *v, const float *delta_hat, int64_
     if (!aligned16(theta_g) || !aligned16(v) || !aligned16(delta_hat)) return DLCX_EINVAL;
     if (!(lr == lr) || !(mu == mu)) return DLCX_EINVAL;
     return launch_nesterov(theta_g, v, delta_hat, numel, lr, mu, as_stream(stream));
+}
+
+int dlcx_quant_round(int64_t numel, int qbits, int group, int K,
+                     const void *const *theta_l_host, int theta_l_dtype,
+                     float *const *ef_inout_host, float *theta_g, float *v, double lr, double mu,
+                     const uint8_t *const *prev_codes_host, const float *const *prev_scales_host,
+                     int requant, uint8_t *const *codes_out_host, float *const *scales_out_host,
+                     void *stream) {
+    if (numel < 0 || (qbits != 4 && qbits != 8) || !group_ok(group) || numel % group)
+        return DLCX_EINVAL;
+    if (K < 1 || K > DLCX_MAX_WORKERS) return DLCX_EINVAL;
+    if (theta_l_dtype != DLCX_F32 && theta_l_dtype != DLCX_BF16) return DLCX_EINVAL;
+    if ((prev_codes_host == nullptr) != (prev_scales_host == nullptr)) return DLCX_EINVAL;
+    if (numel == 0) return DLCX_OK;
+    if (!theta_l_host || !ef_inout_host || !theta_g || !codes_out_host || !scales_out_host)
+        return DLCX_EINVAL;
+    const bool has_prev = prev_codes_host != nullptr;
+    if (has_prev && !v) return DLCX_EINVAL;
+    if (!aligned16(theta_g) || (v && !aligned16(v))) return DLCX_EINVAL;
+    if (!(lr == lr) || !(mu == mu)) return DLCX_EINVAL;
+    PtrPack<const void *> tl;
+    PtrPack<float *> ef;
+    PtrPack<const uint8_t *> pc;
+    PtrPack<const float *> ps;
+    PtrPack<uint8_t *> cs;
+    PtrPack<float *> ss;
+    for (int k = 0; k < K; ++k) {
+        if (!theta_l_host[k] || !ef_inout_host[k] || !codes_out_host[k] || !scales_out_host[k])
+            return DLCX_EINVAL;
+        if (!aligned16(theta_l_host[k]) || !aligned16(ef_inout_host[k]) ||
+            !aligned16(codes_out_host[k]) || !aligned16(scales_out_host[k]))
+            return DLCX_EINVAL;
+        tl.p[k] = theta_l_host[k];
+        ef.p[k] = ef_inout_host[k];
+        cs.p[k] = codes_out_host[k];
+        ss.p[k] = scales_out_host[k];
+        pc.p[k] = nullptr;
+        ps.p[k] = nullptr;
+        if (has_prev) {
+            if (!prev_codes_host[k] || !prev_scales_host[k]) return DLCX_EINVAL;
+            if (!aligned16(prev_codes_host[k]) || !aligned16(prev_scales_host[k]))
+                return DLCX_EINVAL;
+            pc.p[k] = prev_codes_host[k];
+            ps.p[k] = prev_scales_host[k];
+        }
+    }
+    return launch_quant_round(numel, qbits, group, K, tl, theta_l_dtype, ef, theta_g, v, lr, mu,
+                              has_prev, pc, ps, requant != 0, cs, ss, as_stream(stream));
+}
+
+int dlcx_ef_update(int K, float *const *ef_inout_host, const float *delta_hat, int64_t numel,
+                   void *stream) {
+    if (K < 0 || K > DLCX_MAX_WORKERS || numel < 0) return DLCX_EINVAL;
+    if (K == 0 || numel == 0) return DLCX_OK;
+    if (!ef_inout_host || !delta_hat || !aligned16(delta_hat)) return DLCX_EINVAL;
+    PtrPack<float *> ef;
+    for (int k = 0; k < K; ++k) {
+        if (!ef_inout_host[k] || !aligned16(ef_inout_host[k])) return DLCX_EINVAL;
+        ef.p[k] = ef_inout_host[k];
+    }
+    return launch_ef_update(K, ef, delta_hat, numel, as_stream(stream));
+}
+
+int dlcx_requantize(float *x_inout, int64_t count, int qbits, int group, void *stream) {
+    if (count < 0 || (qbits != 4 && qbits != 8) || !group_ok(group) || count % group)
+        return DLCX_EINVAL;
+    if (count == 0) return DLCX_OK;
+    if (!x_inout || !aligned16(x_inout)) return DLCX_EINVAL;
+    return launch_requantize(x_inout, count, qbits, group, as_stream(stream));
+}
+
+double dlcx_comm_seconds(double payload_bytes, int clusters, double bits_per_second) {
+    if (!(payload_bytes >= 0.0) || clusters < 1 || !(bits_per_second > 0.0)) return -1.0;
+    const double between = 2.0 * (double)(clusters - 1) / (double)clusters * payload_bytes;
+    return between * 8.0 / bits_per_second;
+}
+
+static double stage_payload_bytes(const dlcx_desc *descs, int n, int32_t r, double extra) {
+    double total = extra;
+    for (int a = 0; a < n; ++a) {
+        dlcx_desc d = descs[a];
+        const int64_t side = d.m < d.n ? d.m : d.n;
+        d.r = r < side ? r : (int32_t)side;
+        total += (double)dlcx_payload_bytes(&d, DLCX_PHASE_P, nullptr, nullptr);
+        total += (double)dlcx_payload_bytes(&d, DLCX_PHASE_Q, nullptr, nullptr);
+    }
+    return total;
+}
+
+int dlcx_plan_overlap(const dlcx_desc *descs_host, int n_matrices, double extra_bytes,
+                      int32_t rmin, int32_t rmax, int clusters, double bits_per_second,
+                      double step_seconds, int32_t H, int32_t *r_out, int32_t *H_out,
+                      double *comm_seconds_out) {
+    if (n_matrices < 0 || (n_matrices > 0 && !descs_host) || !(extra_bytes >= 0.0)) return DLCX_EINVAL;
+    if (rmin < 1 || rmax < rmin || rmax > DLCX_MAX_RANK || clusters < 1 || H < 1) return DLCX_EINVAL;
+    if (!(bits_per_second > 0.0) || !(step_seconds > 0.0)) return DLCX_EINVAL;
+    if (!r_out || !H_out || !comm_seconds_out) return DLCX_EINVAL;
+    for (int a = 0; a < n_matrices; ++a) {
+        dlcx_desc d = descs_host[a];
+        d.r = 1;  // the rank field of the inputs is not used
+        if (check_desc(&d) != DLCX_OK) return DLCX_EINVAL;
+    }
+    const double budget = (double)H * step_seconds;
+    int32_t best = 0;
+    for (int32_t r = rmin; r <= rmax; ++r) {  // the payload grows with r: keep the last that fits
+        const double t = dlcx_comm_seconds(stage_payload_bytes(descs_host, n_matrices, r, extra_bytes),
+                                           clusters, bits_per_second);
+        if (t <= budget) best = r;
+        else break;
+    }
+    if (best >= rmin) {
+        *r_out = best;
+        *H_out = H;
+        *comm_seconds_out = dlcx_comm_seconds(
+            stage_payload_bytes(descs_host, n_matrices, best, extra_bytes), clusters, bits_per_second);
+        return DLCX_OK;
+    }
+    const double t = dlcx_comm_seconds(stage_payload_bytes(descs_host, n_matrices, rmin, extra_bytes),
+                                       clusters, bits_per_second);
+    double h = t / step_seconds;
+    int64_t hi = (int64_t)h;
+    if ((double)hi < h) ++hi;
+    if (hi < 1) hi = 1;
+    if (hi > INT32_MAX) return DLCX_EINVAL;
+    *r_out = rmin;
+    *H_out = (int32_t)hi;
+    *comm_seconds_out = t;
+    return DLCX_OK;
 }
 
 int dlcx_project(const dlcx_desc *desc, int phase, int K, const float *const *deltas_host,

@@ -53,16 +53,18 @@ __global__ __launch_bounds__(kQThreads) void quantize_kernel(PtrPack<const float
     if ((threadIdx.x & (kLanes - 1)) == 0) scales.p[k][v / kLanes] = scale;
 }
 
+// Mean of K decoded payloads: fp64 sum of the (exact) products code * scale in worker order, one
+// rounding to fp32 at the end.
 template <int kQbits>
 __global__ __launch_bounds__(kQThreads) void dequant_average_kernel(
     int K, PtrPack<const uint8_t *> codes, PtrPack<const float *> scales, int64_t nvec,
-    int lanes_per_group, float inv_k, float *__restrict__ out) {
+    int lanes_per_group, double inv_k, int exact_inv, float *__restrict__ out) {
     const int64_t v = (int64_t)blockIdx.x * kQThreads + threadIdx.x;
     if (v >= nvec) return;
     const int64_t g = v / lanes_per_group;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     for (int k = 0; k < K; ++k) {  // workers in index order
-        const float s = scales.p[k][g];
+        const double s = (double)scales.p[k][g];
         int c0, c1, c2, c3;
         if (kQbits == 4) {
             const uint32_t w = reinterpret_cast<const uint16_t *>(codes.p[k])[v];
@@ -77,16 +79,18 @@ __global__ __launch_bounds__(kQThreads) void dequant_average_kernel(
             c2 = ((int)(w << 8)) >> 24;
             c3 = ((int)w) >> 24;
         }
-        acc.x = fmaf((float)c0, s, acc.x);
-        acc.y = fmaf((float)c1, s, acc.y);
-        acc.z = fmaf((float)c2, s, acc.z);
-        acc.w = fmaf((float)c3, s, acc.w);
+        a0 = fma((double)c0, s, a0);
+        a1 = fma((double)c1, s, a1);
+        a2 = fma((double)c2, s, a2);
+        a3 = fma((double)c3, s, a3);
     }
-    acc.x *= inv_k;
-    acc.y *= inv_k;
-    acc.z *= inv_k;
-    acc.w *= inv_k;
-    reinterpret_cast<float4 *>(out)[v] = acc;
+    if (exact_inv) {  // K a power of two: the reciprocal and the product are exact
+        a0 *= inv_k; a1 *= inv_k; a2 *= inv_k; a3 *= inv_k;
+    } else {
+        const double kd = (double)K;
+        a0 /= kd; a1 /= kd; a2 /= kd; a3 /= kd;
+    }
+    reinterpret_cast<float4 *>(out)[v] = make_float4((float)a0, (float)a1, (float)a2, (float)a3);
 }
 
 template <int kQbits>
@@ -122,14 +126,15 @@ int launch_dequant_average(int K, const PtrPack<const uint8_t *> &codes,
     if (count == 0) return DLCX_OK;
     const int64_t nvec = count >> 2;
     const dim3 grid((unsigned)ceil_div(nvec, kQThreads));
-    const float inv_k = 1.0f / (float)K;
+    const double inv_k = 1.0 / (double)K;
+    const int exact_inv = (K & (K - 1)) == 0;
     Timed timed(KID_DEQUANT_AVG, st);
     if (qbits == 4)
         hipLaunchKernelGGL(dequant_average_kernel<4>, grid, dim3(kQThreads), 0, st, K, codes,
-                           scales, nvec, group / 4, inv_k, mean_out);
+                           scales, nvec, group / 4, inv_k, exact_inv, mean_out);
     else
         hipLaunchKernelGGL(dequant_average_kernel<8>, grid, dim3(kQThreads), 0, st, K, codes,
-                           scales, nvec, group / 4, inv_k, mean_out);
+                           scales, nvec, group / 4, inv_k, exact_inv, mean_out);
     return check_launch("dequant_average");
 }
 

@@ -40,11 +40,11 @@ __global__ __launch_bounds__(kThreads) void delta_ef_kernel(const float *__restr
     for (int u = 0; u < kUnroll; ++u) {
         const int64_t v = base + (int64_t)u * kThreads;
         if (v < nvec) {
-            float4 d;
-            d.x = (g[u].x - l[u].x) + e[u].x;
-            d.y = (g[u].y - l[u].y) + e[u].y;
-            d.z = (g[u].z - l[u].z) + e[u].z;
-            d.w = (g[u].w - l[u].w) + e[u].w;
+            float4 d;  // summed in fp64, rounded to fp32 once
+            d.x = (float)(((double)g[u].x - (double)l[u].x) + (double)e[u].x);
+            d.y = (float)(((double)g[u].y - (double)l[u].y) + (double)e[u].y);
+            d.z = (float)(((double)g[u].z - (double)l[u].z) + (double)e[u].z);
+            d.w = (float)(((double)g[u].w - (double)l[u].w) + (double)e[u].w);
             reinterpret_cast<float4 *>(ef)[v] = d;
         }
     }
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kThreads) void delta_ef_kernel(const float *__restr
                 tl = bf16_bits_to_f32(reinterpret_cast<const uint16_t *>(theta_l)[x]);
             else
                 tl = reinterpret_cast<const float *>(theta_l)[x];
-            ef[x] = (theta_g[x] - tl) + ef[x];
+            ef[x] = (float)(((double)theta_g[x] - (double)tl) + (double)ef[x]);
         }
     }
 }

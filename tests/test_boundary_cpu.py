@@ -88,3 +88,52 @@ def test_select_rank_window_rule_on_the_host(golden):
         assert (rp, r, H) == (int(g["rprime"][t - 1]), int(g["r_t"][t - 1]), int(g["H_t"][t - 1]))
     with pytest.raises(dlcx.DlcxError):
         dlcx.dlcx_select_rank([], [], 0.99, hist, 0, c, r1, 4, r1, H1, rprime=4)
+
+
+def test_quantise_only_entry_points_reject_bad_arguments():
+    L = dlcx.lib()
+    fake = 0x1000
+    arr = (C.c_void_p * 2)(fake, fake)
+    ap = C.cast(arr, C.c_void_p)
+    ok_args = [256, 4, 64, 2, ap, 0, ap, fake, fake, 0.7, 0.9, None, None, 0, ap, ap, None]
+
+    def call(**kw):
+        a = list(ok_args)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return L.dlcx_quant_round(*a)
+
+    assert call(_0=100) == dlcx.EINVAL          # numel % group
+    assert call(_1=5) == dlcx.EINVAL            # qbits
+    assert call(_2=48) == dlcx.EINVAL           # group
+    assert call(_3=0) == dlcx.EINVAL            # K
+    assert call(_5=3) == dlcx.EINVAL            # dtype
+    assert call(_11=ap) == dlcx.EINVAL          # previous codes without previous scales
+    assert call(_7=None) == dlcx.EINVAL         # theta_g
+    assert call(_11=ap, _12=ap, _8=None) == dlcx.EINVAL   # a previous payload needs v
+    assert call(_0=0) == dlcx.OK                # empty tensor: nothing launched
+    assert L.dlcx_requantize(fake, 100, 4, 64, None) == dlcx.EINVAL
+    assert L.dlcx_requantize(fake + 4, 128, 4, 64, None) == dlcx.EINVAL
+    assert L.dlcx_requantize(None, 0, 4, 64, None) == dlcx.OK
+    assert L.dlcx_ef_update(2, ap, None, 64, None) == dlcx.EINVAL
+    assert L.dlcx_ef_update(17, ap, fake, 64, None) == dlcx.EINVAL
+    assert L.dlcx_ef_update(0, None, None, 64, None) == dlcx.OK
+
+
+def test_comm_model_and_overlap_plan_on_the_host(golden):
+    # the library's host-side planner against the oracle's exhaustive one (Sec. 3.3.1, 3.2)
+    from oracle import planner
+    g = golden("compression_accounting.txt")
+    hours = dlcx.dlcx_comm_seconds(100e9 * 4, 3, 1e9) / 3600
+    assert abs(hours - g["allreduce_hours"][0]) < 0.01
+    assert dlcx.dlcx_comm_seconds(1e9, 0, 1e9) < 0          # bad arguments
+    shapes = [(8192, 8192), (8192, 1024), (8192, 28672), (28672, 8192), (512, 256)]
+    for qbits, group in ((4, 128), (8, 64)):
+        descs = [dlcx.desc(m, n, 1, qbits, group) for m, n in shapes]
+        for step, H, extra in ((0.05, 1, 0.0), (0.05, 3, 1e6), (1e-3, 1, 0.0), (10.0, 1, 0.0)):
+            want = planner.plan_overlap(shapes, qbits, group, extra, 4, 256, 3, 1e9, step, H)
+            got = dlcx.dlcx_plan_overlap(descs, extra, 4, 256, 3, 1e9, step, H)
+            assert got[:2] == want[:2]
+            assert abs(got[2] - want[2]) <= 1e-12 * max(want[2], 1.0)
+    with pytest.raises(dlcx.DlcxError):
+        dlcx.dlcx_plan_overlap([dlcx.desc(512, 512, 1, 4, 64)], 0.0, 8, 4, 3, 1e9, 1.0, 1)

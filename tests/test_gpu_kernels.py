@@ -41,9 +41,8 @@ def test_delta_ef(numel, kind):
     dlcx.dlcx_delta_ef(to_dev(tg), to_dev(tl), d_e, numel=numel)
     got = to_np(d_e)
     assert np.array_equal(got[numel:], e[numel:]), "wrote past numel"
-    if numel:
-        assert rel_l2(got[:numel], want) <= 1e-6
-        assert np.max(np.abs(got[:numel] - want)) <= 2.0 ** -22 * np.max(np.abs(want))
+    if numel:  # (theta - theta_l) + e summed in fp64 and rounded once on both sides
+        assert np.array_equal(got[:numel].view(np.uint32), want.view(np.uint32))
 
 
 @pytest.mark.parametrize("numel", [0, 4, 5, 4096, (1 << 20) + 3])
@@ -95,7 +94,8 @@ def test_quantize_codes_and_scales_bit_exact(qbits, group):
     assert np.array_equal(to_np(codes), codes_w)
 
 
-@pytest.mark.parametrize("qbits,group,K", [(4, 64, 2), (4, 128, 4), (8, 64, 8), (4, 16, 1), (8, 256, 16)])
+@pytest.mark.parametrize("qbits,group,K", [(4, 64, 2), (4, 128, 4), (8, 64, 8), (4, 16, 1), (8, 256, 16),
+                                           (4, 32, 3), (8, 128, 7)])
 def test_dequant_average(qbits, group, K):
     g = rng(K * 7 + qbits)
     count = group * 517
@@ -105,9 +105,8 @@ def test_dequant_average(qbits, group, K):
     out = torch.zeros(count, device=DEV)
     dlcx.dlcx_dequant_average([to_dev(p[0]) for p in payloads], [to_dev(p[1]) for p in payloads],
                               count, qbits, group, out)
-    assert rel_l2(to_np(out), want) <= 1e-6
-    if K == 1:
-        assert np.array_equal(to_np(out), want)
+    # fp64 sum of exact products in worker order, one rounding: the same bits on both sides
+    assert np.array_equal(to_np(out).view(np.uint32), want.view(np.uint32))
 
 
 # ------------------------------------------------------------------ rank-r products
