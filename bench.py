@@ -29,7 +29,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False):
+def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, workers=0):
     """plain=True draws i.i.d. Gaussian replicas instead of the low-rank-plus-noise recipe (no
     library QR/GEMM kernels in the process: used for hardware-counter runs, where only the
     traffic of this library's kernels is of interest)."""
@@ -39,7 +39,7 @@ def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False):
     from paper_2506_21263_amd.stage import MatrixState, Stage
 
     cfg = synth.CONFIGS[cfg_id]
-    K, r = cfg["K"], cfg["r"]
+    K, r = workers or cfg["K"], cfg["r"]
     mats, locals_ = [], []
     gen = torch.Generator(device="cpu")
     gen.manual_seed(1234 + cfg_id)
@@ -118,6 +118,112 @@ def cpu_baseline(stage, locals_, cfg_id):
                       "%.1f s per step" % (M.m, M.n, M.K, M.r, cfg["qbits"], cfg["group"], dt)}
 
 
+def quant_only(args):
+    """The outer step with the quantiser as the whole compressor (the Int4-only setting of the
+    paper's smaller model, Sec. 4.1): every tensor of the stage, matrices and vectors alike, is
+    one flat array and one launch of dlcx_quant_round per outer step."""
+    import numpy as np
+    import torch
+
+    import paper_2506_21263_amd as dlcx
+    import synth
+    from oracle import pipeline
+
+    dlcx.lib()
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    K = args.workers or cfg["K"]
+    qbits, group = cfg["qbits"], cfg["group"]
+    layers = args.layers or cfg["layers"]
+    dt_l = torch.bfloat16 if cfg["theta_l"] == "bf16" else torch.float32
+    hidden = min(min(s) for s in cfg["layer_shapes"])
+    tensors = []
+    for layer in range(layers):
+        sizes = [m * n for (m, n) in cfg["layer_shapes"]]
+        sizes += [4 * hidden]           # two norm weights and two biases per layer, one bucket
+        for numel in sizes:
+            th = 0.02 * torch.randn(numel, device=device)
+            tl = [(th - 1e-3 * torch.randn(numel, device=device)).to(dt_l) for _ in range(K)]
+            cb = numel // 2 if qbits == 4 else numel
+            tensors.append(dict(
+                numel=numel, theta=th, v=torch.zeros_like(th), tl=tl,
+                ef=[torch.zeros(numel, device=device) for _ in range(K)],
+                codes=[torch.empty(cb, device=device, dtype=torch.uint8) for _ in range(K)],
+                scales=[torch.empty(numel // group, device=device) for _ in range(K)]))
+    params = sum(t["numel"] for t in tensors)
+    log("quantise-only stage: %d tensors, %.3f G params, K=%d, %.1f GB allocated" %
+        (len(tensors), params / 1e9, K, torch.cuda.memory_allocated() / 1e9))
+    state = {"t": 0}
+
+    def one_step():
+        state["t"] += 1
+        first = state["t"] == 1
+        for T in tensors:
+            dlcx.dlcx_quant_round(T["numel"], qbits, group, T["tl"], T["ef"], T["theta"], T["v"],
+                                  synth.LR, synth.MU, None if first else T["codes"],
+                                  None if first else T["scales"], T["codes"], T["scales"],
+                                  requant=args.requant)
+
+    for _ in range(max(args.warmup, 1)):   # the first outer step has no previous payload
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    dlcx.dlcx_profile_enable(True)
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    prof = dlcx.dlcx_profile_read()
+    dlcx.dlcx_profile_enable(False)
+    ms, cnt = prof["quant_round"]
+    tl_bytes = 2 if cfg["theta_l"] == "bf16" else 4
+    code_b = (0.5 if qbits == 4 else 1.0) + 4.0 / group
+    # per worker: theta_l and delta in, delta and the new payload out, the previous payload in;
+    # once: theta and v in and out
+    bpp = K * (tl_bytes + 8 + 2 * code_b) + 16
+    achieved = bpp * params * args.steps / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "outer-step params/sec per stage (quantise-only compressor + avg + Nesterov)",
+        "value": params / (dt / args.steps), "unit": "params/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": max(args.warmup, 1), "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (fp64 sums, one rounding)", "data": "synthetic",
+        "config": {"workload": cfg["name"] + "-quant-only", "layers": layers,
+                   "tensors": len(tensors), "params": params, "K": K, "qbits": qbits,
+                   "group": group, "theta_l": cfg["theta_l"], "requant": bool(args.requant)},
+        "roofline": {"kernel": "quant_round", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_param_per_launch": bpp,
+                     "avg_launch_ms": ms / cnt, "launches_per_step": cnt / args.steps},
+        "kernels": {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps}
+                    for k, v in prof.items()},
+    }
+    if not args.no_cpu_baseline:
+        T = max(tensors, key=lambda t: t["numel"])
+        th = (0.02 * np.random.default_rng(1).standard_normal(T["numel"])).astype(np.float32)
+        tl = []
+        for x in T["tl"]:
+            tl.append(x.view(torch.int16).cpu().numpy().view(np.uint16) if x.element_size() == 2
+                      else x.cpu().numpy())
+        orc = pipeline.TensorOracle(th, K, qbits, group, synth.LR, synth.MU, requant=args.requant)
+        t1 = time.time()
+        nsteps = 0
+        while nsteps < 2 or time.time() - t1 < 10.0:   # about 10 s of single-thread work
+            orc.step(tl)
+            nsteps += 1
+        dtc = (time.time() - t1) / nsteps
+        out["cpu_baseline"] = {"value": T["numel"] / dtc, "unit": "params/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": "%d outer steps of one tensor of %d elements (K=%d, "
+                                         "int%d/%d), %.2f s per step" %
+                                         (nsteps, T["numel"], K, qbits, group, dtc)}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -131,6 +237,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-load", type=int, default=0,
                     help="bf16 8192^3 GEMMs issued on a second stream per outer step (config 4)")
+    ap.add_argument("--workers", type=int, default=0, help="K (0 = the configuration's)")
+    ap.add_argument("--quant-only", action="store_true",
+                    help="quantiser as the whole compressor (no low-rank step), all tensors flat")
+    ap.add_argument("--requant", action="store_true",
+                    help="quantise-only mode: re-encode the average to q bits")
     ap.add_argument("--probe", action="store_true",
                     help="counter run: plain random inputs, one 1 GiB copy, two steps, no timing")
     args = ap.parse_args()
@@ -138,6 +249,9 @@ def main():
         print("bench.py: this build measures ONE MI355X; --gpus %d is not supported "
               "(no collectives, no second GPU in this run)" % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    if args.quant_only:
+        return quant_only(args)
 
     import torch
 
@@ -156,7 +270,7 @@ def main():
         layers = 5
     fused = not args.unfused
     stage, locals_ = build_stage(args.config, args.mma, layers, device, fused, args.streams,
-                                 plain=args.probe)
+                                 plain=args.probe, workers=args.workers)
     if args.probe:
         x = torch.empty(1 << 28, dtype=torch.float32, device=device)
         y = torch.empty_like(x)
@@ -166,7 +280,7 @@ def main():
         torch.cuda.synchronize()
         print("probe done: %d matrices, 2 steps" % len(stage.mats), file=sys.stderr)
         return
-    K = cfg["K"]
+    K = args.workers or cfg["K"]
     params = stage.params()
     selector = RankSelector(stage, c=cfg.get("window", 5), r1=cfg["r"], rmin=cfg.get("rmin", 4),
                             rmax=cfg.get("rmax", cfg["r"]), H1=125)

@@ -23,8 +23,8 @@ import torch
 from . import (PHASE_P, PHASE_Q, desc, dlcx_average, dlcx_batched_workspace_bytes,
                dlcx_compress_batched, dlcx_decompress, dlcx_delta_ef, dlcx_dequant_average,
                dlcx_effective_rank, dlcx_effective_rank_batched, dlcx_ef_delta_apply_compress,
-               dlcx_orthonormalize_batched, dlcx_outer_nesterov, dlcx_payload_bytes,
-               dlcx_select_rank_from, dlcx_workspace_bytes)
+               dlcx_orthonormalize, dlcx_orthonormalize_batched, dlcx_outer_nesterov,
+               dlcx_payload_bytes, dlcx_requantize, dlcx_select_rank_from, dlcx_workspace_bytes)
 
 
 class MatrixState:
@@ -66,12 +66,15 @@ class Stage:
     streams > 1 deals the matrices to that many HIP streams.  measure_rank=True also launches
     the effective-rank kernel of Alg. 3 for every matrix (results in self.rprime_dev).
     batched=True orthonormalises (and measures) all matrices of the stage in one batch between
-    the two compression phases instead of matrix by matrix.
+    the two compression phases instead of matrix by matrix.  requant=True re-encodes every
+    averaged factor to q bits (dlcx_requantize), as a reduction that carries q-bit values would
+    deliver it, before it is used.
     """
 
     def __init__(self, matrices, lr, mu, fused=False, warm_start=False, streams=1,
-                 measure_rank=False, tau=0.99, batched=True):
+                 measure_rank=False, tau=0.99, batched=True, requant=False):
         self.mats = matrices
+        self.requant = requant
         self.lr, self.mu = lr, mu
         self.fused, self.warm_start = fused, warm_start
         self.measure_rank, self.tau = measure_rank, tau
@@ -122,17 +125,24 @@ class Stage:
                                     stream=stream)
             dlcx_compress_batched(d, PHASE_P, M.ef, basis, M.codes_p, M.scales_p, ws,
                                   stream=stream)
-        if orthonormalize:
+        if orthonormalize and not self.requant:
             dlcx_average(d, PHASE_P, M.codes_p, M.scales_p, M.p_hat, ws, stream=stream)
-        else:  # mean only; the stage orthonormalises all matrices in one batch afterwards
-            dlcx_dequant_average(M.codes_p, M.scales_p, M.r * M.m, M.qbits, M.group, M.p_hat,
-                                 stream=stream)
+            return
+        # mean only; orthonormalised below, or by the stage in one batch afterwards
+        dlcx_dequant_average(M.codes_p, M.scales_p, M.r * M.m, M.qbits, M.group, M.p_hat,
+                             stream=stream)
+        if self.requant:
+            dlcx_requantize(M.p_hat, M.r * M.m, M.qbits, M.group, stream=stream)
+        if orthonormalize:
+            dlcx_orthonormalize(M.m, M.r, M.p_hat, ws, stream=stream)
 
     def _q_phase(self, a, lane, stream, rank):
         M = self.mats[a]
         ws, d = self.workspaces[lane], M.desc()
         dlcx_compress_batched(d, PHASE_Q, M.ef, M.p_hat, M.codes_q, M.scales_q, ws, stream=stream)
         dlcx_average(d, PHASE_Q, M.codes_q, M.scales_q, M.q_bar, ws, stream=stream)
+        if self.requant:
+            dlcx_requantize(M.q_bar, M.r * M.n, M.qbits, M.group, stream=stream)
         M.r_prev = M.r
         if rank:
             dlcx_effective_rank(M.n, M.r, M.q_bar, self.tau, self.rprime_dev[a:], ws,

@@ -299,3 +299,37 @@ def test_adaptive_rank_rounds_config3_like():
             orc.set_basis(pipeline.next_basis(orc.q_bar, r_next, fresh))
         r_now = r_next
     assert r_now < r1, "the rank was expected to shrink with the steeper spectra"
+
+
+@pytest.mark.parametrize("batched", [True, False])
+def test_requantised_factor_averages(batched):
+    # Averaged factors re-encoded to q bits before use (what a reduction carrying q-bit values
+    # would deliver).  The GPU's own payloads are decoded, averaged and re-encoded by the oracle:
+    # Q_bar must match bit for bit, P_hat (orthonormalised afterwards) to the fp32 bar.  Two
+    # rounds, so that the re-encoded factors also pass through the fused feedback sweep.
+    shapes = [(256, 384), (512, 256)]
+    K, r, qbits, group = 3, 8, 4, 64
+    mats, tls = [], []
+    for a, (m, n) in enumerate(shapes):
+        inp = synth.MatrixInputs(m, n, K, r, seed=900 + a, sigma=1e-3, alpha=1.0, theta_l="bf16")
+        mats.append(MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), qbits, group, dlcx.MMA_F32))
+        tls.append([to_dev(inp.theta_local(inp.theta_g, 1, i)) for i in range(K)])
+    st = Stage(mats, synth.LR, synth.MU, fused=True, warm_start=True, streams=2, batched=batched,
+               requant=True)
+    plain = Stage([MatrixState(M.theta_g.clone(), K, M.q_in[:r].clone(), qbits, group, dlcx.MMA_F32)
+                   for M in mats], synth.LR, synth.MU, fused=True, warm_start=True, batched=batched)
+    for t in range(2):
+        st.step(tls)
+        torch.cuda.synchronize()
+        for M in mats:
+            cp, sp = [to_np(c) for c in M.codes_p], [to_np(s) for s in M.scales_p]
+            p_bar = ref.dequant_average(cp, sp, r * M.m, qbits, group)
+            p_hat = ref.orthonormalize(pipeline.requantize(p_bar, qbits, group).reshape(r, M.m))
+            assert rel_l2(to_np(M.p_hat)[:r], p_hat) <= 1e-5
+            cq, sq = [to_np(c) for c in M.codes_q], [to_np(s) for s in M.scales_q]
+            q_bar = pipeline.requantize(ref.dequant_average(cq, sq, r * M.n, qbits, group),
+                                        qbits, group).reshape(r, M.n)
+            assert np.array_equal(to_np(M.q_bar)[:r].view(np.uint32), q_bar.view(np.uint32))
+    plain.step(tls)
+    torch.cuda.synchronize()
+    assert not torch.equal(plain.mats[0].q_bar, mats[0].q_bar)   # the option does something
