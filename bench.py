@@ -165,6 +165,15 @@ def quant_only(args):
                                   None if first else T["scales"], T["codes"], T["scales"],
                                   requant=args.requant)
 
+    if args.probe:
+        x = torch.empty(1 << 28, dtype=torch.float32, device=device)
+        y = torch.empty_like(x)
+        y.copy_(x)  # the plain copy of known size (1 GiB in, 1 GiB out) the counters are scaled by
+        for _ in range(3):
+            one_step()
+        torch.cuda.synchronize()
+        print("probe done: %d tensors, 3 steps" % len(tensors), file=sys.stderr)
+        return
     for _ in range(max(args.warmup, 1)):   # the first outer step has no previous payload
         one_step()
     torch.cuda.synchronize()
