@@ -246,6 +246,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-load", type=int, default=0,
                     help="bf16 8192^3 GEMMs issued on a second stream per outer step (config 4)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the steady outer step into a HIP graph and replay it (fixed ranks)")
     ap.add_argument("--workers", type=int, default=0, help="K (0 = the configuration's)")
     ap.add_argument("--quant-only", action="store_true",
                     help="quantiser as the whole compressor (no low-rank step), all tensors flat")
@@ -306,7 +308,14 @@ def main():
     log("stage: %d matrices, %.3f G params, K=%d, %.1f GB allocated" %
         (len(stage.mats), params / 1e9, K, torch.cuda.memory_allocated() / 1e9))
 
+    use_graph = {"on": False}
+
     def one_step(serial=False):
+        if use_graph["on"] and not serial:
+            stage.replay()
+            rp, r_next, _ = selector.next(stage.t + 1)
+            ranks.append((rp, r_next))
+            return
         if load is not None:
             with torch.cuda.stream(load["stream"]):
                 for _ in range(args.gemm_load):
@@ -328,6 +337,14 @@ def main():
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
+    # fixed ranks and no foreign stream: the steady outer step can be recorded once into a HIP
+    # graph (all launches on all streams) and replayed; measured, it changes nothing here, the
+    # host is not what the step waits for
+    if args.graph and not adaptive and load is None and stage.t >= 2:
+        stage.capture(locals_)
+        use_graph["on"] = True
+        one_step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
@@ -379,7 +396,7 @@ def main():
         "config": {"workload": cfg["name"], "layers": layers, "matrices": len(stage.mats),
                    "params": params, "K": K, "rank": cfg["r"], "qbits": cfg["qbits"],
                    "group": cfg["group"], "theta_l": cfg["theta_l"], "mma": args.mma,
-                   "fused": fused, "streams": stage.nstreams},
+                   "fused": fused, "streams": stage.nstreams, "hip_graph": use_graph["on"]},
         "roofline": roofline,
         "stage_hbm": {"algorithmic_bytes_per_param": b_alg,
                       "achieved_GBps": b_alg * params / (dt / args.steps) / 1e9,

@@ -204,6 +204,26 @@ class Stage:
                                         self.rprime_dev, self.batch_ws)
 
 
+    def capture(self, theta_l_per_matrix):
+        """Record one outer step into a HIP graph (every launch of `step`, on all its streams)
+        and return it; `replay` then issues the whole step with one call.  Call after at least
+        two eager steps, so that the recorded step is the steady one (feedback and update from
+        a previous average) and every kernel has been launched once; the ranks and the buffers
+        (theta_l included) are those of the recording.  Nothing runs while recording."""
+        assert self.t >= 2
+        t_before = self.t
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step(theta_l_per_matrix)
+        self.t = t_before
+        self.graph = graph
+        return graph
+
+    def replay(self):
+        self.t += 1
+        self.graph.replay()
+
+
 class RankSelector:
     """Alg. 3 for a stage: window rule over the r' values the stage measured (measure_rank)."""
 

@@ -333,3 +333,43 @@ def test_requantised_factor_averages(batched):
     plain.step(tls)
     torch.cuda.synchronize()
     assert not torch.equal(plain.mats[0].q_bar, mats[0].q_bar)   # the option does something
+
+
+def test_graph_replay_equals_eager_steps():
+    # One outer step recorded into a HIP graph (all launches, all streams) and replayed: the
+    # state after every replay must equal, bit for bit, the state of a twin stage stepped
+    # eagerly, with eager work of the same library and synchronisations between the replays.
+    shapes = [(256, 384), (512, 256), (384, 640), (256, 256)]
+    K, r = 3, 16
+
+    def make(streams):
+        mats, tls = [], []
+        for a, (m, n) in enumerate(shapes):
+            inp = synth.MatrixInputs(m, n, K, r, seed=700 + a, sigma=1e-3, alpha=1.0, theta_l="bf16")
+            mats.append(MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), 4, 64, dlcx.MMA_BF16))
+            tls.append([to_dev(inp.theta_local(inp.theta_g, 1, i)) for i in range(K)])
+        return Stage(mats, synth.LR, synth.MU, fused=True, warm_start=True, streams=streams,
+                     measure_rank=True), tls
+
+    eager, tls_e = make(3)
+    graphed, tls_g = make(3)
+    for _ in range(2):
+        eager.step(tls_e)
+        graphed.step(tls_g)
+    torch.cuda.synchronize()
+    graphed.capture(tls_g)
+    scratch = torch.zeros(1 << 16, device=DEV)
+    for rep in range(4):
+        eager.step(tls_e)
+        graphed.replay()
+        torch.cuda.synchronize()
+        for A, B in zip(eager.mats, graphed.mats):
+            assert torch.equal(A.theta_g, B.theta_g) and torch.equal(A.v, B.v), rep
+            assert torch.equal(A.q_bar, B.q_bar) and torch.equal(A.p_hat, B.p_hat), rep
+            for x, y in zip(A.ef, B.ef):
+                assert torch.equal(x, y), rep
+        assert torch.equal(eager.rprime_dev, graphed.rprime_dev), rep
+        # eager work between the replays
+        dlcx.dlcx_outer_nesterov(scratch, scratch.clone(), scratch.clone(), 0.5, 0.5)
+        torch.cuda.synchronize()
+    assert eager.t == graphed.t == 6
