@@ -605,9 +605,21 @@ __global__ __launch_bounds__(kW) void round_mfma_kernel(
         }
     };
     const int Kw = ep.K;
-    int64_t jt = jbegin + wave * 64;
-    if (jt < jend) issue(jt, 0, true, ep.apply && Kw == 1);
-    for (; jt < jend; jt += 256) {
+    // This wavefront's tiles are the columns jw + 256 t, t = 0 .. nw - 1.  They are visited in
+    // rotated order, starting at tile ib mod nw: the workgroups of a launch start together, and
+    // without the rotation all of them would sweep the same columns of different rows at the
+    // same time, rows whose distance in memory is the same multiple of a power of two for the
+    // common matrix widths.
+    const int64_t jw = jbegin + wave * 64;
+    const int64_t nw = jw < jend ? (jend - jw + 255) >> 8 : 0;
+    const int64_t shift = nw > 0 ? ib % nw : 0;
+    auto tile_at = [&](int64_t i) {
+        const int64_t t = i + shift;
+        return jw + ((t >= nw ? t - nw : t) << 8);
+    };
+    if (nw > 0) issue(tile_at(0), 0, true, ep.apply && Kw == 1);
+    for (int64_t it = 0; it < nw; ++it) {
+        const int64_t jt = tile_at(it);
         // ---- d = P_hat_prev Q_bar_prev^T for this wavefront's 32 x 64 tile
         f32x16_t d[2];
 #pragma unroll
@@ -700,8 +712,8 @@ __global__ __launch_bounds__(kW) void round_mfma_kernel(
                 // operands of the next item, in flight while this one is multiplied
                 if (!last) {
                     issue(jt, k + 1, false, ep.apply && k + 1 == Kw - 1);
-                } else if (jt + 256 < jend) {
-                    issue(jt + 256, 0, true, ep.apply && Kw == 1);
+                } else if (it + 1 < nw) {
+                    issue(tile_at(it + 1), 0, true, ep.apply && Kw == 1);
                 }
                 wave_lds_sync();
 #pragma unroll
@@ -948,6 +960,7 @@ int launch_reconstruct_mfma(int mma, int64_t m, int64_t n, int r, const float *p
 
 // ---- fused round: workspace layout and launch ------------------------------------------------
 static int kRoundWgTarget = 512;  // workgroups wanted per launch (column ranges per row block)
+constexpr int kComputeUnits = 256;
 struct RoundPlan {
     int chunks;        // column ranges per row block = slabs per worker
     int64_t cols;      // columns per workgroup (multiple of 256)
@@ -964,6 +977,23 @@ static RoundPlan round_plan(int64_t m, int64_t n, int r) {
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks > 4) chunks = 4;
     if (chunks < 1) chunks = 1;
+    // One workgroup occupies a compute unit, so the launch runs in rounds of kComputeUnits
+    // workgroups: among the admissible numbers of column ranges from there up, take the one
+    // that leaves the last round fullest (the first such, for the least slab traffic).
+    {
+        const int64_t top = max_chunks < 4 ? max_chunks : 4;
+        double best = 0.0;
+        int64_t pick = chunks;
+        for (int64_t c = chunks; c <= top; ++c) {
+            const int64_t wgs = rows * c;
+            const double eff = (double)wgs / (double)(ceil_div(wgs, kComputeUnits) * kComputeUnits);
+            if (eff > best + 1e-9) {
+                best = eff;
+                pick = c;
+            }
+        }
+        chunks = pick;
+    }
     p.cols = ceil_div(ceil_div(n, chunks), 256) * 256;
     p.chunks = (int)ceil_div(n, p.cols);
     return p;
