@@ -170,13 +170,13 @@ int dlcx_ef_update(int K, float *const *ef_inout_host, const float *delta_hat, i
  * hops would deliver it, instead of the fp32 mean that dlcx_average leaves. */
 int dlcx_requantize(float *x_inout, int64_t count, int qbits, int group, void *stream);
 
-/* Communication model of Sec. 3.3.1 (host only).  A ring all-reduce between `clusters` clusters
+/* Communication model of Sec. 2.4.1 (host only).  A ring all-reduce between `clusters` clusters
  * moves 2 (clusters - 1) / clusters of the payload over the link between two of them;
  * returns the seconds that takes at `bits_per_second`.  Negative on bad arguments. */
 double dlcx_comm_seconds(double payload_bytes, int clusters, double bits_per_second);
 
 /* Choice of (rank, local steps) that just hides the exchange of one outer step behind local
- * training (the one-step-delay overlap of Sec. 3.2 needs comm <= H * step time).  The payload
+ * training (the one-step-delay overlap of Sec. 2.3 needs comm <= H * step time).  The payload
  * of a worker at rank r is the sum over the n_matrices descriptors of both quantised factors
  * (r clipped to each matrix's smaller side) plus extra_bytes (tensors sent without low-rank).
  * *r_out is the largest rank in [rmin, rmax] whose exchange fits H * step_seconds and *H_out = H;

@@ -2,8 +2,8 @@
 
 TEST INFRASTRUCTURE ONLY (see oracle/ref.py).
 
-Sec. 3.3.1 (analysis of communication overhead): with a ring all-reduce between C clusters the
-link between two clusters carries 2 (C - 1) / C of what every worker holds.  Sec. 3.2 (one-step
+Sec. 2.4.1 (analysis of communication overhead): with a ring all-reduce between C clusters the
+link between two clusters carries 2 (C - 1) / C of what every worker holds.  Sec. 2.3 (one-step
 delay): the exchange of outer step t-1 runs beside the H local steps of outer step t, so it is
 hidden when it takes no longer than H local steps.
 """

@@ -121,7 +121,7 @@ def test_quantise_only_entry_points_reject_bad_arguments():
 
 
 def test_comm_model_and_overlap_plan_on_the_host(golden):
-    # the library's host-side planner against the oracle's exhaustive one (Sec. 3.3.1, 3.2)
+    # the library's host-side planner against the oracle's exhaustive one (Sec. 2.4.1, 2.3)
     from oracle import planner
     g = golden("compression_accounting.txt")
     hours = dlcx.dlcx_comm_seconds(100e9 * 4, 3, 1e9) / 3600

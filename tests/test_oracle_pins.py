@@ -544,7 +544,7 @@ def test_requantized_factor_average_changes_only_within_the_bound():
 
 # --------------------------------------------------------------------------- communication model
 def test_comm_model_reproduces_the_papers_worked_example():
-    # Sec. 3.3.1: 100B parameters in FP32, 3 clusters, 1 Gbps, H = 500 steps of 1 s.
+    # Sec. 2.4.1: 100B parameters in FP32, 3 clusters, 1 Gbps, H = 500 steps of 1 s.
     from oracle import planner
     g = read_golden("compression_accounting.txt")
     payload = 100e9 * 4
