@@ -384,6 +384,17 @@ def main():
                     "algorithmic_bytes_per_param_per_launch": bpp,
                     "avg_launch_ms": kernels[dom]["ms_per_step"] / launches,
                     "launches_per_step": launches}
+        if dom == "round_fused" and args.mma != 0:
+            # matrix-core work of the same kernel: r (reconstruction) + r K (projection)
+            # multiply-adds per element, each as 3 (bf16x2) or 6 (bf16x3) bf16 piece products
+            pieces = 3 if args.mma == 2 else 6
+            useful = 2.0 * cfg["r"] * (1 + K) * params
+            roofline["mfma"] = {
+                "useful_TFLOPs": useful / (kernels[dom]["ms_per_step"] * 1e-3) / 1e12,
+                "executed_bf16_TFLOPs": useful * pieces / (kernels[dom]["ms_per_step"] * 1e-3) / 1e12,
+                "peak_bf16_TFLOPs": 2500.0,
+                "note": "HBM-bound: %.0f executed flop per byte against a ridge of 312"
+                        % (2.0 * cfg["r"] * (1 + K) * pieces / bpp)}
     b_alg = (14 if tl_bytes == 2 else 16) * K + 20
     out = {
         "metric": "outer-step params/sec per stage (compress+avg+Nesterov)",

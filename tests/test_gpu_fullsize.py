@@ -196,3 +196,50 @@ def test_full_size_matrix_sampled(m, n):
         assert rel_l2(got_s, sw) <= TOL, ("P round 2 scales", k)
         nb, ok = code_mismatch_report(got_c, cw, p_rows, sw, R * GROUP, QBITS, GROUP, ref.unpack_codes)
         assert ok and nb <= 0.02 * R * GROUP, ("P round 2 payload", k, nb)
+
+
+def test_quantise_only_step_full_size_sampled_groups():
+    # The quantise-only sweep on a tensor the size of the largest matrix of the stage (28672 x
+    # 8192 = 234.9 M elements, K = 4, int4 / 128, bf16 replicas), three outer steps running free.
+    # Every operation of that step is local to a group of 128 elements, so the oracle run on a
+    # sample of whole groups (first, last and 3000 drawn at random) must reproduce the GPU's
+    # values there bit for bit.  The replicas are synthetic and do not depend on GPU results.
+    from oracle import pipeline
+    numel, Kq, group, T = 28672 * 8192, 4, 128, 3
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(4242)
+    theta = 0.02 * torch.randn(numel, device=DEV, generator=gen)
+    v = torch.zeros_like(theta)
+    ef = [torch.zeros(numel, device=DEV) for _ in range(Kq)]
+    codes = [torch.zeros(numel // 2, device=DEV, dtype=torch.uint8) for _ in range(Kq)]
+    scales = [torch.zeros(numel // group, device=DEV) for _ in range(Kq)]
+    ngroups = numel // group
+    rng = np.random.default_rng(7)
+    gsel = np.unique(np.concatenate([[0, 1, ngroups - 2, ngroups - 1],
+                                     rng.integers(0, ngroups, 3000)])).astype(np.int64)
+    eidx = (torch.from_numpy(gsel).to(DEV)[:, None] * group +
+            torch.arange(group, device=DEV)[None, :]).reshape(-1)
+    gidx = torch.from_numpy(gsel).to(DEV)
+    theta0_s = theta[eidx].cpu().numpy()
+    orc = pipeline.TensorOracle(theta0_s, Kq, 4, group, synth.LR, synth.MU)
+    theta0_dev = theta.clone()
+    for t in range(1, T + 1):
+        tl = []
+        for i in range(Kq):
+            g = 1e-3 * torch.randn(numel, device=DEV, generator=gen) * (1.0 + 4.0 * (i == t % Kq))
+            tl.append((theta0_dev - g).to(torch.bfloat16))
+        orc.step([_bits(x[eidx]) for x in tl])
+        dlcx.dlcx_quant_round(numel, 4, group, tl, ef, theta, v, synth.LR, synth.MU,
+                              None if t == 1 else codes, None if t == 1 else scales, codes, scales)
+        torch.cuda.synchronize()
+        cidx = (gidx[:, None] * (group // 2) +
+                torch.arange(group // 2, device=DEV)[None, :]).reshape(-1)
+        for i in range(Kq):
+            assert np.array_equal(codes[i][cidx].cpu().numpy(), orc.codes[i]), (t, i)
+            assert np.array_equal(scales[i][gidx].cpu().numpy().view(np.uint32),
+                                  orc.scales[i].view(np.uint32)), (t, i)
+            assert np.array_equal(ef[i][eidx].cpu().numpy().view(np.uint32),
+                                  orc.ef[i].view(np.uint32)), (t, i)
+        assert np.array_equal(theta[eidx].cpu().numpy().view(np.uint32), orc.theta.view(np.uint32)), t
+        assert np.array_equal(v[eidx].cpu().numpy().view(np.uint32), orc.v.view(np.uint32)), t
+    assert orc.n_applied == T - 1 and not np.array_equal(orc.theta, theta0_s)
