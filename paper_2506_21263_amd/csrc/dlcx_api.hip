@@ -568,7 +568,11 @@ int dlcx_ef_delta_apply_compress(const dlcx_desc *desc, int32_t r_prev, const fl
             !aligned16(codes_out_host[k]) || !aligned16(scales_out_host[k]))
             return DLCX_EINVAL;
     }
-    if (desc->mma == DLCX_MMA_FMA) {  // no fused kernel in this mode: the same steps one by one
+    // No fused kernel in the FMA mode.  Above rank 64 the fused kernel would need one launch per
+    // worker (its accumulators are r x 32 per worker and wavefront) and re-read the fragments of
+    // both products for every tile and worker; the feedback / update sweep followed by the
+    // projection kernel moves 16 more bytes per element and is about twice as fast there.
+    if (desc->mma == DLCX_MMA_FMA || desc->r > 64) {
         if (r_prev > 0) {
             dlcx_desc dp = *desc;
             dp.r = r_prev;

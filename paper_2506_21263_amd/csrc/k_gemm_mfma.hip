@@ -969,8 +969,8 @@ struct RoundPlan {
 
 static RoundPlan round_plan(int64_t m, int64_t n, int r) {
     RoundPlan p;
-    const int cb = cb_of(r);
-    p.kc = cb <= 2 ? 4 : cb == 4 ? 2 : 1;
+    (void)r;
+    p.kc = 4;
     const int64_t rows = ceil_div(m, 32);
     int64_t chunks = ceil_div(kRoundWgTarget, rows);
     const int64_t max_chunks = ceil_div(n, 256);
@@ -1092,11 +1092,10 @@ static int round_ns(int64_t m, int64_t n, int r, int r_prev, const float *p_hat,
             dst.p[k] = pl.chunks > 1 ? slabs + (int64_t)(k0 + k) * pl.chunks * slab
                                      : factors.p[k0 + k];
         }
-        switch (cb) {
+        switch (cb) {  // ranks above 64 do not come here: see dlcx_ef_delta_apply_compress
             case 1: rc = round_launch<NS, 1, 4>(pf, qf, ks, bf, ep, dst, m, n, r, pl, slab, st); break;
             case 2: rc = round_launch<NS, 2, 4>(pf, qf, ks, bf, ep, dst, m, n, r, pl, slab, st); break;
-            case 4: rc = round_launch<NS, 4, 2>(pf, qf, ks, bf, ep, dst, m, n, r, pl, slab, st); break;
-            default: rc = round_launch<NS, 8, 1>(pf, qf, ks, bf, ep, dst, m, n, r, pl, slab, st); break;
+            default: rc = DLCX_EINVAL; break;
         }
         if (rc != DLCX_OK) return rc;
     }

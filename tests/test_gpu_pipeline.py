@@ -40,6 +40,9 @@ CASES = [
     ("cfg2-like", 1024, 768, 4, 64, 4, 128, "bf16", 2, 1e-3),
     ("cfg4-like", 768, 1024, 8, 64, 8, 64, "bf16", 2, 1e-3),
     ("ragged", 528, 336, 3, 20, 4, 16, "bf16", 2, 1e-3),
+    # ranks above 64: the fused entry point takes the sweep-plus-projection form
+    ("rank96", 640, 2048, 2, 96, 4, 128, "bf16", 2, 1e-3),
+    ("rank256-K5", 2048, 512, 5, 256, 8, 64, "f32", 2, 1e-3),
 ]
 
 
