@@ -376,3 +376,59 @@ def test_graph_replay_equals_eager_steps():
         dlcx.dlcx_outer_nesterov(scratch, scratch.clone(), scratch.clone(), 0.5, 0.5)
         torch.cuda.synchronize()
     assert eager.t == graphed.t == 6
+
+
+@pytest.mark.parametrize("mma", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+def test_zero_pseudo_gradient_stays_zero(mma, fused):
+    # Replicas that did not move (theta_l = theta_g, zero error buffers): every factor, payload
+    # and average is exactly zero (no NaN from the orthonormalisation of a zero matrix), theta
+    # and v do not change over three outer steps, and the measured r' is 0 (counted as rmin).
+    m, n, K, r = 256, 384, 3, 8
+    rng = np.random.default_rng(3)
+    theta0 = (0.02 * rng.standard_normal((m, n))).astype(np.float32)
+    q_in = rng.standard_normal((r, n)).astype(np.float32)
+    M = MatrixState(to_dev(theta0), K, to_dev(q_in), 4, 64, mma)
+    st = Stage([M], synth.LR, synth.MU, fused=fused, warm_start=False, measure_rank=True)
+    tl = [[to_dev(theta0) for _ in range(K)]]
+    for _ in range(3):
+        st.step(tl)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(M.theta_g), theta0)
+    assert not torch.any(M.v != 0) and not torch.any(M.q_bar[:r] != 0)
+    assert not torch.any(M.p_hat[:r] != 0)
+    for k in range(K):
+        assert not torch.any(M.ef[k] != 0)
+        assert not torch.any(M.codes_p[k] != 0) and not torch.any(M.codes_q[k] != 0)
+    assert int(st.rprime_dev[0]) == 0
+
+
+@pytest.mark.parametrize("mma", MODES, ids=MODE_IDS)
+def test_rank_one_single_worker_lockstep(mma):
+    # the smallest compressor: r = 1, K = 1 (the mean is the decoded payload itself).  One round
+    # from the oracle's state, every float at the mode's bar, codes against the oracle's
+    # quantiser of the GPU's own factor.
+    m, n, r, K, qbits, group = 272, 208, 1, 1, 8, 16
+    inp = synth.MatrixInputs(m, n, K, r, seed=41, sigma=1e-3, alpha=1.0, theta_l="bf16")
+    orc = pipeline.MatrixOracle(inp.theta_g, K, inp.q_in, qbits, group, synth.LR, synth.MU)
+    M = MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), qbits, group, mma)
+    st = Stage([M], synth.LR, synth.MU, fused=True, warm_start=True)
+    tol = TOL[mma]
+    for t in (1, 2):
+        tl = [inp.theta_local(orc.theta, t, 0)]
+        # lockstep: the GPU starts the round from the oracle's state
+        M.theta_g.copy_(to_dev(orc.theta))
+        M.v.copy_(to_dev(orc.v))
+        M.ef[0].copy_(to_dev(orc.ef[0]))
+        if t == 2:
+            M.p_hat[:r].copy_(to_dev(orc.p_hat))
+            M.q_bar[:r].copy_(to_dev(orc.q_bar))
+        orc.step(tl)
+        orc.set_basis(orc.q_bar)
+        st.step([[to_dev(tl[0])]])
+        torch.cuda.synchronize()
+        assert rel_l2(to_np(M.ef[0]), orc.trace["delta"][0]) <= tol
+        assert rel_l2(to_np(M.theta_g), orc.theta) <= tol
+        # sign and scale of a rank-one basis are fixed by the positive-diagonal rule
+        assert rel_l2(to_np(M.p_hat)[:r], orc.p_hat) <= 20 * tol
+        assert rel_l2(to_np(M.q_bar)[:r], orc.q_bar) <= 20 * tol
