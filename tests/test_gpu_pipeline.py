@@ -432,3 +432,35 @@ def test_rank_one_single_worker_lockstep(mma):
         # sign and scale of a rank-one basis are fixed by the positive-diagonal rule
         assert rel_l2(to_np(M.p_hat)[:r], orc.p_hat) <= 20 * tol
         assert rel_l2(to_np(M.q_bar)[:r], orc.q_bar) <= 20 * tol
+
+
+@pytest.mark.parametrize("mma", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+@pytest.mark.parametrize("qbits,K", [(8, 3), (4, 2)])
+def test_exactly_representable_input_passes_the_compressor_unchanged(mma, fused, qbits, K):
+    # Closed form with the quantiser ON (see the oracle pin of the same name): +-1 factor
+    # vectors and singular values qmax * 2^-c make every factor entry +-qmax times a power of
+    # two, so the codes are all +-qmax, Delta equals the pseudo-gradient and the second outer
+    # step is the Nesterov step of exactly that gradient.  Holds in every product mode: the
+    # operands have few enough bits for the bf16 splits to be exact.
+    from test_oracle_pins import exact_lowrank_case
+    qmax = 2 ** (qbits - 1) - 1
+    m, n, r, theta0, tl, q_in, delta = exact_lowrank_case(qmax, K)
+    M = MatrixState(to_dev(theta0), K, to_dev(q_in), qbits, 16, mma)
+    st = Stage([M], 0.5, 0.0, fused=fused, warm_start=True)
+    st.step([[to_dev(x) for x in tl]])
+    d_hat = torch.zeros(m, n, device=DEV)
+    dlcx.dlcx_decompress(M.desc(), M.p_hat, M.q_bar, d_hat, workspace=st.workspace)
+    torch.cuda.synchronize()
+    for k in range(K):
+        assert np.array_equal(to_np(M.ef[k]), delta)
+        codes = ref.unpack_codes(to_np(M.codes_p[k]), r * m, qbits)
+        assert np.all(np.abs(codes) == qmax)
+        codes = ref.unpack_codes(to_np(M.codes_q[k]), r * n, qbits)
+        assert np.all(np.abs(codes) == qmax)
+    assert np.max(np.abs(np.abs(to_np(M.p_hat)[:r]) - 0.25)) <= 1e-7
+    assert rel_l2(to_np(d_hat), delta) <= 1e-6
+    st.step([[to_dev(theta0) for _ in range(K)]])
+    torch.cuda.synchronize()
+    assert rel_l2(to_np(M.theta_g), -0.5 * delta) <= 1e-6
+    assert np.max(np.abs(to_np(M.ef[0]))) <= 1e-6 * np.max(np.abs(delta))
