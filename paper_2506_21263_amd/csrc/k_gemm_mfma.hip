@@ -435,7 +435,6 @@ __global__ __launch_bounds__(kW) void reconstruct_mfma_kernel(
         if (jt < jend) {
             const int64_t jb0 = jt >> 5;
             const bool two = jb0 + 1 < nblk;
-#pragma unroll 2
             for (int s = 0; s < KS; ++s) {
                 uint4 a[NS], b0[NS], b1[NS];
 #pragma unroll
@@ -458,7 +457,6 @@ __global__ __launch_bounds__(kW) void reconstruct_mfma_kernel(
         __syncthreads();
         const int64_t j = jt + pc4 * 4;
         if (jt >= jend || j >= n) continue;
-#pragma unroll 2
         for (int pass = 0; pass < 8; ++pass) {
             const int row = pass * 4 + prow;
             const int64_t i = ib * 32 + row;
@@ -629,7 +627,6 @@ __global__ __launch_bounds__(kW) void round_mfma_kernel(
         {
             const int64_t jb0 = jt >> 5;
             const bool two = jb0 + 1 < nblk;
-#pragma unroll 2
             for (int s = 0; s < KS; ++s) {
                 uint4 a[NS], b0[NS], b1[NS];
 #pragma unroll
