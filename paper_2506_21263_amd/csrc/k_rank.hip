@@ -1,10 +1,14 @@
 // r' of Alg. 3 for one matrix: the smallest k whose k largest eigenvalues of S = Q_bar^T Q_bar
 // hold at least tau of the trace (with P_hat orthonormal these are the squared singular values of
 // the decompressed average).  S is accumulated in fp64 (same partial-sum kernel as the
-// orthonormalisation); its eigenvalues come from a one-sided Jacobi iteration on the columns of S
-// (S is symmetric positive semi-definite, so the column norms at convergence are the
-// eigenvalues), run by one workgroup with a round-robin pair schedule; then sort, prefix sum and
-// count, all in fp64.
+// orthonormalisation).  One workgroup per matrix finds its eigenvalues, all in fp64:
+//   r <= 128: S fits in LDS; one-sided Jacobi iteration on the columns of S (S is symmetric
+//             positive semi-definite, so the column norms at convergence are the eigenvalues)
+//             with a round-robin pair schedule;
+//   r  > 128: S stays in global memory (L2); Householder reduction to tridiagonal form (each
+//             step one symmetric matrix-vector product and one rank-2 update of the trailing
+//             block), then every eigenvalue by bisection on the Sturm sequence, one thread each.
+// Then sort, prefix sum and count.
 #include "common.h"
 
 namespace dlcx {
@@ -18,7 +22,114 @@ __device__ __forceinline__ double team_sum(double v) {
     return v;
 }
 
-constexpr size_t kJacobiLdsMax = 140 * 1024;
+constexpr size_t kJacobiLdsMax = 128 * 1024;
+
+// Sum of one value per thread over the workgroup, in a fixed order; every thread gets it.
+__device__ __forceinline__ double block_sum(double v, double *red, int nthreads) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    __syncthreads();  // earlier readers of red are done
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double s = 0.0;
+    for (int w = 0; w < nthreads / 64; ++w) s += red[w];
+    return s;
+}
+
+// Eigenvalues of the symmetric r x r matrix a (column-major, leading dimension ld, both halves
+// stored, in global memory), descending, negative ones clamped to zero, into out[0..r).
+// d, e, v, w: r doubles each; psum: (nthreads / 256) * 256 doubles; red: 16 doubles (all LDS).
+__device__ void tridiagonal_eigenvalues(double *a, int r, int ld, double *d, double *e, double *v,
+                                        double *w, double *psum, double *red, double *out,
+                                        int nthreads) {
+    const int tid = threadIdx.x;
+    const int parts = nthreads / 256;
+    for (int k = 0; k + 2 < r; ++k) {
+        const int L = r - k - 1;
+        double *x = a + (int64_t)k * ld + k + 1;  // column k below the diagonal
+        const double xt = tid < L ? x[tid] : 0.0;
+        const double sumsq = block_sum(xt * xt, red, nthreads);
+        const double x0 = x[0];
+        const double tail = sumsq - x0 * x0;
+        if (tid == 0) d[k] = a[(int64_t)k * ld + k];
+        if (!(tail > 0.0)) {  // already tridiagonal in this column: no reflection
+            if (tid == 0) e[k] = x0;
+            __syncthreads();
+            continue;
+        }
+        const double alpha = -copysign(sqrt(sumsq), x0);
+        const double v0 = x0 - alpha;
+        const double beta = 2.0 / (tail + v0 * v0);
+        if (tid < L) v[tid] = tid == 0 ? v0 : xt;
+        if (tid == 0) e[k] = alpha;
+        __syncthreads();
+        // p = beta * A22 v: thread (part, i) sums its quarter of the columns of row i
+        double *a22 = a + (int64_t)(k + 1) * ld + k + 1;
+        {
+            const int i = tid & 255, part = tid >> 8;
+            const int per = (L + parts - 1) / parts;
+            const int j0 = part * per, j1 = j0 + per < L ? j0 + per : L;
+            double acc = 0.0;
+            if (i < L)
+                for (int j = j0; j < j1; ++j) acc = fma(a22[(int64_t)j * ld + i], v[j], acc);
+            psum[part * 256 + i] = acc;
+        }
+        __syncthreads();
+        double pi = 0.0;
+        if (tid < L) {
+            for (int q = 0; q < parts; ++q) pi += psum[q * 256 + tid];
+            pi *= beta;
+        }
+        const double vp = block_sum(tid < L ? v[tid] * pi : 0.0, red, nthreads);
+        const double kk = 0.5 * beta * vp;
+        if (tid < L) w[tid] = pi - kk * v[tid];
+        __syncthreads();
+        // A22 <- A22 - v w^T - w v^T
+        for (int idx = tid; idx < L * L; idx += nthreads) {
+            const int i = idx % L, j = idx / L;
+            double *p = a22 + (int64_t)j * ld + i;
+            *p = *p - (v[i] * w[j] + w[i] * v[j]);
+        }
+        __threadfence_block();
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (r >= 2) {
+            d[r - 2] = a[(int64_t)(r - 2) * ld + r - 2];
+            e[r - 2] = a[(int64_t)(r - 2) * ld + r - 1];
+        }
+        d[r - 1] = a[(int64_t)(r - 1) * ld + r - 1];
+    }
+    __syncthreads();
+    // Gershgorin interval, then the c-th largest eigenvalue by bisection: the number of negative
+    // terms of the Sturm sequence at x is the number of eigenvalues below x
+    double lo0 = d[0], hi0 = d[0];
+    for (int i = 0; i < r; ++i) {
+        const double rad = (i > 0 ? fabs(e[i - 1]) : 0.0) + (i + 1 < r ? fabs(e[i]) : 0.0);
+        lo0 = fmin(lo0, d[i] - rad);
+        hi0 = fmax(hi0, d[i] + rad);
+    }
+    for (int c = tid; c < r; c += nthreads) {
+        const int below = r - 1 - c;  // eigenvalues smaller than the one wanted
+        double lo = lo0, hi = hi0;
+        for (int itn = 0; itn < 200; ++itn) {
+            const double mid = 0.5 * (lo + hi);
+            if (!(mid > lo && mid < hi)) break;
+            int cnt = 0;
+            double q = d[0] - mid;
+            cnt += q < 0.0;
+            for (int i = 1; i < r; ++i) {
+                if (fabs(q) < 1e-300) q = -1e-300;
+                q = d[i] - mid - e[i - 1] * e[i - 1] / q;
+                cnt += q < 0.0;
+            }
+            if (cnt > below) hi = mid;
+            else lo = mid;
+        }
+        out[c] = fmax(0.5 * (lo + hi), 0.0);
+    }
+    __syncthreads();
+}
 
 __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, double tau) {
     const int nthreads = blockDim.x;  // 256 for small matrices, 1024 when r > 128
@@ -32,6 +143,8 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, dou
     double *a = a_in_lds ? smem : it.g;              // column-major re x re: a[col * re + row]
     __shared__ double eig[DLCX_MAX_RANK];
     __shared__ double sorted[DLCX_MAX_RANK];
+    __shared__ double tri_e[DLCX_MAX_RANK], tri_v[DLCX_MAX_RANK], tri_w[DLCX_MAX_RANK];
+    __shared__ double tri_psum[(kJT / 256) * 256], tri_red[kJT / 64];
     __shared__ int rotated;
     const int tid = threadIdx.x;
     for (int x = tid; x < re * re; x += nthreads) {
@@ -46,7 +159,12 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, dou
     __syncthreads();
     const int team = tid >> 4, lane = tid & 15;
     const int npairs = re / 2;
-    for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
+    if (!a_in_lds) {
+        __threadfence_block();
+        tridiagonal_eigenvalues(a, r, re, eig, tri_e, tri_v, tri_w, tri_psum, tri_red, sorted,
+                                nthreads);
+    }
+    for (int sweep = 0; a_in_lds && sweep < kMaxSweeps; ++sweep) {
         if (tid == 0) rotated = 0;
         __syncthreads();
         for (int step = 0; step < re - 1; ++step) {
@@ -90,19 +208,21 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, dou
         __syncthreads();
         if (!any) break;
     }
-    for (int c = tid; c < r; c += nthreads) {
-        double s = 0.0;
-        for (int i = 0; i < re; ++i) s = fma(a[c * re + i], a[c * re + i], s);
-        eig[c] = sqrt(s);
+    if (a_in_lds) {
+        for (int c = tid; c < r; c += nthreads) {
+            double s = 0.0;
+            for (int i = 0; i < re; ++i) s = fma(a[c * re + i], a[c * re + i], s);
+            eig[c] = sqrt(s);
+        }
+        __syncthreads();
+        for (int c = tid; c < r; c += nthreads) {  // rank sort, descending, ties by index
+            const double e = eig[c];
+            int pos = 0;
+            for (int u = 0; u < r; ++u) pos += (eig[u] > e) || (eig[u] == e && u < c);
+            sorted[pos] = e;
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    for (int c = tid; c < r; c += nthreads) {  // rank sort, descending, ties by index
-        const double e = eig[c];
-        int pos = 0;
-        for (int u = 0; u < r; ++u) pos += (eig[u] > e) || (eig[u] == e && u < c);
-        sorted[pos] = e;
-    }
-    __syncthreads();
     if (tid == 0) {
         double total = 0.0;
         for (int c = 0; c < r; ++c) total += sorted[c];

@@ -267,7 +267,8 @@ def test_effective_rank_prescribed_spectra(alpha, want):
     assert int(out.item()) == want
 
 
-@pytest.mark.parametrize("n,r", [(64, 1), (128, 7), (528, 33), (1024, 64), (768, 128), (512, 130)])
+@pytest.mark.parametrize("n,r", [(64, 1), (128, 7), (528, 33), (1024, 64), (768, 128), (512, 129),
+                                 (512, 130), (1024, 192), (512, 255), (768, 256)])
 def test_effective_rank_random_and_zero(n, r):
     g = rng(n + r)
     q = (g.standard_normal((r, n)) * (np.arange(1, r + 1)[:, None] ** -1.2)).astype(np.float32)
@@ -278,6 +279,17 @@ def test_effective_rank_random_and_zero(n, r):
         assert int(out.item()) == ref.effective_rank(q, tau), tau
     dlcx.dlcx_effective_rank(n, r, torch.zeros(r, n, device=DEV), 0.99, out, ws)
     assert int(out.item()) == 0
+    if r >= 8:  # rank-deficient Gram: repeated, zero and low-rank columns
+        q2 = q.copy()
+        q2[5] = q2[3]
+        q2[6] = 0.0
+        q2[r // 2:] = (g.standard_normal((r - r // 2, 3)) @ g.standard_normal((3, n))).astype(np.float32)
+        for tau in (0.9, 0.999, 1.0):
+            dlcx.dlcx_effective_rank(n, r, to_dev(q2), tau, out, ws)
+            want = ref.effective_rank(q2, tau)
+            # at tau = 1 the count depends on eigenvalues at rounding level: not compared
+            if tau < 1.0:
+                assert int(out.item()) == want, tau
 
 
 def test_select_rank_stage_value_and_window():
