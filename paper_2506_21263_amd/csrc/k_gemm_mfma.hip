@@ -142,31 +142,49 @@ __global__ __launch_bounds__(kW) void pack_kstrided_kernel(const float *__restri
 
 // ---------------------------------------------------------------------------------------------
 // P phase:  P_k[i][c] = sum_j delta_k[i][j] Q_in[c][j].
-// Workgroup: 64 rows of delta (2 row blocks), swept along j in stages of 64 (4 k-steps).
+// Workgroup: RB row blocks (32 RB rows) of delta, swept along j in stages of 64 (4 k-steps).
 // The 4 wavefronts split the work as WC (groups of CBW basis blocks) x WK (halves of a stage) x
-// WR (row blocks).  A = basis fragments (M = c), B = delta from LDS (N = i): D[c][i].
+// WR (groups of row blocks).  A = basis fragments (M = c), B = delta from LDS (N = i): D[c][i].
+// A basis fragment serves RB / WR row blocks once it is in registers, so the fragment traffic
+// per byte of delta falls with RB: at r = 256 it is 4 : 1 with 64 rows and 2 : 1 with 128, which
+// is what lets the matrix cores, not L2, set the pace there.
 // ---------------------------------------------------------------------------------------------
 constexpr int kPPitch = 64 * 2 + 16;  // bytes per LDS row of one piece: 64 bf16 + pad
 
-template <int NS, int CBW, int WC, int WK, int WR>
+// Workgroup barrier for data exchanged through LDS: every LDS access of this wavefront has
+// completed before it arrives, and the compiler moves no memory access across.  Global loads
+// that are still outstanding (the next stage, already requested) are NOT waited for, which
+// __syncthreads() would do.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int NS, int CBW, int WC, int WK, int WR, int RB>
+constexpr int project_p_lds_bytes() {
+    constexpr int buf = 2 * NS * 32 * RB * kPPitch;
+    constexpr int red = (WK == 2) ? 2 * CBW * (RB / WR) * 16 * 64 * 4 : 0;
+    return buf > red ? buf : red;
+}
+
+template <int NS, int CBW, int WC, int WK, int WR, int RB>
 __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float *> deltas,
                                                             const uint4 *__restrict__ afrags,
                                                             PtrPack<float *> outs, int64_t m,
                                                             int64_t n, int r) {
     constexpr int CB = CBW * WC;
-    constexpr int RBW = 2 / WR;
+    constexpr int RBW = RB / WR;
     constexpr int KSW = 4 / WK;
+    constexpr int kRows = 32 * RB;
+    constexpr int kVec = kRows * 16 / kW;  // float4 per thread and stage
     static_assert(WC * WK * WR == 4, "four wavefronts");
-    constexpr int kBuf = NS * 64 * kPPitch;
-    constexpr int kRed = (WK == 2) ? 2 * CBW * RBW * 16 * 64 * 4 : 0;
-    constexpr int kLds = (2 * kBuf > kRed) ? 2 * kBuf : kRed;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
+    constexpr int kBuf = NS * kRows * kPPitch;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const float *__restrict__ delta = deltas.p[blockIdx.y];
     float *__restrict__ out = outs.p[blockIdx.y];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wc = wave % WC, wk = (wave / WC) % WK, wr = wave / (WC * WK);
-    const int64_t i0 = (int64_t)blockIdx.x * 64;
+    const int64_t i0 = (int64_t)blockIdx.x * kRows;
     const int64_t nstages = (n + 63) / 64;
 
     f32x16_t acc[CBW][RBW];
@@ -177,11 +195,11 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    // this thread's four float4 of a stage: (row, 4 columns)
-    float4 pre[4];
+    // this thread's float4 of a stage: (row, 4 columns)
+    float4 pre[kVec];
     auto load_stage = [&](int64_t t) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kVec; ++u) {
             const int idx = tid + kW * u;
             const int row = idx >> 4, c4 = idx & 15;
             const int64_t j = t * 64 + c4 * 4;
@@ -194,7 +212,7 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
     for (int64_t t = 0; t < nstages; ++t) {
         unsigned char *buf = lds + (t & 1) * kBuf;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kVec; ++u) {
             const int idx = tid + kW * u;
             const int row = idx >> 4, c4 = idx & 15;
             uint32_t lo[NS], hi[NS];
@@ -202,10 +220,11 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
             split2<NS>(pre[u].z, pre[u].w, hi);
 #pragma unroll
             for (int h = 0; h < NS; ++h)
-                *reinterpret_cast<uint2 *>(buf + (h * 64 + row) * kPPitch + c4 * 8) =
+                *reinterpret_cast<uint2 *>(buf + (h * kRows + row) * kPPitch + c4 * 8) =
                     make_uint2(lo[h], hi[h]);
         }
-        if (t + 1 < nstages) load_stage(t + 1);
+        // the basis fragments of this stage are requested before the next stage of delta, so
+        // that waiting for them does not wait for that stage as well
         uint4 a[KSW][CBW][NS];
 #pragma unroll
         for (int ks = 0; ks < KSW; ++ks)
@@ -216,7 +235,10 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
                     const int64_t sg = t * 4 + wk * KSW + ks;
                     a[ks][cb][h] = afrags[((sg * CB + wc * CBW + cb) * NS + h) * 64 + lane];
                 }
-        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < nstages) load_stage(t + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_barrier();
 #pragma unroll
         for (int ks = 0; ks < KSW; ++ks) {
             const int s = wk * KSW + ks;
@@ -227,7 +249,7 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
                 for (int h = 0; h < NS; ++h) {
                     const int row = (wr * RBW + rb) * 32 + (lane & 31);
                     b[rb][h] = *reinterpret_cast<const uint4 *>(
-                        buf + (h * 64 + row) * kPPitch + s * 32 + (lane >> 5) * 16);
+                        buf + (h * kRows + row) * kPPitch + s * 32 + (lane >> 5) * 16);
                 }
 #pragma unroll
             for (int cb = 0; cb < CBW; ++cb)
@@ -829,6 +851,27 @@ static int pack_kcontig(const float *src, int nrows, int64_t L, int RB, int64_t 
     return check_launch("pack_kcontig");
 }
 
+template <int NS, int CBW, int WC, int WK, int WR, int RB>
+static int project_p_launch(const PtrPack<const float *> &delta, const uint4 *frags,
+                            const PtrPack<float *> &out, int64_t m, int64_t n, int r, int K,
+                            hipStream_t st) {
+    constexpr int lds = project_p_lds_bytes<NS, CBW, WC, WK, WR, RB>();
+    static bool granted = false;
+    if (lds > 48 * 1024 && !granted) {
+        int rc = note_hip(
+            hipFuncSetAttribute(
+                reinterpret_cast<const void *>(project_p_mfma_kernel<NS, CBW, WC, WK, WR, RB>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, lds),
+            "project_p attribute");
+        if (rc != DLCX_OK) return rc;
+        granted = true;
+    }
+    const dim3 grid((unsigned)ceil_div(m, 32 * RB), (unsigned)K);
+    hipLaunchKernelGGL((project_p_mfma_kernel<NS, CBW, WC, WK, WR, RB>), grid, dim3(kW), lds, st,
+                       delta, frags, out, m, n, r);
+    return DLCX_OK;
+}
+
 template <int NS>
 static int project_p_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const float *> &delta,
                         const float *q_in, const PtrPack<float *> &out, void *workspace,
@@ -838,14 +881,20 @@ static int project_p_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
     uint4 *frags = reinterpret_cast<uint4 *>(workspace);
     int rc = pack_kcontig<NS>(q_in, r, n, cb, KS, frags, st);
     if (rc != DLCX_OK) return rc;
-    const dim3 grid((unsigned)ceil_div(m, 64), (unsigned)K);
     Timed timed(KID_PROJECT_P, st);
     switch (cb) {
-        case 1: hipLaunchKernelGGL((project_p_mfma_kernel<NS, 1, 1, 2, 2>), grid, dim3(kW), 0, st, delta, frags, out, m, n, r); break;
-        case 2: hipLaunchKernelGGL((project_p_mfma_kernel<NS, 2, 1, 2, 2>), grid, dim3(kW), 0, st, delta, frags, out, m, n, r); break;
-        case 4: hipLaunchKernelGGL((project_p_mfma_kernel<NS, 2, 2, 1, 2>), grid, dim3(kW), 0, st, delta, frags, out, m, n, r); break;
-        default: hipLaunchKernelGGL((project_p_mfma_kernel<NS, 2, 4, 1, 1>), grid, dim3(kW), 0, st, delta, frags, out, m, n, r); break;
+        case 1: rc = project_p_launch<NS, 1, 1, 2, 2, 2>(delta, frags, out, m, n, r, K, st); break;
+        case 2: rc = project_p_launch<NS, 2, 1, 2, 2, 2>(delta, frags, out, m, n, r, K, st); break;
+        case 4: rc = project_p_launch<NS, 2, 2, 1, 2, 2>(delta, frags, out, m, n, r, K, st); break;
+        default:
+            // 128 rows per workgroup once that still gives every compute unit a workgroup
+            if (ceil_div(m, 128) * K >= 256)
+                rc = project_p_launch<NS, 2, 4, 1, 1, 4>(delta, frags, out, m, n, r, K, st);
+            else
+                rc = project_p_launch<NS, 2, 4, 1, 1, 2>(delta, frags, out, m, n, r, K, st);
+            break;
     }
+    if (rc != DLCX_OK) return rc;
     return check_launch("project_p_mfma");
 }
 

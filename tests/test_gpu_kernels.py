@@ -117,6 +117,7 @@ SHAPES = [  # (m, n, r, K, group): several tiles and ragged tails in both dimens
     (1024, 768, 64, 4, 128),
     (640, 2048, 96, 2, 128),
     (2048, 512, 256, 1, 64),
+    (4096, 320, 200, 8, 64),     # enough workgroups for the 128-row form of the P kernel
 ]
 
 
