@@ -321,7 +321,13 @@ __device__ __forceinline__ void vec_to_array<4>(const float4 &v, float (&out)[4]
     out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
 }
 
-template <int NS, int CB, int JB, int DEPTH>
+// RANKSPLIT: the 4 wavefronts take a quarter of the basis blocks each, over all the rows of the
+// workgroup, instead of a quarter of the rows with all basis blocks.  A wavefront then needs only
+// its own P_hat fragments (a quarter of them) per 16 rows of delta, which it shares with the
+// other three through L1; at r = 256 that is the difference between 8 bytes of fragments per
+// byte of delta and 1/2, and it leaves room for 16-byte loads of delta.  No sums cross
+// wavefronts in this form.
+template <int NS, int CBALL, int JB, int DEPTH, bool RANKSPLIT>
 __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float *> deltas,
                                                             const uint4 *__restrict__ afrags,
                                                             PtrPack<float *> outs, int64_t m,
@@ -329,14 +335,20 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
                                                             int64_t ksteps_per_wave,
                                                             int64_t slab_stride) {
     typedef typename VecOf<JB>::type vec_t;
-    __shared__ float red[CB * JB * 16 * 64];
+    constexpr int CB = RANKSPLIT ? CBALL / 4 : CBALL;  // basis blocks of one wavefront
+    static_assert(!RANKSPLIT || CBALL % 4 == 0, "a quarter of the basis blocks per wavefront");
+    __shared__ float red[RANKSPLIT ? 1 : CB * JB * 16 * 64];
     const float *__restrict__ delta = deltas.p[blockIdx.y];
     float *__restrict__ out = outs.p[blockIdx.y] + (int64_t)blockIdx.z * slab_stride;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int cb0 = RANKSPLIT ? wave * CB : 0;  // first basis block of this wavefront
     const int64_t jcol = (int64_t)blockIdx.x * (32 * JB) + JB * (lane & 31);
     const bool col_ok = jcol < n;  // n is a multiple of 16: the JB columns are in or out together
-    const int64_t s_begin = ((int64_t)blockIdx.z * 4 + wave) * ksteps_per_wave;
-    const int64_t s_end = s_begin + ksteps_per_wave;  // a multiple of DEPTH k-steps
+    const int64_t s_begin =
+        RANKSPLIT ? (int64_t)blockIdx.z * 4 * ksteps_per_wave
+                  : ((int64_t)blockIdx.z * 4 + wave) * ksteps_per_wave;
+    // a multiple of DEPTH k-steps
+    const int64_t s_end = s_begin + (RANKSPLIT ? 4 : 1) * ksteps_per_wave;
 
     f32x16_t acc[CB][JB];
 #pragma unroll
@@ -368,7 +380,7 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                 for (int h = 0; h < NS; ++h)
-                    a[cb][h] = afrags[(((s + d) * CB + cb) * NS + h) * 64 + lane];
+                    a[cb][h] = afrags[(((s + d) * CBALL + cb0 + cb) * NS + h) * 64 + lane];
             uint4 b[JB][NS];
 #pragma unroll
             for (int q = 0; q < JB; ++q) {
@@ -385,7 +397,7 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
         }
     }
     // wavefronts 3, 2, 1 hand their sums to wavefront 0, in that order
-    for (int w = 3; w >= 1; --w) {
+    for (int w = 3; !RANKSPLIT && w >= 1; --w) {
         if (wave == w) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
@@ -407,12 +419,12 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
         }
         __syncthreads();
     }
-    if (wave != 0 || !col_ok) return;
+    if ((!RANKSPLIT && wave != 0) || !col_ok) return;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int c = cb * 32 + d_row(v, lane);
+            const int c = (cb0 + cb) * 32 + d_row(v, lane);
             if (c < r) {
 #pragma unroll
                 for (int q = 0; q < JB; ++q) out[(int64_t)c * n + jcol + q] = acc[cb][q][v];
@@ -816,8 +828,10 @@ struct QPlan {
 static QPlan q_plan(int64_t m, int64_t n, int r, int K) {
     QPlan p;
     const int cb = cb_of(r);
-    p.JB = cb <= 2 ? 4 : cb == 4 ? 2 : 1;  // accumulators: CB * JB * 16 registers
-    p.depth = cb <= 2 ? 2 : 4;             // k-steps (16 rows) of delta in flight per wavefront
+    // accumulators: (basis blocks of a wavefront) * JB * 16 registers; with 8 basis blocks a
+    // wavefront takes a quarter of them (RANKSPLIT) and JB is 4 again
+    p.JB = cb == 4 ? 2 : 4;
+    p.depth = cb == 4 ? 4 : 2;             // k-steps (16 rows) of delta in flight per wavefront
     const int64_t col_wgs = ceil_div(n, 32 * p.JB) * K;
     int64_t S = ceil_div(512, col_wgs);
     const int64_t smax = ceil_div(m, 64 * p.depth * 2);  // at least 2 pipeline rounds per wave
@@ -921,10 +935,10 @@ static int project_q_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
     {
     Timed timed(KID_PROJECT_Q, st);
     switch (cb) {
-        case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        case 2: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 2, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        case 4: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 4, 2, 4>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        default: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 8, 1, 4>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 4, 2, false>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 2: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 2, 4, 2, false>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 4: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 4, 2, 4, false>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        default: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 8, 4, 2, true>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
     }
     rc = check_launch("project_q_mfma");
     }
