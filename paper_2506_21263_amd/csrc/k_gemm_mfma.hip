@@ -321,13 +321,8 @@ __device__ __forceinline__ void vec_to_array<4>(const float4 &v, float (&out)[4]
     out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
 }
 
-// RANKSPLIT: the 4 wavefronts take a quarter of the basis blocks each, over all the rows of the
-// workgroup, instead of a quarter of the rows with all basis blocks.  A wavefront then needs only
-// its own P_hat fragments (a quarter of them) per 16 rows of delta, which it shares with the
-// other three through L1; at r = 256 that is the difference between 8 bytes of fragments per
-// byte of delta and 1/2, and it leaves room for 16-byte loads of delta.  No sums cross
-// wavefronts in this form.
-template <int NS, int CBALL, int JB, int DEPTH, bool RANKSPLIT>
+// Used up to 2 basis blocks (r <= 64); above that project_q_lds_kernel below.
+template <int NS, int CB, int JB, int DEPTH>
 __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float *> deltas,
                                                             const uint4 *__restrict__ afrags,
                                                             PtrPack<float *> outs, int64_t m,
@@ -335,20 +330,14 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
                                                             int64_t ksteps_per_wave,
                                                             int64_t slab_stride) {
     typedef typename VecOf<JB>::type vec_t;
-    constexpr int CB = RANKSPLIT ? CBALL / 4 : CBALL;  // basis blocks of one wavefront
-    static_assert(!RANKSPLIT || CBALL % 4 == 0, "a quarter of the basis blocks per wavefront");
-    __shared__ float red[RANKSPLIT ? 1 : CB * JB * 16 * 64];
+    __shared__ float red[CB * JB * 16 * 64];
     const float *__restrict__ delta = deltas.p[blockIdx.y];
     float *__restrict__ out = outs.p[blockIdx.y] + (int64_t)blockIdx.z * slab_stride;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int cb0 = RANKSPLIT ? wave * CB : 0;  // first basis block of this wavefront
     const int64_t jcol = (int64_t)blockIdx.x * (32 * JB) + JB * (lane & 31);
     const bool col_ok = jcol < n;  // n is a multiple of 16: the JB columns are in or out together
-    const int64_t s_begin =
-        RANKSPLIT ? (int64_t)blockIdx.z * 4 * ksteps_per_wave
-                  : ((int64_t)blockIdx.z * 4 + wave) * ksteps_per_wave;
-    // a multiple of DEPTH k-steps
-    const int64_t s_end = s_begin + (RANKSPLIT ? 4 : 1) * ksteps_per_wave;
+    const int64_t s_begin = ((int64_t)blockIdx.z * 4 + wave) * ksteps_per_wave;
+    const int64_t s_end = s_begin + ksteps_per_wave;  // a multiple of DEPTH k-steps
 
     f32x16_t acc[CB][JB];
 #pragma unroll
@@ -380,7 +369,7 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                 for (int h = 0; h < NS; ++h)
-                    a[cb][h] = afrags[(((s + d) * CBALL + cb0 + cb) * NS + h) * 64 + lane];
+                    a[cb][h] = afrags[(((s + d) * CB + cb) * NS + h) * 64 + lane];
             uint4 b[JB][NS];
 #pragma unroll
             for (int q = 0; q < JB; ++q) {
@@ -397,7 +386,7 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
         }
     }
     // wavefronts 3, 2, 1 hand their sums to wavefront 0, in that order
-    for (int w = 3; !RANKSPLIT && w >= 1; --w) {
+    for (int w = 3; w >= 1; --w) {
         if (wave == w) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
@@ -419,17 +408,115 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
         }
         __syncthreads();
     }
-    if ((!RANKSPLIT && wave != 0) || !col_ok) return;
+    if (wave != 0 || !col_ok) return;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int c = (cb0 + cb) * 32 + d_row(v, lane);
+            const int c = cb * 32 + d_row(v, lane);
             if (c < r) {
 #pragma unroll
                 for (int q = 0; q < JB; ++q) out[(int64_t)c * n + jcol + q] = acc[cb][q][v];
             }
         }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Q phase for 4 or 8 basis blocks (64 < r <= 256), where the matrix cores and the path of the
+// operands to them, not HBM, set the pace.  A workgroup owns 128 columns and sweeps its range of
+// rows in stages of 32 (2 k-steps).  A stage of delta is read once, as 512-byte row segments, and
+// laid down in LDS as fp32; every wavefront then picks the reduction-major operand of each of the
+// four 32-column blocks out of it (8 rows of one column per lane), splits it into bf16 pieces
+// and multiplies it with the CBW basis blocks it owns (a quarter of them), whose fragments only
+// this wavefront fetches.  Stages are double-buffered behind one LDS-only barrier each; nothing
+// is added across wavefronts.
+// ---------------------------------------------------------------------------------------------
+constexpr int kQPitch = 128 + 4;  // floats per LDS row of a stage
+
+template <int NS, int CBW>
+__global__ __launch_bounds__(kW) void project_q_lds_kernel(PtrPack<const float *> deltas,
+                                                           const uint4 *__restrict__ afrags,
+                                                           PtrPack<float *> outs, int64_t m,
+                                                           int64_t n, int r, int64_t ksteps_per_wg,
+                                                           int64_t slab_stride) {
+    constexpr int CB = 4 * CBW;
+    __shared__ __attribute__((aligned(16))) float stage[2][32 * kQPitch];
+    const float *__restrict__ delta = deltas.p[blockIdx.y];
+    float *__restrict__ out = outs.p[blockIdx.y] + (int64_t)blockIdx.z * slab_stride;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t j0 = (int64_t)blockIdx.x * 128;
+    const int64_t s_begin = (int64_t)blockIdx.z * ksteps_per_wg;  // even
+    const int64_t nstages = ksteps_per_wg >> 1;
+
+    f32x16_t acc[CBW][4];
+#pragma unroll
+    for (int a = 0; a < CBW; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    // this thread's four float4 of a stage: rows (tid >> 5) + 8 u, columns 4 (tid & 31) .. + 3
+    float4 pre[4];
+    const int prow = tid >> 5, pc4 = tid & 31;
+    const bool col_ok = j0 + pc4 * 4 < n;
+    auto load_stage = [&](int64_t t) {
+        const int64_t i0 = (s_begin + 2 * t) * 16;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = i0 + prow + 8 * u;
+            pre[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < m && col_ok)
+                pre[u] = *reinterpret_cast<const float4 *>(delta + i * n + j0 + pc4 * 4);
+        }
+    };
+    if (nstages > 0) load_stage(0);
+    for (int64_t t = 0; t < nstages; ++t) {
+        float *buf = stage[t & 1];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            *reinterpret_cast<float4 *>(&buf[(prow + 8 * u) * kQPitch + pc4 * 4]) = pre[u];
+        // this wavefront's basis fragments of the stage, requested before the next stage of
+        // delta so that waiting for them does not wait for that stage as well
+        uint4 a[2][CBW][NS];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                for (int h = 0; h < NS; ++h)
+                    a[ks][cb][h] = afrags[(((s_begin + 2 * t + ks) * CB + wave * CBW + cb) * NS + h) *
+                                              64 + lane];
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < nstages) load_stage(t + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_barrier();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float x[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    x[e] = buf[(ks * 16 + (lane >> 5) * 8 + e) * kQPitch + q * 32 + (lane & 31)];
+                uint4 b[NS];
+                split8<NS>(x, b);
+#pragma unroll
+                for (int cb = 0; cb < CBW; ++cb) mfma_split<NS>(a[ks][cb], b, acc[cb][q]);
+            }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int64_t j = j0 + q * 32 + (lane & 31);
+        if (j >= n) continue;
+#pragma unroll
+        for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int c = (wave * CBW + cb) * 32 + d_row(v, lane);
+                if (c < r) out[(int64_t)c * n + j] = acc[cb][q][v];
+            }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -828,10 +915,9 @@ struct QPlan {
 static QPlan q_plan(int64_t m, int64_t n, int r, int K) {
     QPlan p;
     const int cb = cb_of(r);
-    // accumulators: (basis blocks of a wavefront) * JB * 16 registers; with 8 basis blocks a
-    // wavefront takes a quarter of them (RANKSPLIT) and JB is 4 again
-    p.JB = cb == 4 ? 2 : 4;
-    p.depth = cb == 4 ? 4 : 2;             // k-steps (16 rows) of delta in flight per wavefront
+    // 128 columns per workgroup in both Q kernels
+    p.JB = 4;
+    p.depth = 2;                           // k-steps (16 rows) of delta in flight per wavefront
     const int64_t col_wgs = ceil_div(n, 32 * p.JB) * K;
     int64_t S = ceil_div(512, col_wgs);
     const int64_t smax = ceil_div(m, 64 * p.depth * 2);  // at least 2 pipeline rounds per wave
@@ -935,10 +1021,10 @@ static int project_q_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
     {
     Timed timed(KID_PROJECT_Q, st);
     switch (cb) {
-        case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 4, 2, false>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        case 2: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 2, 4, 2, false>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        case 4: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 4, 2, 4, false>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        default: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 8, 4, 2, true>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 2: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 2, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
+        case 4: hipLaunchKernelGGL((project_q_lds_kernel<NS, 1>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
+        default: hipLaunchKernelGGL((project_q_lds_kernel<NS, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
     }
     rc = check_launch("project_q_mfma");
     }
