@@ -86,6 +86,23 @@ __device__ __forceinline__ int d_row(int v, int lane) {
     return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
 }
 
+// Accesses to the big streams (delta, theta_l, theta, v), each touched once per sweep: marked
+// non-temporal so that they do not displace the fragments and one another in the caches.
+typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t nt_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float4 stream_load4(const float *p) {
+    const nt_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4 *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 stream_load2(const void *p) {
+    const nt_u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x2 *>(p));
+    return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ void stream_store4(float *p, const float4 &a) {
+    const nt_f32x4 v = {a.x, a.y, a.z, a.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<nt_f32x4 *>(p));
+}
+
 // ---------------------------------------------------------------------------------------------
 // Fragment packing.
 // ---------------------------------------------------------------------------------------------
@@ -705,21 +722,19 @@ __global__ __launch_bounds__(kW) void round_mfma_kernel(
             if (TLBF16) lraw[p] = *reinterpret_cast<const traw_t *>(&x[p]);
             else lraw[p] = *reinterpret_cast<const traw_t *>(&x[p]);
             if (okp) {
-                x[p] = *reinterpret_cast<const float4 *>(ep.ef.p[k] + off);
-                if (TLBF16)
-                    lraw[p] = *reinterpret_cast<const traw_t *>(
-                        reinterpret_cast<const uint16_t *>(ep.tl.p[k]) + off);
+                x[p] = stream_load4(ep.ef.p[k] + off);
+                if constexpr (TLBF16)
+                    lraw[p] = stream_load2(reinterpret_cast<const uint16_t *>(ep.tl.p[k]) + off);
                 else
-                    lraw[p] = *reinterpret_cast<const traw_t *>(
-                        reinterpret_cast<const float *>(ep.tl.p[k]) + off);
+                    lraw[p] = stream_load4(reinterpret_cast<const float *>(ep.tl.p[k]) + off);
             }
             if (with_theta) {
                 tv[p] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (okp) tv[p] = *reinterpret_cast<const float4 *>(ep.theta + off);
+                if (okp) tv[p] = stream_load4(ep.theta + off);
             }
             if (with_vel) {
                 vv[p] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (okp) vv[p] = *reinterpret_cast<const float4 *>(ep.vel + off);
+                if (okp) vv[p] = stream_load4(ep.vel + off);
             }
         }
     };
@@ -804,7 +819,7 @@ __global__ __launch_bounds__(kW) void round_mfma_kernel(
                     g.z = (tv[p].z - l.z) + (x[p].z - dv[p].z);
                     g.w = (tv[p].w - l.w) + (x[p].w - dv[p].w);
                     if (okp) {
-                        *reinterpret_cast<float4 *>(e + off) = g;
+                        stream_store4(e + off, g);
                     } else {
                         g = make_float4(0.f, 0.f, 0.f, 0.f);
                     }
@@ -823,8 +838,8 @@ __global__ __launch_bounds__(kW) void round_mfma_kernel(
                         tn.y = fmaf(-ep.lr, fmaf(ep.mu, vn.y, dv[p].y), tv[p].y);
                         tn.z = fmaf(-ep.lr, fmaf(ep.mu, vn.z, dv[p].z), tv[p].z);
                         tn.w = fmaf(-ep.lr, fmaf(ep.mu, vn.w, dv[p].w), tv[p].w);
-                        *reinterpret_cast<float4 *>(ep.vel + off) = vn;
-                        *reinterpret_cast<float4 *>(ep.theta + off) = tn;
+                        stream_store4(ep.vel + off, vn);
+                        stream_store4(ep.theta + off, tn);
                     }
                 }
                 // operands of the next item, in flight while this one is multiplied

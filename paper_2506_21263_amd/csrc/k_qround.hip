@@ -23,6 +23,18 @@ namespace dlcx {
 
 constexpr int kQrThreads = 256;
 
+// 16-byte accesses of data that is touched once per outer step: marked non-temporal so that they
+// do not displace one another in the caches
+typedef float qr_f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load4(const float *p) {
+    const qr_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const qr_f32x4 *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stream_store4(float *p, const float4 &a) {
+    const qr_f32x4 v = {a.x, a.y, a.z, a.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<qr_f32x4 *>(p));
+}
+
 template <int kLanes>
 __device__ __forceinline__ float qr_group_max(float a) {
 #pragma unroll
@@ -136,13 +148,13 @@ __global__ __launch_bounds__(kQrThreads) void quant_round_kernel(QRoundArgs a) {
     }
     float4 t = make_float4(0.f, 0.f, 0.f, 0.f), vel = t;
     if (live) {
-        t = reinterpret_cast<const float4 *>(a.theta)[vc];
-        if (a.has_prev) vel = reinterpret_cast<const float4 *>(a.vel)[vc];
+        t = stream_load4(a.theta + 4 * vc);
+        if (a.has_prev) vel = stream_load4(a.vel + 4 * vc);
     }
     for (int k = 0; k < a.K; ++k) {
         float4 x = make_float4(0.f, 0.f, 0.f, 0.f), l = x;
         if (live) {
-            x = reinterpret_cast<const float4 *>(a.ef.p[k])[vc];
+            x = stream_load4(a.ef.p[k] + 4 * vc);
             if (kBf16) {
                 const uint2 b = reinterpret_cast<const uint2 *>(a.tl.p[k])[vc];
                 l = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
@@ -167,7 +179,7 @@ __global__ __launch_bounds__(kQrThreads) void quant_round_kernel(QRoundArgs a) {
         float s;
         quantize4<kQbits, kLanes>(dl, c, s);
         if (live) {
-            reinterpret_cast<float4 *>(a.ef.p[k])[vc] = dl;
+            stream_store4(a.ef.p[k] + 4 * vc, dl);
             store_codes4<kQbits>(a.codes.p[k], vc, c);
             if ((threadIdx.x & (kLanes - 1)) == 0) a.scales.p[k][g] = s;
         }
@@ -184,8 +196,8 @@ __global__ __launch_bounds__(kQrThreads) void quant_round_kernel(QRoundArgs a) {
             vn[q] = (float)vd;
             tn[q] = (float)td;
         }
-        reinterpret_cast<float4 *>(a.vel)[vc] = make_float4(vn[0], vn[1], vn[2], vn[3]);
-        reinterpret_cast<float4 *>(a.theta)[vc] = make_float4(tn[0], tn[1], tn[2], tn[3]);
+        stream_store4(a.vel + 4 * vc, make_float4(vn[0], vn[1], vn[2], vn[3]));
+        stream_store4(a.theta + 4 * vc, make_float4(tn[0], tn[1], tn[2], tn[3]));
     }
 }
 
