@@ -13,6 +13,23 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
     return __uint_as_float(bits16 << 16);
 }
 
+// Every stream here is touched once per sweep: non-temporal accesses, so that the streams do not
+// displace one another in the caches.
+typedef float st_f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t st_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float4 stream_load4(const float *base, int64_t v) {
+    const st_f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const st_f32x4 *>(base) + v);
+    return make_float4(x.x, x.y, x.z, x.w);
+}
+__device__ __forceinline__ uint2 stream_load2(const void *base, int64_t v) {
+    const st_u32x2 x = __builtin_nontemporal_load(reinterpret_cast<const st_u32x2 *>(base) + v);
+    return make_uint2(x.x, x.y);
+}
+__device__ __forceinline__ void stream_store4(float *base, int64_t v, const float4 &a) {
+    const st_f32x4 x = {a.x, a.y, a.z, a.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<st_f32x4 *>(base) + v);
+}
+
 template <bool kBf16>
 __global__ __launch_bounds__(kThreads) void delta_ef_kernel(const float *__restrict__ theta_g,
                                                             const void *__restrict__ theta_l,
@@ -25,14 +42,14 @@ __global__ __launch_bounds__(kThreads) void delta_ef_kernel(const float *__restr
     for (int u = 0; u < kUnroll; ++u) {
         const int64_t v = base + (int64_t)u * kThreads;
         if (v < nvec) {
-            g[u] = reinterpret_cast<const float4 *>(theta_g)[v];
-            e[u] = reinterpret_cast<const float4 *>(ef)[v];
+            g[u] = stream_load4(theta_g, v);
+            e[u] = stream_load4(ef, v);
             if (kBf16) {
-                const uint2 b = reinterpret_cast<const uint2 *>(theta_l)[v];
+                const uint2 b = stream_load2(theta_l, v);
                 l[u] = make_float4(bf16_bits_to_f32(b.x & 0xFFFFu), bf16_bits_to_f32(b.x >> 16),
                                    bf16_bits_to_f32(b.y & 0xFFFFu), bf16_bits_to_f32(b.y >> 16));
             } else {
-                l[u] = reinterpret_cast<const float4 *>(theta_l)[v];
+                l[u] = stream_load4(reinterpret_cast<const float *>(theta_l), v);
             }
         }
     }
@@ -45,7 +62,7 @@ __global__ __launch_bounds__(kThreads) void delta_ef_kernel(const float *__restr
             d.y = (float)(((double)g[u].y - (double)l[u].y) + (double)e[u].y);
             d.z = (float)(((double)g[u].z - (double)l[u].z) + (double)e[u].z);
             d.w = (float)(((double)g[u].w - (double)l[u].w) + (double)e[u].w);
-            reinterpret_cast<float4 *>(ef)[v] = d;
+            stream_store4(ef, v, d);
         }
     }
     // ragged tail (numel not a multiple of 4): the last block's first threads
@@ -73,9 +90,9 @@ __global__ __launch_bounds__(kThreads) void nesterov_kernel(float *__restrict__ 
     for (int u = 0; u < kUnroll; ++u) {
         const int64_t i = base + (int64_t)u * kThreads;
         if (i < nvec) {
-            t[u] = reinterpret_cast<const float4 *>(theta)[i];
-            v[u] = reinterpret_cast<const float4 *>(vel)[i];
-            g[u] = reinterpret_cast<const float4 *>(grad)[i];
+            t[u] = stream_load4(theta, i);
+            v[u] = stream_load4(vel, i);
+            g[u] = stream_load4(grad, i);
         }
     }
 #pragma unroll
@@ -91,8 +108,8 @@ __global__ __launch_bounds__(kThreads) void nesterov_kernel(float *__restrict__ 
             tn.y = fmaf(-lr, fmaf(mu, vn.y, g[u].y), t[u].y);
             tn.z = fmaf(-lr, fmaf(mu, vn.z, g[u].z), t[u].z);
             tn.w = fmaf(-lr, fmaf(mu, vn.w, g[u].w), t[u].w);
-            reinterpret_cast<float4 *>(vel)[i] = vn;
-            reinterpret_cast<float4 *>(theta)[i] = tn;
+            stream_store4(vel, i, vn);
+            stream_store4(theta, i, tn);
         }
     }
     if (blockIdx.x == gridDim.x - 1) {
