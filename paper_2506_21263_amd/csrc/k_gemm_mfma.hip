@@ -222,7 +222,7 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
             const int64_t j = t * 64 + c4 * 4;
             pre[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (i0 + row < m && j < n)
-                pre[u] = *reinterpret_cast<const float4 *>(delta + (i0 + row) * n + j);
+                pre[u] = stream_load4(delta + (i0 + row) * n + j);
         }
     };
     load_stage(0);
@@ -339,6 +339,23 @@ __device__ __forceinline__ void vec_to_array<4>(const float4 &v, float (&out)[4]
 }
 
 // Used up to 2 basis blocks (r <= 64); above that project_q_lds_kernel below.
+template <int JB>
+__device__ __forceinline__ typename VecOf<JB>::type stream_load_vec(const float *p);
+template <>
+__device__ __forceinline__ float stream_load_vec<1>(const float *p) {
+    return __builtin_nontemporal_load(p);
+}
+template <>
+__device__ __forceinline__ float2 stream_load_vec<2>(const float *p) {
+    typedef float nt_f32x2 __attribute__((ext_vector_type(2)));
+    const nt_f32x2 v = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x2 *>(p));
+    return make_float2(v.x, v.y);
+}
+template <>
+__device__ __forceinline__ float4 stream_load_vec<4>(const float *p) {
+    return stream_load4(p);
+}
+
 template <int NS, int CB, int JB, int DEPTH>
 __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float *> deltas,
                                                             const uint4 *__restrict__ afrags,
@@ -372,8 +389,7 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
 #pragma unroll
             for (int q = 0; q < JB; ++q) breg[d][e][q] = 0.f;
             if (ibase + e < m && col_ok)
-                vec_to_array<JB>(*reinterpret_cast<const vec_t *>(delta + (ibase + e) * n + jcol),
-                                 breg[d][e]);
+                vec_to_array<JB>(stream_load_vec<JB>(delta + (ibase + e) * n + jcol), breg[d][e]);
         }
     };
 #pragma unroll
@@ -484,7 +500,7 @@ __global__ __launch_bounds__(kW) void project_q_lds_kernel(PtrPack<const float *
             const int64_t i = i0 + prow + 8 * u;
             pre[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (i < m && col_ok)
-                pre[u] = *reinterpret_cast<const float4 *>(delta + i * n + j0 + pc4 * 4);
+                pre[u] = stream_load4(delta + i * n + j0 + pc4 * 4);
         }
     };
     if (nstages > 0) load_stage(0);
