@@ -233,6 +233,32 @@ def quant_only(args):
     print(json.dumps(out), flush=True)
 
 
+def mfma_peak(args):
+    """Attainable bf16 matrix-core rate of this GPU (32x32x16 MFMAs, nothing competing)."""
+    import torch
+
+    import paper_2506_21263_amd as dlcx
+
+    dlcx.lib()
+    torch.cuda.set_device(0)
+    wgs, iters = 256 * 8, 20000
+    out = torch.empty(wgs * 256, device="cuda:0")
+    dlcx.dlcx_mfma_peak_probe(wgs, 100, out)
+    torch.cuda.synchronize()
+    dlcx.dlcx_profile_enable(True)
+    for _ in range(3):
+        dlcx.dlcx_mfma_peak_probe(wgs, iters, out)
+    torch.cuda.synchronize()
+    ms, cnt = dlcx.dlcx_profile_read()["mfma_peak"]
+    dlcx.dlcx_profile_enable(False)
+    flop = wgs * 4 * iters * 8 * 32768.0
+    rate = flop / (ms / cnt * 1e-3) / 1e12
+    print(json.dumps({"metric": "attainable bf16 MFMA rate (v_mfma_f32_32x32x16_bf16)",
+                      "value": rate, "unit": "TFLOP/s", "datasheet_peak": 2500.0,
+                      "frac_of_datasheet": rate / 2500.0, "ms_per_launch": ms / cnt,
+                      "workgroups": wgs, "mfma_per_wavefront": iters * 8}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -253,6 +279,8 @@ def main():
                     help="quantiser as the whole compressor (no low-rank step), all tensors flat")
     ap.add_argument("--requant", action="store_true",
                     help="quantise-only mode: re-encode the average to q bits")
+    ap.add_argument("--mfma-peak", action="store_true",
+                    help="measure the attainable bf16 matrix-core rate and exit")
     ap.add_argument("--probe", action="store_true",
                     help="counter run: plain random inputs, one 1 GiB copy, two steps, no timing")
     args = ap.parse_args()
@@ -261,6 +289,8 @@ def main():
               "(no collectives, no second GPU in this run)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
+    if args.mfma_peak:
+        return mfma_peak(args)
     if args.quant_only:
         return quant_only(args)
 

@@ -24,7 +24,8 @@ inline int check_launch(const char *where) { return note_hip(hipGetLastError(), 
 enum KernelId {
     KID_DELTA_EF = 0, KID_NESTEROV, KID_QUANTIZE, KID_DEQUANT_AVG, KID_PACK, KID_PROJECT_P,
     KID_PROJECT_Q, KID_SUM_SLABS, KID_RECONSTRUCT, KID_GRAM, KID_CHOL, KID_APPLY_W, KID_JACOBI,
-    KID_ROUND, KID_QUANT_ROUND, KID_REQUANT, KID_EF_UPDATE, KID_COUNT
+    KID_ROUND, KID_QUANT_ROUND, KID_REQUANT, KID_EF_UPDATE,
+    KID_MFMA_PEAK, KID_COUNT
 };
 struct Timed {
     Timed(int kid, hipStream_t st);
@@ -64,6 +65,9 @@ int launch_quant_round(int64_t numel, int qbits, int group, int K, const PtrPack
 int launch_requantize(float *x, int64_t count, int qbits, int group, hipStream_t st);
 int launch_ef_update(int K, const PtrPack<float *> &ef, const float *d, int64_t numel,
                      hipStream_t st);
+
+// ---- measurement aid (k_peak.hip) -------------------------------------------------------
+int launch_mfma_peak(int workgroups, int iters, float *out, hipStream_t st);
 
 // ---- rank-r products ------------------------------------------------------------------
 // P_k = delta_k * Q_in   (delta m x n, q_in r x n, out r x m)

@@ -131,7 +131,8 @@ const char *dlcx_last_hip_error(void) { return g_last_error.c_str(); }
 static const char *const kKernelNames[KID_COUNT] = {
     "delta_ef", "outer_nesterov", "quantize", "dequant_average", "pack_fragments", "project_p",
     "project_q", "sum_slabs", "reconstruct", "gram_partials", "chol_inverse", "apply_w",
-    "jacobi_rank", "round_fused", "quant_round", "requantize", "ef_update"};
+    "jacobi_rank", "round_fused", "quant_round", "requantize", "ef_update",
+    "mfma_peak"};
 
 int dlcx_profile_enable(int on) {
     for (auto &r : g_prof) {
@@ -275,6 +276,12 @@ int dlcx_quant_round(int64_t numel, int qbits, int group, int K,
     }
     return launch_quant_round(numel, qbits, group, K, tl, theta_l_dtype, ef, theta_g, v, lr, mu,
                               has_prev, pc, ps, requant != 0, cs, ss, as_stream(stream));
+}
+
+int dlcx_mfma_peak_probe(int workgroups, int iters, float *out, void *stream) {
+    if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24)) return DLCX_EINVAL;
+    if (!out || !aligned16(out)) return DLCX_EINVAL;
+    return launch_mfma_peak(workgroups, iters, out, as_stream(stream));
 }
 
 int dlcx_ef_update(int K, float *const *ef_inout_host, const float *delta_hat, int64_t numel,
