@@ -91,6 +91,7 @@ def cpu_baseline(stage, locals_, cfg_id):
     """The oracle, as it stands, on one matrix of the workload: two outer steps of the smallest
     matrix shape of the stage (K workers), single thread."""
     import numpy as np
+    import torch
 
     import synth
     from oracle import pipeline
@@ -104,7 +105,7 @@ def cpu_baseline(stage, locals_, cfg_id):
     tl = []
     for x in locals_[a]:
         if x.dtype.is_floating_point and x.element_size() == 2:
-            tl.append(x.view(__import__("torch").int16).cpu().numpy().view(np.uint16))
+            tl.append(x.view(torch.int16).cpu().numpy().view(np.uint16))
         else:
             tl.append(x.cpu().numpy())
     orc = pipeline.MatrixOracle(theta, M.K, q_in, cfg["qbits"], cfg["group"], synth.LR, synth.MU)

@@ -1136,7 +1136,7 @@ int launch_reconstruct_mfma(int mma, int64_t m, int64_t n, int r, const float *p
 }
 
 // ---- fused round: workspace layout and launch ------------------------------------------------
-static int kRoundWgTarget = 512;  // workgroups wanted per launch (column ranges per row block)
+constexpr int kRoundWgTarget = 512;  // workgroups wanted per launch (column ranges per row block)
 constexpr int kComputeUnits = 256;
 struct RoundPlan {
     int chunks;        // column ranges per row block = slabs per worker

@@ -167,3 +167,28 @@ def torch_matrix_inputs(m, n, K, r, seed, sigma, alpha, theta_l, device, kmax=51
         replicas.append(tl.to(torch.bfloat16) if theta_l == "bf16" else tl)
         del G
     return dict(theta_g=theta_g, theta_l=replicas, q_in=q_in)
+
+
+def hadamard(k):
+    """Sylvester matrix of order 2^k: entries +-1, mutually orthogonal columns."""
+    H = np.ones((1, 1))
+    for _ in range(k):
+        H = np.block([[H, H], [H, -H]])
+    return H
+
+
+def exact_lowrank_case(qmax, K):
+    """delta = sum_c s_c h_c g_c^T with +-1 vectors h_c (length 16), g_c (length 64) and
+    s_c = qmax * 2^-c: every factor entry the compressor meets is +-qmax times a power of two, so
+    both quantisations, the mean, the orthonormalisation (column norms are powers of two times
+    qmax) and all three products are exact.  Closed form: Delta == delta, bit for bit."""
+    m, n, r = 16, 64, 4
+    Hm, Hn = hadamard(4), hadamard(6)
+    h, g = Hm[:, [1, 2, 5, 9]], Hn[:, [3, 7, 20, 41]]
+    s = qmax * 2.0 ** -np.arange(r)
+    delta = (h * s) @ g.T
+    assert np.array_equal(delta, delta.astype(np.float32))
+    theta0 = np.zeros((m, n), np.float32)
+    tl = [(-delta).astype(np.float32) for _ in range(K)]     # theta_l = theta - delta
+    q_in = np.ascontiguousarray(g.T, np.float32)             # r x n: the basis is V itself
+    return m, n, r, theta0, tl, q_in, delta.astype(np.float32)

@@ -443,9 +443,8 @@ def test_exactly_representable_input_passes_the_compressor_unchanged(mma, fused,
     # two, so the codes are all +-qmax, Delta equals the pseudo-gradient and the second outer
     # step is the Nesterov step of exactly that gradient.  Holds in every product mode: the
     # operands have few enough bits for the bf16 splits to be exact.
-    from test_oracle_pins import exact_lowrank_case
     qmax = 2 ** (qbits - 1) - 1
-    m, n, r, theta0, tl, q_in, delta = exact_lowrank_case(qmax, K)
+    m, n, r, theta0, tl, q_in, delta = synth.exact_lowrank_case(qmax, K)
     M = MatrixState(to_dev(theta0), K, to_dev(q_in), qbits, 16, mma)
     st = Stage([M], 0.5, 0.0, fused=fused, warm_start=True)
     st.step([[to_dev(x) for x in tl]])

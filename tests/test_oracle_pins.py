@@ -583,31 +583,6 @@ def test_overlap_plan_is_the_largest_rank_that_hides():
 
 
 # --------------------------------------------------------------------------- exact pipeline
-def hadamard(k):
-    """Sylvester matrix of order 2^k: entries +-1, mutually orthogonal columns."""
-    H = np.ones((1, 1))
-    for _ in range(k):
-        H = np.block([[H, H], [H, -H]])
-    return H
-
-
-def exact_lowrank_case(qmax, K):
-    """delta = sum_c s_c h_c g_c^T with +-1 vectors h_c (length 16), g_c (length 64) and
-    s_c = qmax * 2^-c: every factor entry the compressor meets is +-qmax times a power of two, so
-    both quantisations, the mean, the orthonormalisation (column norms are powers of two times
-    qmax) and all three products are exact.  Closed form: Delta == delta, bit for bit."""
-    m, n, r = 16, 64, 4
-    Hm, Hn = hadamard(4), hadamard(6)
-    h, g = Hm[:, [1, 2, 5, 9]], Hn[:, [3, 7, 20, 41]]
-    s = qmax * 2.0 ** -np.arange(r)
-    delta = (h * s) @ g.T
-    assert np.array_equal(delta, delta.astype(np.float32))
-    theta0 = np.zeros((m, n), np.float32)
-    tl = [(-delta).astype(np.float32) for _ in range(K)]     # theta_l = theta - delta
-    q_in = np.ascontiguousarray(g.T, np.float32)             # r x n: the basis is V itself
-    return m, n, r, theta0, tl, q_in, delta.astype(np.float32)
-
-
 @pytest.mark.parametrize("qbits,K", [(8, 1), (8, 3), (4, 2)])
 def test_quantised_lowrank_pipeline_is_exact_on_representable_input(qbits, K):
     # The decompressed average WITH the quantiser on, against a closed form: on this input the
@@ -615,7 +590,7 @@ def test_quantised_lowrank_pipeline_is_exact_on_representable_input(qbits, K):
     # exact, so Delta equals the pseudo-gradient, the error buffers come out zero and the second
     # outer step moves theta by the Nesterov step of exactly that gradient.
     qmax = 2 ** (qbits - 1) - 1
-    m, n, r, theta0, tl, q_in, delta = exact_lowrank_case(qmax, K)
+    m, n, r, theta0, tl, q_in, delta = synth.exact_lowrank_case(qmax, K)
     orc = pipeline.MatrixOracle(theta0, K, q_in, qbits, 16, lr=0.5, mu=0.0)
     p_hat, q_bar = orc.step(tl)
     assert np.array_equal(orc.trace["delta"][0], delta)
