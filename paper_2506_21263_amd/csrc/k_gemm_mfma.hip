@@ -225,6 +225,23 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
                 pre[u] = stream_load4(delta + (i0 + row) * n + j);
         }
     };
+    // basis fragments of a stage: fetched one stage ahead, so that the matrix cores do not wait
+    // for L2 after every barrier -- except in the 4-block shape, where the second copy of the
+    // fragments costs a wavefront per SIMD and the kernel comes out slower
+    constexpr bool kAhead = !(CBW == 2 && WC == 2);
+    uint4 a[KSW][CBW][NS];
+    auto load_frags = [&](uint4 (&dst)[KSW][CBW][NS], int64_t t) {
+#pragma unroll
+        for (int ks = 0; ks < KSW; ++ks)
+#pragma unroll
+            for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                for (int h = 0; h < NS; ++h) {
+                    const int64_t sg = t * 4 + wk * KSW + ks;
+                    dst[ks][cb][h] = afrags[((sg * CB + wc * CBW + cb) * NS + h) * 64 + lane];
+                }
+    };
+    if (kAhead && nstages > 0) load_frags(a, 0);
     load_stage(0);
     for (int64_t t = 0; t < nstages; ++t) {
         unsigned char *buf = lds + (t & 1) * kBuf;
@@ -240,18 +257,14 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
                 *reinterpret_cast<uint2 *>(buf + (h * kRows + row) * kPPitch + c4 * 8) =
                     make_uint2(lo[h], hi[h]);
         }
-        // the basis fragments of this stage are requested before the next stage of delta, so
-        // that waiting for them does not wait for that stage as well
-        uint4 a[KSW][CBW][NS];
-#pragma unroll
-        for (int ks = 0; ks < KSW; ++ks)
-#pragma unroll
-            for (int cb = 0; cb < CBW; ++cb)
-#pragma unroll
-                for (int h = 0; h < NS; ++h) {
-                    const int64_t sg = t * 4 + wk * KSW + ks;
-                    a[ks][cb][h] = afrags[((sg * CB + wc * CBW + cb) * NS + h) * 64 + lane];
-                }
+        // the next stage's fragments are requested before the next stage of delta, so that
+        // waiting for them later does not wait for that stage as well
+        uint4 an[KSW][CBW][NS];  // unused (and removed by the compiler) unless kAhead
+        if (kAhead) {
+            if (t + 1 < nstages) load_frags(an, t + 1);
+        } else {
+            load_frags(a, t);
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (t + 1 < nstages) load_stage(t + 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -272,6 +285,14 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
             for (int cb = 0; cb < CBW; ++cb)
 #pragma unroll
                 for (int rb = 0; rb < RBW; ++rb) mfma_split<NS>(a[ks][cb], b[rb], acc[cb][rb]);
+        }
+        if (kAhead && t + 1 < nstages) {
+#pragma unroll
+            for (int ks = 0; ks < KSW; ++ks)
+#pragma unroll
+                for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                    for (int h = 0; h < NS; ++h) a[ks][cb][h] = an[ks][cb][h];
         }
     }
     if (WK == 2) {  // add the two halves of the reduction: wk = 1 hands over through LDS
@@ -503,23 +524,37 @@ __global__ __launch_bounds__(kW) void project_q_lds_kernel(PtrPack<const float *
                 pre[u] = stream_load4(delta + i * n + j0 + pc4 * 4);
         }
     };
-    if (nstages > 0) load_stage(0);
-    for (int64_t t = 0; t < nstages; ++t) {
-        float *buf = stage[t & 1];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            *reinterpret_cast<float4 *>(&buf[(prow + 8 * u) * kQPitch + pc4 * 4]) = pre[u];
-        // this wavefront's basis fragments of the stage, requested before the next stage of
-        // delta so that waiting for them does not wait for that stage as well
-        uint4 a[2][CBW][NS];
+    // this wavefront's basis fragments of a stage, requested before the next stage of delta so
+    // that waiting for them does not wait for that stage as well; with one basis block per
+    // wavefront there are registers to fetch them a whole stage ahead (with two, that would
+    // cost the second wavefront per SIMD)
+    constexpr bool kAhead = CBW == 1;
+    uint4 a[2][CBW][NS];
+    auto load_frags = [&](uint4 (&dst)[2][CBW][NS], int64_t t) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int cb = 0; cb < CBW; ++cb)
 #pragma unroll
                 for (int h = 0; h < NS; ++h)
-                    a[ks][cb][h] = afrags[(((s_begin + 2 * t + ks) * CB + wave * CBW + cb) * NS + h) *
-                                              64 + lane];
+                    dst[ks][cb][h] =
+                        afrags[(((s_begin + 2 * t + ks) * CB + wave * CBW + cb) * NS + h) * 64 + lane];
+    };
+    if (nstages > 0) {
+        if (kAhead) load_frags(a, 0);
+        load_stage(0);
+    }
+    for (int64_t t = 0; t < nstages; ++t) {
+        float *buf = stage[t & 1];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            *reinterpret_cast<float4 *>(&buf[(prow + 8 * u) * kQPitch + pc4 * 4]) = pre[u];
+        uint4 an[2][CBW][NS];  // unused (and removed by the compiler) unless kAhead
+        if (kAhead) {
+            if (t + 1 < nstages) load_frags(an, t + 1);
+        } else {
+            load_frags(a, t);
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (t + 1 < nstages) load_stage(t + 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -537,6 +572,14 @@ __global__ __launch_bounds__(kW) void project_q_lds_kernel(PtrPack<const float *
 #pragma unroll
                 for (int cb = 0; cb < CBW; ++cb) mfma_split<NS>(a[ks][cb], b, acc[cb][q]);
             }
+        if (kAhead && t + 1 < nstages) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                    for (int h = 0; h < NS; ++h) a[ks][cb][h] = an[ks][cb][h];
+        }
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
