@@ -30,10 +30,15 @@ def _mean64(factors):
 
 
 class MatrixOracle:
-    def __init__(self, theta_g, K, q_in, qbits, group, lr=0.7, mu=0.9, requant=False):
+    def __init__(self, theta_g, K, q_in, qbits, group, lr=0.7, mu=0.9, requant=False, iters=1):
         """qbits None switches the quantiser off (factors averaged exactly); requant re-encodes
-        each averaged factor to q bits, as a low-bit reduction would hand it on."""
+        each averaged factor to q bits, as a low-bit reduction would hand it on; iters is the
+        number of power iterations the LOWRANK step of Alg. 1 takes per round (1 in the paper;
+        every further one is a P phase from the Q average just formed, then a Q phase, on the
+        same pseudo-gradients -- subspace iteration, two more averages each)."""
+        assert iters >= 1
         self.requant = requant
+        self.iters = iters
         self.m, self.n = theta_g.shape
         self.K = K
         self.theta = np.ascontiguousarray(theta_g, np.float32).copy()
@@ -85,17 +90,23 @@ class MatrixOracle:
             ref.outer_nesterov(self.theta.reshape(-1), self.v.reshape(-1),
                                d_hat_prev.reshape(-1), self.lr, self.mu)
             self.n_applied += 1
-        # ---- Compressor, P phase
-        self.trace["q_in"] = self.q_in.copy()
-        P = [ref.project_p(self.ef[i], self.q_in) for i in range(self.K)]
-        self.trace["P"] = P
-        p_bar = self._avg(P, "P")
-        self.trace["p_bar"] = p_bar
-        self.p_hat = ref.orthonormalize(p_bar)
-        # ---- Compressor, Q phase
-        Q = [ref.project_q(self.ef[i], self.p_hat) for i in range(self.K)]
-        self.trace["Q"] = Q
-        self.q_bar = self._avg(Q, "Q")
+        basis = self.q_in
+        for j in range(self.iters):
+            sfx = "" if j == 0 else "@%d" % j  # trace keys of the iterations after the first
+            # ---- Compressor, P phase
+            self.trace["q_in" + sfx] = basis.copy()
+            P = [ref.project_p(self.ef[i], basis) for i in range(self.K)]
+            self.trace["P" + sfx] = P
+            p_bar = self._avg(P, "P" + sfx)
+            self.trace["p_bar" + sfx] = p_bar
+            self.p_hat = ref.orthonormalize(p_bar)
+            self.trace["p_hat" + sfx] = self.p_hat
+            # ---- Compressor, Q phase
+            Q = [ref.project_q(self.ef[i], self.p_hat) for i in range(self.K)]
+            self.trace["Q" + sfx] = Q
+            self.q_bar = self._avg(Q, "Q" + sfx)
+            self.trace["q_bar" + sfx] = self.q_bar
+            basis = self.q_bar
         return self.p_hat, self.q_bar
 
     def delta_hat(self):

@@ -158,6 +158,40 @@ def test_subspace_iteration_converges_to_truncated_svd():
     assert rel(M_hat, best) < 1e-4
 
 
+def test_power_iterations_within_a_round_are_subspace_iteration():
+    # iters power iterations inside one round act on the round's own pseudo-gradients: with the
+    # quantiser off they are subspace iteration on the mean matrix, so the residual falls
+    # monotonically towards the Eckart-Young bound sqrt(sum_{k>r} sigma_k^2) (numpy's SVD of the
+    # mean), and the decompressed average approaches the best rank-r approximation.
+    m, n, r, K = 72, 56, 4, 3
+    inp = synth.MatrixInputs(m, n, K, r, seed=23, sigma=2e-3, alpha=1.5)
+    theta = inp.theta_g
+    tl = [inp.theta_local(theta, 1, i) for i in range(K)]
+    Mbar = np.mean([theta.astype(np.float64) - x for x in tl], axis=0)
+    u, sv, vt = np.linalg.svd(Mbar)
+    floor = np.sqrt(np.sum(sv[r:] ** 2))
+    best = (u[:, :r] * sv[:r]) @ vt[:r]
+    errs = []
+    for iters in (1, 2, 3, 6, 40):
+        orc = pipeline.MatrixOracle(theta, K, inp.q_in, None, 1, iters=iters)
+        orc.step(tl)
+        assert np.array_equal(orc.theta, theta)           # nothing is applied at t = 1
+        errs.append(np.linalg.norm(Mbar - orc.delta_hat()))
+        assert errs[-1] >= floor * (1 - 1e-6)
+    assert all(a > b for a, b in zip(errs, errs[1:]))     # every further iteration helps
+    assert errs[-1] <= floor * (1 + 1e-4)
+    assert rel(orc.delta_hat(), best) < 2e-3
+    # the second iteration starts from the first one's Q average (a hand-over to anything else,
+    # the round's input basis say, would repeat the first iteration instead)
+    orc = pipeline.MatrixOracle(theta, K, inp.q_in, None, 1, iters=2)
+    orc.step(tl)
+    Ms = [d for d in orc.trace["delta"]]
+    _, q1, _ = _lowrank_once(Ms, inp.q_in)
+    p2, q2, _ = _lowrank_once(Ms, q1)
+    assert np.array_equal(orc.trace["q_bar"], q1) and np.array_equal(orc.trace["q_in@1"], q1)
+    assert np.array_equal(orc.p_hat, p2) and np.array_equal(orc.q_bar, q2)
+
+
 # --------------------------------------------------------------------------- orthonormalize
 def test_orthonormalize_matches_householder_qr():
     m, r = 30, 7
