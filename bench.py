@@ -29,7 +29,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, workers=0):
+def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, workers=0, iters=1):
     """plain=True draws i.i.d. Gaussian replicas instead of the low-rank-plus-noise recipe (no
     library QR/GEMM kernels in the process: used for hardware-counter runs, where only the
     traffic of this library's kernels is of interest)."""
@@ -67,7 +67,7 @@ def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, worker
         log("generated layer %d/%d  (%.1f s, %.1f GB allocated)" %
             (layer + 1, layers, time.time() - t0, torch.cuda.memory_allocated() / 1e9))
     stage = Stage(mats, synth.LR, synth.MU, fused=fused, warm_start=True, streams=streams,
-                  measure_rank=True)
+                  measure_rank=True, iters=iters)
     return stage, locals_
 
 
@@ -108,7 +108,8 @@ def cpu_baseline(stage, locals_, cfg_id):
             tl.append(x.view(torch.int16).cpu().numpy().view(np.uint16))
         else:
             tl.append(x.cpu().numpy())
-    orc = pipeline.MatrixOracle(theta, M.K, q_in, cfg["qbits"], cfg["group"], synth.LR, synth.MU)
+    orc = pipeline.MatrixOracle(theta, M.K, q_in, cfg["qbits"], cfg["group"], synth.LR, synth.MU,
+                                iters=stage.iters)
     t0 = time.time()
     orc.step(tl)
     orc.set_basis(orc.q_bar)
@@ -280,6 +281,8 @@ def main():
                     help="quantiser as the whole compressor (no low-rank step), all tensors flat")
     ap.add_argument("--requant", action="store_true",
                     help="quantise-only mode: re-encode the average to q bits")
+    ap.add_argument("--power-iters", type=int, default=1,
+                    help="power iterations per round (1 = the paper's compressor)")
     ap.add_argument("--mfma-peak", action="store_true",
                     help="measure the attainable bf16 matrix-core rate and exit")
     ap.add_argument("--probe", action="store_true",
@@ -312,7 +315,7 @@ def main():
         layers = 5
     fused = not args.unfused
     stage, locals_ = build_stage(args.config, args.mma, layers, device, fused, args.streams,
-                                 plain=args.probe, workers=args.workers)
+                                 plain=args.probe, workers=args.workers, iters=args.power_iters)
     if args.probe:
         x = torch.empty(1 << 28, dtype=torch.float32, device=device)
         y = torch.empty_like(x)
@@ -426,7 +429,8 @@ def main():
                 "peak_bf16_TFLOPs": 2500.0,
                 "note": "HBM-bound: %.0f executed flop per byte against a ridge of 312"
                         % (2.0 * cfg["r"] * (1 + K) * pieces / bpp)}
-    b_alg = (14 if tl_bytes == 2 else 16) * K + 20
+    # every further power iteration reads each worker's pseudo-gradient twice more
+    b_alg = (14 if tl_bytes == 2 else 16) * K + 20 + 8 * K * (args.power_iters - 1)
     out = {
         "metric": "outer-step params/sec per stage (compress+avg+Nesterov)",
         "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps,
@@ -438,7 +442,8 @@ def main():
         "config": {"workload": cfg["name"], "layers": layers, "matrices": len(stage.mats),
                    "params": params, "K": K, "rank": cfg["r"], "qbits": cfg["qbits"],
                    "group": cfg["group"], "theta_l": cfg["theta_l"], "mma": args.mma,
-                   "fused": fused, "streams": stage.nstreams, "hip_graph": use_graph["on"]},
+                   "fused": fused, "streams": stage.nstreams, "hip_graph": use_graph["on"],
+                   "power_iters": args.power_iters},
         "roofline": roofline,
         "stage_hbm": {"algorithmic_bytes_per_param": b_alg,
                       "achieved_GBps": b_alg * params / (dt / args.steps) / 1e9,

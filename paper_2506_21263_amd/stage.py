@@ -68,13 +68,17 @@ class Stage:
     batched=True orthonormalises (and measures) all matrices of the stage in one batch between
     the two compression phases instead of matrix by matrix.  requant=True re-encodes every
     averaged factor to q bits (dlcx_requantize), as a reduction that carries q-bit values would
-    deliver it, before it is used.
+    deliver it, before it is used.  iters > 1 repeats the two compression phases on the round's
+    pseudo-gradients, each repeat starting from the Q average just formed (more power iterations
+    per round: a closer rank-r fit for two more averages each).
     """
 
     def __init__(self, matrices, lr, mu, fused=False, warm_start=False, streams=1,
-                 measure_rank=False, tau=0.99, batched=True, requant=False):
+                 measure_rank=False, tau=0.99, batched=True, requant=False, iters=1):
+        assert iters >= 1
         self.mats = matrices
         self.requant = requant
+        self.iters = iters
         self.lr, self.mu = lr, mu
         self.fused, self.warm_start = fused, warm_start
         self.measure_rank, self.tau = measure_rank, tau
@@ -125,6 +129,18 @@ class Stage:
                                     stream=stream)
             dlcx_compress_batched(d, PHASE_P, M.ef, basis, M.codes_p, M.scales_p, ws,
                                   stream=stream)
+        self._p_average(M, ws, stream, orthonormalize)
+
+    def _p_phase_again(self, a, lane, stream, orthonormalize):
+        """P phase of a further power iteration: basis = the Q average just formed."""
+        M = self.mats[a]
+        ws = self.workspaces[lane]
+        dlcx_compress_batched(M.desc(), PHASE_P, M.ef, M.q_bar, M.codes_p, M.scales_p, ws,
+                              stream=stream)
+        self._p_average(M, ws, stream, orthonormalize)
+
+    def _p_average(self, M, ws, stream, orthonormalize):
+        d = M.desc()
         if orthonormalize and not self.requant:
             dlcx_average(d, PHASE_P, M.codes_p, M.scales_p, M.p_hat, ws, stream=stream)
             return
@@ -184,21 +200,29 @@ class Stage:
             for a in range(n):
                 lane, st = self._lane(a)
                 self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st, orthonormalize=True)
+                for j in range(1, self.iters):
+                    self._q_phase(a, lane, st, rank=False)
+                    self._p_phase_again(a, lane, st, orthonormalize=True)
                 self._q_phase(a, lane, st, rank=self.measure_rank)
             self._join(main)
             return
-        main = self._fork()
-        for a in range(n):
-            lane, st = self._lane(a)
-            self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st, orthonormalize=False)
-        self._join(main)
         descs = [M.desc() for M in self.mats]
-        dlcx_orthonormalize_batched(descs, [M.p_hat for M in self.mats], self.batch_ws)
-        main = self._fork()
-        for a in range(n):
-            lane, st = self._lane(a)
-            self._q_phase(a, lane, st, rank=False)
-        self._join(main)
+        for j in range(self.iters):
+            main = self._fork()
+            for a in range(n):
+                lane, st = self._lane(a)
+                if j == 0:
+                    self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st,
+                                            orthonormalize=False)
+                else:
+                    self._p_phase_again(a, lane, st, orthonormalize=False)
+            self._join(main)
+            dlcx_orthonormalize_batched(descs, [M.p_hat for M in self.mats], self.batch_ws)
+            main = self._fork()
+            for a in range(n):
+                lane, st = self._lane(a)
+                self._q_phase(a, lane, st, rank=False)
+            self._join(main)
         if self.measure_rank:
             dlcx_effective_rank_batched(descs, [M.q_bar for M in self.mats], self.tau,
                                         self.rprime_dev, self.batch_ws)

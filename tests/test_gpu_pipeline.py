@@ -463,3 +463,93 @@ def test_exactly_representable_input_passes_the_compressor_unchanged(mma, fused,
     torch.cuda.synchronize()
     assert rel_l2(to_np(M.theta_g), -0.5 * delta) <= 1e-6
     assert np.max(np.abs(to_np(M.ef[0]))) <= 1e-6 * np.max(np.abs(delta))
+
+
+@pytest.mark.parametrize("mma", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("batched", [True, False], ids=["batched", "per-matrix"])
+def test_further_power_iterations_within_a_round(mma, batched):
+    # iters = 3: after the round's first P and Q phase, two more of each on the same
+    # pseudo-gradients, every P phase from the Q average just formed.  Lockstep for the later
+    # iterations (the GPU projects the oracle's pseudo-gradients on the oracle's basis of that
+    # iteration), then the stage driver free-running against the oracle until the first code flip.
+    # The later iterations project on a basis that is nearly aligned with the singular vectors,
+    # so the sums cancel more and a float error of a few 1e-5 of a group's range is ordinary:
+    # the codes are therefore checked against the oracle's quantiser applied to the GPU's own
+    # factor (bit for bit), the factor against the oracle's at the mode's bar.
+    name, m, n, K, r, qbits, group, kind, iters = "iters3", 528, 400, 3, 12, 8, 16, "bf16", 3
+    tol = TOL[mma]
+    inp = synth.MatrixInputs(m, n, K, r, seed=97, sigma=1e-3, alpha=1.0, theta_l=kind)
+    orc = pipeline.MatrixOracle(inp.theta_g, K, inp.q_in, qbits, group, synth.LR, synth.MU,
+                                iters=iters)
+    M = MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), qbits, group, mma)
+    st = Stage([M], synth.LR, synth.MU, fused=True, warm_start=True, measure_rank=True,
+               batched=batched, iters=iters)
+    d = M.desc()
+    ws = ws_for(d, K)
+    flipped = False
+    for t in (1, 2):
+        tl = [inp.theta_local(orc.theta, t, i) for i in range(K)]
+        orc.step(tl)
+        deltas = [to_dev(x) for x in orc.trace["delta"]]
+        for j in range(1, iters):
+            sfx = "@%d" % j
+            assert np.array_equal(orc.trace["q_in" + sfx], orc.trace["q_bar" + ("@%d" % (j - 1) if j > 1 else "")])
+            codes, scales = payload_buffers(d, dlcx.PHASE_P, K)
+            dlcx.dlcx_compress_batched(d, dlcx.PHASE_P, deltas, to_dev(orc.trace["q_in" + sfx]),
+                                       codes, scales, ws)
+            torch.cuda.synchronize()
+            factors = to_np(ws[: K * r * m * 4].view(torch.float32)).reshape(K, r, m)
+            for k in range(K):
+                assert rel_l2(factors[k], orc.trace["P" + sfx][k]) <= tol, (t, j, k)
+                cw, sw = ref.quantize(factors[k], qbits, group)
+                assert np.array_equal(to_np(codes[k]), cw), (t, j, k)
+                assert np.array_equal(to_np(scales[k]).view(np.uint32), sw.view(np.uint32))
+            p_hat = torch.zeros(r, m, device=DEV)
+            dlcx.dlcx_average(d, dlcx.PHASE_P, [to_dev(c) for c in orc.trace["P" + sfx + "_codes"]],
+                              [to_dev(s) for s in orc.trace["P" + sfx + "_scales"]], p_hat, ws)
+            cond = np.linalg.cond(orc.trace["p_bar" + sfx].astype(np.float64))
+            assert rel_l2(to_np(p_hat), orc.trace["p_hat" + sfx]) <= max(1e-5, 4e-7 * cond), (t, j)
+            codes, scales = payload_buffers(d, dlcx.PHASE_Q, K)
+            dlcx.dlcx_compress_batched(d, dlcx.PHASE_Q, deltas, to_dev(orc.trace["p_hat" + sfx]),
+                                       codes, scales, ws)
+            torch.cuda.synchronize()
+            factors = to_np(ws[: K * r * n * 4].view(torch.float32)).reshape(K, r, n)
+            for k in range(K):
+                assert rel_l2(factors[k], orc.trace["Q" + sfx][k]) <= tol, (t, j, k)
+                cw, sw = ref.quantize(factors[k], qbits, group)
+                assert np.array_equal(to_np(codes[k]), cw), (t, j, k)
+                assert np.array_equal(to_np(scales[k]).view(np.uint32), sw.view(np.uint32))
+        # ---- the stage driver, free-running
+        st.step([[to_dev(x) for x in tl]])
+        torch.cuda.synchronize()
+        last = "@%d" % (iters - 1)
+        for tag, cg in (("P" + last, M.codes_p), ("Q" + last, M.codes_q)):
+            for k in range(K):
+                flipped = flipped or not np.array_equal(to_np(cg[k]), orc.trace[tag + "_codes"][k])
+        if not flipped:
+            cond = np.linalg.cond(orc.trace["p_bar" + last].astype(np.float64))
+            d_hat = torch.zeros(m, n, device=DEV)
+            dlcx.dlcx_decompress(d, M.p_hat, M.q_bar, d_hat, workspace=st.workspace)
+            assert rel_l2(to_np(d_hat), orc.delta_hat()) <= max(tol, 4e-7 * cond), (t, cond)
+            assert rel_l2(to_np(M.theta_g), orc.theta) <= tol and rel_l2(to_np(M.v), orc.v) <= tol
+            for k in range(K):
+                assert rel_l2(to_np(M.ef[k]), orc.trace["delta"][k]) <= tol, (t, k)
+        assert rel_l2(to_np(M.theta_g), orc.theta) <= 2e-2
+        # flips or not: the driver's own state is consistent with its own payloads, and it fits
+        # the mean pseudo-gradient about as well as the oracle's three iterations do
+        cq, sq = [to_np(c) for c in M.codes_q], [to_np(x) for x in M.scales_q]
+        assert np.array_equal(to_np(M.q_bar)[:r].reshape(-1).view(np.uint32),
+                              ref.dequant_average(cq, sq, r * n, qbits, group).view(np.uint32))
+        mean = np.mean([x.astype(np.float64) for x in orc.trace["delta"]], axis=0)
+        d_hat = torch.zeros(m, n, device=DEV)
+        dlcx.dlcx_decompress(d, M.p_hat, M.q_bar, d_hat, workspace=st.workspace)
+        if t == 1:  # identical pseudo-gradients on both sides in the first round
+            assert abs(np.linalg.norm(mean - to_np(d_hat)) / np.linalg.norm(mean - orc.delta_hat())
+                       - 1) < 1e-2
+        orc.set_basis(orc.q_bar)
+    if not flipped:
+        assert int(st.rprime_dev[0].item()) == ref.effective_rank(orc.q_bar, 0.99)
+    # the further iterations fit the mean pseudo-gradient better than the first one did
+    mean = np.mean([x.astype(np.float64) for x in orc.trace["delta"]], axis=0)
+    first = ref.reconstruct(orc.trace["p_hat"], orc.trace["q_bar"])
+    assert np.linalg.norm(mean - orc.delta_hat()) < np.linalg.norm(mean - first)
