@@ -88,8 +88,9 @@ def algorithmic_bytes_per_param(kernel, K, tl_bytes, fused):
 
 
 def cpu_baseline(stage, locals_, cfg_id):
-    """The oracle, as it stands, on one matrix of the workload: two outer steps of the smallest
-    matrix shape of the stage (K workers), single thread."""
+    """The oracle, as it stands, on one matrix of the workload: outer steps of the smallest
+    matrix shape of the stage (K workers), single thread, for about 12 s (at least two steps:
+    the first applies nothing)."""
     import numpy as np
     import torch
 
@@ -111,13 +112,16 @@ def cpu_baseline(stage, locals_, cfg_id):
     orc = pipeline.MatrixOracle(theta, M.K, q_in, cfg["qbits"], cfg["group"], synth.LR, synth.MU,
                                 iters=stage.iters)
     t0 = time.time()
-    orc.step(tl)
-    orc.set_basis(orc.q_bar)
-    orc.step(tl)
-    dt = (time.time() - t0) / 2.0
+    steps = 0
+    while steps < 2 or (time.time() - t0) * (steps + 1) / steps < 12.0:
+        orc.step(tl)
+        orc.set_basis(orc.q_bar)
+        steps += 1
+    dt = (time.time() - t0) / steps
     return {"value": M.m * M.n / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
-            "sample": "2 outer steps of one %dx%d matrix of the stage (K=%d, r=%d, int%d/%d), "
-                      "%.1f s per step" % (M.m, M.n, M.K, M.r, cfg["qbits"], cfg["group"], dt)}
+            "sample": "%d outer steps of one %dx%d matrix of the stage (K=%d, r=%d, int%d/%d), "
+                      "%.1f s per step" % (steps, M.m, M.n, M.K, M.r, cfg["qbits"], cfg["group"],
+                                           dt)}
 
 
 def quant_only(args):
@@ -264,8 +268,8 @@ def mfma_peak(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration (synth.CONFIGS)")
     ap.add_argument("--mma", type=int, default=2, help="0 fma/fp64-acc, 1 fp32-accurate MFMA, 2 bf16 MFMA")
     ap.add_argument("--layers", type=int, default=0, help="layers resident (0 = the whole stage)")
