@@ -12,9 +12,9 @@ kernel of libdlcx_hip.so.
               Q phase: compress, average                        dlcx_compress_batched, dlcx_average
               r' of the new average (Alg. 3)                    dlcx_effective_rank
 
-The matrices of a stage are independent, so they are dealt round-robin to a few HIP streams (all
-at the default priority): the short, latency-bound kernels of one matrix (Cholesky, Jacobi,
-quantiser) then run beside the HBM-bound sweeps of another.
+The matrices of a stage are independent, so consecutive runs of them are dealt to a few HIP
+streams (all at the default priority): the short, latency-bound kernels of one run (Cholesky,
+Jacobi, quantiser; batched over the run) then go beside the HBM-bound sweeps of another.
 """
 import ctypes as C
 
@@ -99,10 +99,20 @@ class Stage:
         self.rprime_dev = torch.zeros(len(matrices), device=dev, dtype=torch.int32)
         self.batched = batched
         self.serial = False
-        self.batch_ws = None
+        # lanes: consecutive runs of matrices with about the same number of elements each
+        total, acc, self.lane_of = sum(m.m * m.n for m in matrices), 0, []
+        for M in matrices:
+            self.lane_of.append(min(self.nstreams - 1, acc * self.nstreams // total))
+            acc += M.m * M.n
+        self.lane_ranges = []
+        for lane in range(self.nstreams):
+            idx = [a for a, l in enumerate(self.lane_of) if l == lane]
+            self.lane_ranges.append((idx[0], idx[-1] + 1) if idx else (0, 0))
+        self.batch_ws = [None] * self.nstreams
         if batched:
-            nbytes = dlcx_batched_workspace_bytes([M.desc(M.r_max) for M in matrices])
-            self.batch_ws = torch.empty(nbytes, device=dev, dtype=torch.uint8)
+            for lane, (lo, hi) in enumerate(self.lane_ranges):
+                nbytes = dlcx_batched_workspace_bytes([M.desc(M.r_max) for M in matrices[lo:hi]])
+                self.batch_ws[lane] = torch.empty(max(nbytes, 256), device=dev, dtype=torch.uint8)
 
     def params(self):
         return sum(m.m * m.n for m in self.mats)
@@ -185,7 +195,7 @@ class Stage:
     def _lane(self, a):
         if self.serial:
             return 0, None
-        lane = a % self.nstreams
+        lane = self.lane_of[a]
         return lane, (self.side[lane] if self.side else None)
 
     def step(self, theta_l_per_matrix, serial=False):
@@ -206,26 +216,30 @@ class Stage:
                 self._q_phase(a, lane, st, rank=self.measure_rank)
             self._join(main)
             return
-        descs = [M.desc() for M in self.mats]
-        for j in range(self.iters):
-            main = self._fork()
-            for a in range(n):
-                lane, st = self._lane(a)
-                if j == 0:
-                    self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st,
-                                            orthonormalize=False)
-                else:
-                    self._p_phase_again(a, lane, st, orthonormalize=False)
-            self._join(main)
-            dlcx_orthonormalize_batched(descs, [M.p_hat for M in self.mats], self.batch_ws)
-            main = self._fork()
-            for a in range(n):
-                lane, st = self._lane(a)
-                self._q_phase(a, lane, st, rank=False)
-            self._join(main)
-        if self.measure_rank:
-            dlcx_effective_rank_batched(descs, [M.q_bar for M in self.mats], self.tau,
-                                        self.rprime_dev, self.batch_ws)
+        # each lane batches its own matrices: the latency-bound batched kernels of one lane run
+        # beside the HBM-bound sweeps of the others, and no lane waits for another inside a step
+        main = self._fork()
+        for lane, (lo, hi) in enumerate(self.lane_ranges):
+            if hi == lo:
+                continue
+            _, st = self._lane(lo)
+            mats = self.mats[lo:hi]
+            descs = [M.desc() for M in mats]
+            for j in range(self.iters):
+                for a in range(lo, hi):
+                    if j == 0:
+                        self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st,
+                                                orthonormalize=False)
+                    else:
+                        self._p_phase_again(a, lane, st, orthonormalize=False)
+                dlcx_orthonormalize_batched(descs, [M.p_hat for M in mats], self.batch_ws[lane],
+                                            stream=st)
+                for a in range(lo, hi):
+                    self._q_phase(a, lane, st, rank=False)
+            if self.measure_rank:
+                dlcx_effective_rank_batched(descs, [M.q_bar for M in mats], self.tau,
+                                            self.rprime_dev[lo:], self.batch_ws[lane], stream=st)
+        self._join(main)
 
 
     def capture(self, theta_l_per_matrix):
