@@ -29,7 +29,8 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, workers=0, iters=1):
+def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, workers=0, iters=1,
+                chunk=0):
     """plain=True draws i.i.d. Gaussian replicas instead of the low-rank-plus-noise recipe (no
     library QR/GEMM kernels in the process: used for hardware-counter runs, where only the
     traffic of this library's kernels is of interest)."""
@@ -67,7 +68,7 @@ def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, worker
         log("generated layer %d/%d  (%.1f s, %.1f GB allocated)" %
             (layer + 1, layers, time.time() - t0, torch.cuda.memory_allocated() / 1e9))
     stage = Stage(mats, synth.LR, synth.MU, fused=fused, warm_start=True, streams=streams,
-                  measure_rank=True, iters=iters)
+                  measure_rank=True, iters=iters, chunk=chunk)
     return stage, locals_
 
 
@@ -285,6 +286,8 @@ def main():
                     help="quantiser as the whole compressor (no low-rank step), all tensors flat")
     ap.add_argument("--requant", action="store_true",
                     help="quantise-only mode: re-encode the average to q bits")
+    ap.add_argument("--chunk", type=int, default=0,
+                    help="matrices per batch of a stream (0 = the stream's whole share at once)")
     ap.add_argument("--power-iters", type=int, default=1,
                     help="power iterations per round (1 = the paper's compressor)")
     ap.add_argument("--mfma-peak", action="store_true",
@@ -319,7 +322,8 @@ def main():
         layers = 5
     fused = not args.unfused
     stage, locals_ = build_stage(args.config, args.mma, layers, device, fused, args.streams,
-                                 plain=args.probe, workers=args.workers, iters=args.power_iters)
+                                 plain=args.probe, workers=args.workers, iters=args.power_iters,
+                                 chunk=args.chunk)
     if args.probe:
         x = torch.empty(1 << 28, dtype=torch.float32, device=device)
         y = torch.empty_like(x)

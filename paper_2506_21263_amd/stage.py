@@ -62,11 +62,12 @@ class Stage:
 
     fused=True uses dlcx_ef_delta_apply_compress (one pass for error buffers, pseudo-gradients,
     outer update and the P-phase projection, the decompressed average never written);
-    fused=False runs the separate entry points.  warm_start=True takes Q_bar of the previous round as the basis of the P phase.
-    streams > 1 deals the matrices to that many HIP streams.  measure_rank=True also launches
-    the effective-rank kernel of Alg. 3 for every matrix (results in self.rprime_dev).
-    batched=True orthonormalises (and measures) all matrices of the stage in one batch between
-    the two compression phases instead of matrix by matrix.  requant=True re-encodes every
+    fused=False runs the separate entry points.  warm_start=True takes Q_bar of the previous
+    round as the basis of the P phase.  streams > 1 deals consecutive runs of matrices to that
+    many HIP streams.  measure_rank=True also launches the effective-rank kernel of Alg. 3 for
+    every matrix (results in self.rprime_dev).  batched=True orthonormalises (and measures) the
+    matrices of a stream `chunk` at a time in one batch between the two compression phases
+    instead of matrix by matrix (chunk = 0: a stream's whole run).  requant=True re-encodes every
     averaged factor to q bits (dlcx_requantize), as a reduction that carries q-bit values would
     deliver it, before it is used.  iters > 1 repeats the two compression phases on the round's
     pseudo-gradients, each repeat starting from the Q average just formed (more power iterations
@@ -74,8 +75,8 @@ class Stage:
     """
 
     def __init__(self, matrices, lr, mu, fused=False, warm_start=False, streams=1,
-                 measure_rank=False, tau=0.99, batched=True, requant=False, iters=1):
-        assert iters >= 1
+                 measure_rank=False, tau=0.99, batched=True, requant=False, iters=1, chunk=0):
+        assert iters >= 1 and chunk >= 0
         self.mats = matrices
         self.requant = requant
         self.iters = iters
@@ -108,11 +109,25 @@ class Stage:
         for lane in range(self.nstreams):
             idx = [a for a, l in enumerate(self.lane_of) if l == lane]
             self.lane_ranges.append((idx[0], idx[-1] + 1) if idx else (0, 0))
+        # a lane works through its run in chunks of `chunk` matrices (0: the length of the run),
+        # the first chunk of lane l cut to (l + 1) / nstreams of that, so that the lanes are in
+        # different phases of the step (one in its projections while another is in its sweeps)
+        self.lane_chunks = []
+        for lane, (lo, hi) in enumerate(self.lane_ranges):
+            chunks, a = [], lo
+            size = chunk if chunk > 0 else max(hi - lo, 1)
+            first = max(1, size * (lane + 1) // self.nstreams)
+            while a < hi:
+                b = min(hi, a + (first if not chunks else size))
+                chunks.append((a, b))
+                a = b
+            self.lane_chunks.append(chunks)
         self.batch_ws = [None] * self.nstreams
         if batched:
-            for lane, (lo, hi) in enumerate(self.lane_ranges):
-                nbytes = dlcx_batched_workspace_bytes([M.desc(M.r_max) for M in matrices[lo:hi]])
-                self.batch_ws[lane] = torch.empty(max(nbytes, 256), device=dev, dtype=torch.uint8)
+            for lane, chunks in enumerate(self.lane_chunks):
+                nbytes = max([dlcx_batched_workspace_bytes([M.desc(M.r_max) for M in matrices[a:b]])
+                              for a, b in chunks] + [256])
+                self.batch_ws[lane] = torch.empty(nbytes, device=dev, dtype=torch.uint8)
 
     def params(self):
         return sum(m.m * m.n for m in self.mats)
@@ -219,26 +234,26 @@ class Stage:
         # each lane batches its own matrices: the latency-bound batched kernels of one lane run
         # beside the HBM-bound sweeps of the others, and no lane waits for another inside a step
         main = self._fork()
-        for lane, (lo, hi) in enumerate(self.lane_ranges):
-            if hi == lo:
-                continue
-            _, st = self._lane(lo)
-            mats = self.mats[lo:hi]
-            descs = [M.desc() for M in mats]
-            for j in range(self.iters):
-                for a in range(lo, hi):
-                    if j == 0:
-                        self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st,
-                                                orthonormalize=False)
-                    else:
-                        self._p_phase_again(a, lane, st, orthonormalize=False)
-                dlcx_orthonormalize_batched(descs, [M.p_hat for M in mats], self.batch_ws[lane],
-                                            stream=st)
-                for a in range(lo, hi):
-                    self._q_phase(a, lane, st, rank=False)
-            if self.measure_rank:
-                dlcx_effective_rank_batched(descs, [M.q_bar for M in mats], self.tau,
-                                            self.rprime_dev[lo:], self.batch_ws[lane], stream=st)
+        for lane, chunks in enumerate(self.lane_chunks):
+            for lo, hi in chunks:
+                _, st = self._lane(lo)
+                mats = self.mats[lo:hi]
+                descs = [M.desc() for M in mats]
+                for j in range(self.iters):
+                    for a in range(lo, hi):
+                        if j == 0:
+                            self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st,
+                                                    orthonormalize=False)
+                        else:
+                            self._p_phase_again(a, lane, st, orthonormalize=False)
+                    dlcx_orthonormalize_batched(descs, [M.p_hat for M in mats],
+                                                self.batch_ws[lane], stream=st)
+                    for a in range(lo, hi):
+                        self._q_phase(a, lane, st, rank=False)
+                if self.measure_rank:
+                    dlcx_effective_rank_batched(descs, [M.q_bar for M in mats], self.tau,
+                                                self.rprime_dev[lo:], self.batch_ws[lane],
+                                                stream=st)
         self._join(main)
 
 
