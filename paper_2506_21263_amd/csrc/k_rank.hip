@@ -132,7 +132,7 @@ __device__ void tridiagonal_eigenvalues(double *a, int r, int ld, double *d, dou
 }
 
 __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, double tau) {
-    const int nthreads = blockDim.x;  // 256 for small matrices, 1024 when r > 128
+    const int nthreads = blockDim.x;  // 256 .. 1024: one team of 16 lanes per column pair
     extern __shared__ double smem[];
     const FactorItem it = batch.it[blockIdx.x];
     const int r = it.r, nchunks = it.nchunks;
@@ -280,8 +280,12 @@ int launch_effective_rank_batch(const FactorBatch &batch, double tau, hipStream_
     Timed timed(KID_JACOBI, st);
     int rmax = 0;
     for (int i = 0; i < batch.n; ++i) rmax = batch.it[i].r > rmax ? batch.it[i].r : rmax;
-    hipLaunchKernelGGL(jacobi_rank_kernel, dim3((unsigned)batch.n), dim3(rmax > 128 ? 1024 : 256),
-                       bytes, st, batch, tau);
+    // a team of 16 lanes per column pair of the largest matrix (r / 2 pairs), so that a step of
+    // the pair schedule is one pass; 1024 threads for the tridiagonal path
+    int threads = ((rmax + 1) / 2 * 16 + 255) / 256 * 256;
+    threads = threads < 256 ? 256 : (threads > kJT || rmax > 128 ? kJT : threads);
+    hipLaunchKernelGGL(jacobi_rank_kernel, dim3((unsigned)batch.n), dim3((unsigned)threads), bytes,
+                       st, batch, tau);
     return check_launch("jacobi_rank");
 }
 
