@@ -103,7 +103,8 @@ class Stage:
         # lanes: consecutive runs of matrices with about the same number of elements each
         total, acc, self.lane_of = sum(m.m * m.n for m in matrices), 0, []
         for M in matrices:
-            self.lane_of.append(min(self.nstreams - 1, acc * self.nstreams // total))
+            mid = acc + M.m * M.n // 2
+            self.lane_of.append(min(self.nstreams - 1, mid * self.nstreams // total))
             acc += M.m * M.n
         self.lane_ranges = []
         for lane in range(self.nstreams):

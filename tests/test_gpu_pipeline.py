@@ -213,22 +213,25 @@ def test_multi_stream_stage_equals_single_stream():
     shapes = [(256, 384), (512, 256), (384, 640), (256, 256), (640, 384)]
     K, r = 3, 16
 
-    def run(streams, batched=True):
+    def run(streams, batched=True, chunk=0):
         mats, tls = [], []
         for a, (m, n) in enumerate(shapes):
             inp = synth.MatrixInputs(m, n, K, r, seed=500 + a, sigma=1e-3, alpha=1.0, theta_l="bf16")
             mats.append(MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), 4, 64, dlcx.MMA_BF16))
             tls.append([to_dev(inp.theta_local(inp.theta_g, 1, i)) for i in range(K)])
         st = Stage(mats, synth.LR, synth.MU, fused=True, warm_start=True, streams=streams,
-                   measure_rank=True, batched=batched)
+                   measure_rank=True, batched=batched, chunk=chunk)
         for _ in range(3):
             st.step(tls)
         torch.cuda.synchronize()
         return st
 
-    one, three, loose = run(1), run(3), run(2, batched=False)
-    assert three.nstreams == 3
-    for other in (three, loose):
+    one, three, loose, chunked = run(1), run(3), run(2, batched=False), run(2, chunk=2)
+    assert three.nstreams == 3 and max(len(c) for c in chunked.lane_chunks) >= 2
+    for st in (one, three, chunked):   # every matrix in exactly one chunk
+        covered = sorted(a for chunks in st.lane_chunks for lo, hi in chunks for a in range(lo, hi))
+        assert covered == list(range(len(shapes)))
+    for other in (three, loose, chunked):
         for A, B in zip(one.mats, other.mats):
             assert torch.equal(A.theta_g, B.theta_g) and torch.equal(A.v, B.v)
             assert torch.equal(A.q_bar, B.q_bar) and torch.equal(A.p_hat, B.p_hat)
