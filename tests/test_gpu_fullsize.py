@@ -243,3 +243,89 @@ def test_quantise_only_step_full_size_sampled_groups():
         assert np.array_equal(theta[eidx].cpu().numpy().view(np.uint32), orc.theta.view(np.uint32)), t
         assert np.array_equal(v[eidx].cpu().numpy().view(np.uint32), orc.v.view(np.uint32)), t
     assert orc.n_applied == T - 1 and not np.array_equal(orc.theta, theta0_s)
+
+
+def test_flat_tensors_beyond_2_31_elements():
+    # Largest sizes: a flat tensor of 2^31 + 4736 elements (+ 3 for the entry points that take a
+    # ragged tail), where every 32-bit element index overflows.  All these steps are local to an
+    # element or to a group of 128, so the oracle run on three windows (the start, across 2^31,
+    # the end with the tail) must reproduce the GPU there: bit for bit for delta, codes, scales
+    # and the quantise-only step, to 1e-6 for the fp32 Nesterov kernel.
+    from oracle import pipeline
+    group = 128
+    numel = 2 ** 31 + group * 37
+    total = numel + 3
+    win = [(0, 8192), (2 ** 31 - 8192, 2 ** 31 + 4096), (numel - 8192, total)]
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(31)
+
+    def sample(x, upto=total):
+        return [x[a:min(b, upto)].cpu().numpy() for a, b in win]
+
+    theta = torch.empty(total, device=DEV).normal_(0.0, 0.02, generator=gen)
+    e = torch.empty(total, device=DEV).normal_(0.0, 1e-3, generator=gen)
+    tl = torch.empty(total, device=DEV).normal_(0.0, 1e-3, generator=gen).neg_().add_(theta)
+    tl = tl.to(torch.bfloat16)
+    th_s, e_s, tl_s = sample(theta), sample(e), [_bits(x[a:b]) for x in [tl] for a, b in win]
+    # ---- pseudo-gradient with error compensation
+    dlcx.dlcx_delta_ef(theta, tl, e)
+    torch.cuda.synchronize()
+    d_s = sample(e)
+    for w in range(3):
+        want = ref.delta_ef(th_s[w], tl_s[w], e_s[w])
+        assert np.array_equal(d_s[w].view(np.uint32), want.view(np.uint32)), ("delta_ef", w)
+    # ---- quantiser on the first numel elements (whole groups)
+    codes = torch.zeros(numel // 2, device=DEV, dtype=torch.uint8)
+    scales = torch.zeros(numel // group, device=DEV)
+    dlcx.dlcx_quantize(e, 4, group, codes, scales, count=numel)
+    torch.cuda.synchronize()
+    for w, (a, b) in enumerate(win):
+        b = min(b, numel)
+        cw, sw = ref.quantize(d_s[w][: b - a], 4, group)
+        assert np.array_equal(codes[a // 2:b // 2].cpu().numpy(), cw), ("codes", w)
+        assert np.array_equal(scales[a // group:b // group].cpu().numpy().view(np.uint32),
+                              sw.view(np.uint32)), ("scales", w)
+    del codes, scales
+    # ---- outer Nesterov step with delta as the gradient
+    v = torch.empty(total, device=DEV).normal_(0.0, 1e-3, generator=gen)
+    v_s = sample(v)
+    dlcx.dlcx_outer_nesterov(theta, v, e, synth.LR, synth.MU)
+    torch.cuda.synchronize()
+    th2, v2 = sample(theta), sample(v)
+    for w in range(3):
+        tw, vw = th_s[w].copy(), v_s[w].copy()
+        ref.outer_nesterov(tw, vw, d_s[w], synth.LR, synth.MU)
+        assert rel_l2(th2[w], tw) <= 1e-6 and rel_l2(v2[w], vw) <= 1e-6, ("nesterov", w)
+        assert not np.array_equal(th2[w], th_s[w])
+    del tl, e
+    # ---- the quantise-only outer step, K = 2, two steps running free on numel elements
+    Kq = 2
+    theta = theta[:numel]
+    v = v[:numel].zero_()
+    theta0 = theta.clone()
+    ef = [torch.zeros(numel, device=DEV) for _ in range(Kq)]
+    codes = [torch.zeros(numel // 2, device=DEV, dtype=torch.uint8) for _ in range(Kq)]
+    scales = [torch.zeros(numel // group, device=DEV) for _ in range(Kq)]
+    qwin = [(a, min(b, numel)) for a, b in win]
+    cat = lambda x: np.concatenate([x[a:b].cpu().numpy() for a, b in qwin])
+    orc = pipeline.TensorOracle(cat(theta), Kq, 4, group, synth.LR, synth.MU)
+    for t in (1, 2):
+        tls = []
+        for i in range(Kq):
+            g = torch.empty(numel, device=DEV).normal_(0.0, 1e-3 * (1 + i + t), generator=gen)
+            tls.append(g.neg_().add_(theta0).to(torch.bfloat16))
+            del g
+        orc.step([np.concatenate([_bits(x[a:b]) for a, b in qwin]) for x in tls])
+        dlcx.dlcx_quant_round(numel, 4, group, tls, ef, theta, v, synth.LR, synth.MU,
+                              None if t == 1 else codes, None if t == 1 else scales, codes, scales)
+        torch.cuda.synchronize()
+        for i in range(Kq):
+            got_c = np.concatenate([codes[i][a // 2:b // 2].cpu().numpy() for a, b in qwin])
+            got_s = np.concatenate([scales[i][a // group:b // group].cpu().numpy() for a, b in qwin])
+            assert np.array_equal(got_c, orc.codes[i]), (t, i)
+            assert np.array_equal(got_s.view(np.uint32), orc.scales[i].view(np.uint32)), (t, i)
+            assert np.array_equal(cat(ef[i]).view(np.uint32), orc.ef[i].view(np.uint32)), (t, i)
+        assert np.array_equal(cat(theta).view(np.uint32), orc.theta.view(np.uint32)), t
+        assert np.array_equal(cat(v).view(np.uint32), orc.v.view(np.uint32)), t
+        del tls
+    assert orc.n_applied == 1
