@@ -59,18 +59,19 @@ def _oracle_q_columns(deltas, p_hat, cols):
     return out
 
 
-def _check_groups(codes_gpu, scales_gpu, factor_ref, L, groups, what):
-    """Bit-compare the payload of whole groups (along L) of every factor column."""
+def _check_groups(codes_gpu, scales_gpu, factor_ref, L, groups, what, r=R, ref_offset=0):
+    """Bit-compare the payload of whole groups (along L) of every factor column; factor_ref
+    holds the reference factor from element ref_offset of each column on."""
     G = GROUP
     flips = 0
     for g in groups:
-        blk = np.ascontiguousarray(factor_ref[:, g * G:(g + 1) * G])          # (r, G)
+        blk = np.ascontiguousarray(factor_ref[:, g * G - ref_offset:(g + 1) * G - ref_offset])
         cw, sw = ref.quantize(blk.reshape(-1), QBITS, G)
         got_c = np.stack([codes_gpu[(c * L + g * G) // 2:(c * L + (g + 1) * G) // 2]
-                          for c in range(R)]).reshape(-1)
-        got_s = np.array([scales_gpu[(c * L) // G + g] for c in range(R)], np.float32)
+                          for c in range(r)]).reshape(-1)
+        got_s = np.array([scales_gpu[(c * L) // G + g] for c in range(r)], np.float32)
         assert rel_l2(got_s, sw) <= TOL, what
-        nb, ok = code_mismatch_report(got_c, cw, blk, sw, R * G, QBITS, G, ref.unpack_codes)
+        nb, ok = code_mismatch_report(got_c, cw, blk, sw, r * G, QBITS, G, ref.unpack_codes)
         assert ok, (what, g, "code mismatch that is not a one-step boundary flip")
         flips += nb
     return flips
@@ -329,3 +330,105 @@ def test_flat_tensors_beyond_2_31_elements():
         assert np.array_equal(cat(v).view(np.uint32), orc.v.view(np.uint32)), t
         del tls
     assert orc.n_applied == 1
+
+
+@pytest.mark.timeout(400)
+def test_matrix_beyond_2_31_elements():
+    # Largest sizes on the low-rank path: one 65536 x 32896 matrix (2.156 G elements, element
+    # 2^31 sits in row 65280), K = 1, r = 8, bf16 replica, the fused entry point of the bench.
+    # Round 1 and the Q phase against the oracle on whole groups at the start, across the 2^31
+    # boundary and at the end; round 2 (feedback, new delta, outer update) on sampled rows there.
+    m, n, r, Kb = 65536, 32896, 8, 1
+    assert m * n > 2 ** 31
+    print("matrix %dx%d" % (m, n), flush=True)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(65536)
+    # theta ~ N(0, 0.02^2); pseudo-gradient = rank-12 part with a 1/k spectrum + small noise
+    theta = torch.empty(m, n, device=DEV).normal_(0.0, 0.02, generator=gen)
+    U = torch.linalg.qr(torch.randn(m, 12, device=DEV, generator=gen))[0]
+    V = torch.linalg.qr(torch.randn(n, 12, device=DEV, generator=gen))[0]
+    sv = 1.0 / torch.arange(1, 13, device=DEV)
+    g = (U * sv) @ V.T
+    g.add_(torch.empty(m, n, device=DEV).normal_(0.0, 2e-5, generator=gen))
+    tl = (theta - g).to(torch.bfloat16)
+    del g, U, V
+    q_in_t = torch.randn(r, n, device=DEV, generator=gen)
+    theta0 = theta.cpu().numpy()
+    tl_bits = _bits(tl)
+    q_in = q_in_t.cpu().numpy()
+    d = dlcx.desc(m, n, r, QBITS, GROUP, MMA)
+    ws = ws_for(d, Kb)
+    rows = np.array([0, 1, 31, 32, 65279, 65280, 65281, 65407, 65408, m - 33, m - 2, m - 1])
+
+    # ---- oracle, round 1
+    delta = ref.delta_ef(theta0.reshape(-1), tl_bits.reshape(-1),
+                         np.zeros(m * n, np.float32)).reshape(m, n)
+    P = _oracle_full_p([delta], q_in)
+    cp, sp = ref.quantize(P[0], QBITS, GROUP)
+    p_bar = ref.dequant_average([cp], [sp], r * m, QBITS, GROUP).reshape(r, m)
+    p_hat = ref.orthonormalize(p_bar)
+
+    # ---- GPU round 1, fused entry point (r_prev = 0)
+    efs = [torch.zeros(m, n, device=DEV)]
+    th, v = theta.clone(), torch.zeros(m, n, device=DEV)
+    codes, scales = payload_buffers(d, dlcx.PHASE_P, Kb)
+    dlcx.dlcx_ef_delta_apply_compress(d, 0, None, None, [tl], efs, th, v, synth.LR, synth.MU,
+                                      q_in_t, codes, scales, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(th, theta) and not bool(v.any())
+    idx = torch.from_numpy(rows).to(DEV)
+    assert rel_l2(efs[0][idx].cpu().numpy(), delta[rows]) <= 1e-6
+    groups_m = [0, 65280 // GROUP, m // GROUP - 1]          # rows 65280.. hold element 2^31
+    flips = _check_groups(to_np(codes[0]), to_np(scales[0]), P[0], m, groups_m, "P", r=r)
+    d_p_hat = torch.zeros(r, m, device=DEV)
+    dlcx.dlcx_average(d, dlcx.PHASE_P, [to_dev(cp)], [to_dev(sp)], d_p_hat, ws)
+    cond = np.linalg.cond(p_bar.astype(np.float64))
+    assert rel_l2(to_np(d_p_hat), p_hat) <= max(1e-5, 4e-7 * cond), cond
+    # ---- Q phase from the oracle's basis: first and last group of columns
+    codes_q, scales_q = payload_buffers(d, dlcx.PHASE_Q, Kb)
+    dlcx.dlcx_compress_batched(d, dlcx.PHASE_Q, efs, to_dev(p_hat), codes_q, scales_q, ws)
+    torch.cuda.synchronize()
+    for gq in (0, n // GROUP - 1):
+        cols = np.arange(gq * GROUP, (gq + 1) * GROUP)
+        Qs = _oracle_q_columns([delta], p_hat, cols)
+        flips += _check_groups(to_np(codes_q[0]), to_np(scales_q[0]), Qs[0], n, [gq], "Q", r=r,
+                               ref_offset=gq * GROUP)
+    assert flips <= 2e-3 * r * GROUP * 5 + 2, flips
+
+    # ---- round 2, fused, with a seeded previous Q_bar: sampled rows
+    rs = np.random.default_rng(5)
+    q_bar = (rs.standard_normal((r, n)) * (np.arange(1, r + 1)[:, None] ** -1.0) * 1e-2).astype(np.float32)
+    tl2 = (tl.float() + torch.empty(m, n, device=DEV).normal_(0.0, 1e-4, generator=gen)).to(torch.bfloat16)
+    v.normal_(0.0, 1e-4, generator=gen)
+    v_rows = v[idx].cpu().numpy()
+    tl2_rows = _bits(tl2[idx])
+    codes2, scales2 = payload_buffers(d, dlcx.PHASE_P, Kb)
+    dlcx.dlcx_ef_delta_apply_compress(d, r, to_dev(p_hat), to_dev(q_bar), [tl2], efs, th, v,
+                                      synth.LR, synth.MU, to_dev(q_bar), codes2, scales2, ws)
+    torch.cuda.synchronize()
+    d_hat_rows = ref.reconstruct(np.ascontiguousarray(p_hat[:, rows]), q_bar)
+    e = delta[rows].copy()
+    ref.ef_update(e.reshape(-1), d_hat_rows.reshape(-1))
+    nd = ref.delta_ef(theta0[rows].reshape(-1), np.ascontiguousarray(tl2_rows).reshape(-1),
+                      e.reshape(-1)).reshape(len(rows), n)
+    th_w, v_w = theta0[rows].copy(), v_rows.copy()
+    ref.outer_nesterov(th_w.reshape(-1), v_w.reshape(-1), d_hat_rows.reshape(-1), synth.LR, synth.MU)
+    got = efs[0][idx].cpu().numpy()
+    assert rel_l2(got, nd) <= TOL
+    base = delta[rows] + (theta0[rows] - synth.bf16_bits_to_f32(tl2_rows))
+    assert rel_l2(base - got, d_hat_rows) <= TOL
+    assert rel_l2(theta0[rows] - th[idx].cpu().numpy(), theta0[rows] - th_w) <= TOL
+    assert rel_l2(v[idx].cpu().numpy(), v_w) <= TOL
+    # the P payload of round 2 for the last group of rows (all beyond element 2^31)
+    g0 = m // GROUP - 1
+    grp = np.arange(g0 * GROUP, m)
+    gidx = torch.from_numpy(grp).to(DEV)
+    d_hat_g = ref.reconstruct(np.ascontiguousarray(p_hat[:, grp]), q_bar)
+    e = delta[grp].copy()
+    ref.ef_update(e.reshape(-1), d_hat_g.reshape(-1))
+    nd_g = ref.delta_ef(theta0[grp].reshape(-1), np.ascontiguousarray(_bits(tl2[gidx])).reshape(-1),
+                        e.reshape(-1)).reshape(GROUP, n)
+    p_rows = ref.project_p(nd_g, q_bar)
+    flips2 = _check_groups(to_np(codes2[0]), to_np(scales2[0]), p_rows, m, [g0], "P round 2", r=r,
+                           ref_offset=g0 * GROUP)
+    assert flips2 <= 0.02 * r * GROUP
