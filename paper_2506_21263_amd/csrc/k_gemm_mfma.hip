@@ -332,6 +332,159 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
 }
 
 // ---------------------------------------------------------------------------------------------
+// P phase at 8 basis blocks (128 < r <= 256), where a stage of matrix-core work is about as long
+// as a round trip to HBM and a single wavefront per SIMD cannot hide one behind the other.  The
+// workgroup has 8 wavefronts with two roles.  Wavefronts 4..7 (producers) stream delta: stage s
+// lives in register set s & 1, is split into bf16 pieces and laid down in LDS buffer s & 1 one
+// stage before it is used, and its set is refilled at once with stage s + 2, so that every
+// request has two stages of time to come back.  Wavefronts 0..3 (consumers) own WC x WR blocks of
+// the output, fetch their basis fragments through L2 two k-steps ahead (their load counter never
+// waits for HBM) and keep the matrix cores busy on the buffer the producers filled last.  One
+// LDS-only barrier per stage for all eight.  Loads past the matrix or past the last stage are
+// clamped to a valid address and zeroed / never read, which keeps both loops free of branches.
+// ---------------------------------------------------------------------------------------------
+constexpr int kWs = 512;  // threads of the two-role workgroup
+
+template <int NS, int CBW, int WC, int WR, int RB>
+__global__ __launch_bounds__(kWs) void project_p_ws_kernel(PtrPack<const float *> deltas,
+                                                           const uint4 *__restrict__ afrags,
+                                                           PtrPack<float *> outs, int64_t m,
+                                                           int64_t n, int r) {
+    constexpr int CB = CBW * WC;
+    constexpr int RBW = RB / WR;
+    constexpr int kRows = 32 * RB;
+    constexpr int kVec = kRows * 16 / kW;  // float4 per producer thread and stage
+    static_assert(WC * WR == 4, "four consumer wavefronts");
+    constexpr int kBuf = NS * kRows * kPPitch;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    const float *__restrict__ delta = deltas.p[blockIdx.y];
+    float *__restrict__ out = outs.p[blockIdx.y];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t i0 = (int64_t)blockIdx.x * kRows;
+    const int64_t nstages = (n + 63) / 64;
+
+    if (wave >= 4) {  // ---------------------------------------------------------- producers
+        const int tid = threadIdx.x - kW;
+        auto load_stage = [&](float4 (&set)[kVec], int64_t t) {
+            const int64_t tc = t < nstages ? t : nstages - 1;
+#pragma unroll
+            for (int u = 0; u < kVec; ++u) {
+                const int idx = tid + kW * u;
+                const int row = idx >> 4, c4 = idx & 15;
+                const int64_t j = tc * 64 + c4 * 4;
+                const bool ok = i0 + row < m && j < n;
+                // the value of a clamped load is discarded when the stage is laid down, not
+                // here: touching it now would wait for the request just made
+                set[u] = stream_load4(ok ? delta + (i0 + row) * n + j : delta);
+            }
+        };
+        auto store_stage = [&](const float4 (&set)[kVec], unsigned char *buf, int64_t t) {
+#pragma unroll
+            for (int u = 0; u < kVec; ++u) {
+                const int idx = tid + kW * u;
+                const int row = idx >> 4, c4 = idx & 15;
+                const bool ok = i0 + row < m && t * 64 + c4 * 4 < n;
+                const float4 x = make_float4(ok ? set[u].x : 0.f, ok ? set[u].y : 0.f,
+                                             ok ? set[u].z : 0.f, ok ? set[u].w : 0.f);
+                uint32_t lo[NS], hi[NS];
+                split2<NS>(x.x, x.y, lo);
+                split2<NS>(x.z, x.w, hi);
+#pragma unroll
+                for (int h = 0; h < NS; ++h)
+                    *reinterpret_cast<uint2 *>(buf + (h * kRows + row) * kPPitch + c4 * 8) =
+                        make_uint2(lo[h], hi[h]);
+            }
+        };
+        // one step: lay down stage `stage` (held in `set`) for the consumers' next iteration
+        // while they work on the stage before it, then refill the set two stages further on
+        auto step = [&](float4 (&set)[kVec], int64_t stage, bool refill) {
+            store_stage(set, lds + (stage & 1) * kBuf, stage);
+            if (refill) load_stage(set, stage + 2);
+            lds_barrier();
+            // nothing of the next step moves above the barrier: splitting its set earlier would
+            // wait for requests that are younger than they should be
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        float4 set0[kVec], set1[kVec];
+        load_stage(set0, 0);
+        load_stage(set1, 1);
+        step(set0, 0, true);
+        // two stages per trip, no way round the second inside the loop: the compiler's wait
+        // counts at the loop head then see one order of outstanding requests only.  (Four sets
+        // and four stages of distance measured no faster.)
+        int64_t t = 0;
+        for (; t + 1 < nstages; t += 2) {
+            step(set1, t + 1, true);
+            step(set0, t + 2, true);
+        }
+        // an odd number of stages: the consumers' last iteration needs its barrier
+        if (t < nstages) step(set1, t + 1, false);
+        return;
+    }
+    // -------------------------------------------------------------------------------- consumers
+    const int wc = wave % WC, wr = wave / WC;
+    f32x16_t acc[CBW][RBW];
+#pragma unroll
+    for (int a = 0; a < CBW; ++a)
+#pragma unroll
+        for (int b = 0; b < RBW; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    // fragments of global k-step g (4 per stage) in ring position g % AD (a deeper ring, a whole
+    // stage, measured no faster)
+    constexpr int AD = 2;
+    uint4 a[AD][CBW][NS];
+    const int64_t gmax = nstages * 4 - 1;
+    auto load_frags = [&](int64_t g, int pos) {
+        const int64_t gc = g < gmax ? g : gmax;
+#pragma unroll
+        for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+            for (int h = 0; h < NS; ++h)
+                a[pos][cb][h] = afrags[((gc * CB + wc * CBW + cb) * NS + h) * 64 + lane];
+    };
+#pragma unroll
+    for (int g = 0; g < AD; ++g) load_frags(g, g);
+    lds_barrier();
+    for (int64_t t = 0; t < nstages; ++t) {
+        const unsigned char *buf = lds + (t & 1) * kBuf;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint4 b[RBW][NS];
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+                for (int h = 0; h < NS; ++h) {
+                    const int row = (wr * RBW + rb) * 32 + (lane & 31);
+                    b[rb][h] = *reinterpret_cast<const uint4 *>(
+                        buf + (h * kRows + row) * kPPitch + ks * 32 + (lane >> 5) * 16);
+                }
+#pragma unroll
+            for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb)
+                    mfma_split<NS>(a[ks % AD][cb], b[rb], acc[cb][rb]);
+            // requested here and nowhere later: AD k-steps of matrix-core work to come back
+            load_frags(t * 4 + ks + AD, ks % AD);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lds_barrier();
+    }
+#pragma unroll
+    for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
+            const int64_t i = i0 + (wr * RBW + rb) * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int c = (wc * CBW + cb) * 32 + d_row(v, lane);
+                if (c < r && i < m) out[(int64_t)c * m + i] = acc[cb][rb][v];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Q phase:  Q_k[j][c] = sum_i delta_k[i][j] P_hat[c][i].
 // Wavefront: 32 JB columns x all CB basis blocks over its own range of rows.  The B operand
 // (N = column, reduction down the column) is loaded straight from HBM into the operand layout:
@@ -359,7 +512,7 @@ __device__ __forceinline__ void vec_to_array<4>(const float4 &v, float (&out)[4]
     out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
 }
 
-// Used up to 2 basis blocks (r <= 64); above that project_q_lds_kernel below.
+// Used up to 2 basis blocks (r <= 64); above that project_q_ws_kernel below.
 template <int JB>
 __device__ __forceinline__ typename VecOf<JB>::type stream_load_vec(const float *p);
 template <>
@@ -473,126 +626,6 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
                 for (int q = 0; q < JB; ++q) out[(int64_t)c * n + jcol + q] = acc[cb][q][v];
             }
         }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Q phase for 4 or 8 basis blocks (64 < r <= 256), where the matrix cores and the path of the
-// operands to them, not HBM, set the pace.  A workgroup owns 128 columns and sweeps its range of
-// rows in stages of 32 (2 k-steps).  A stage of delta is read once, as 512-byte row segments, and
-// laid down in LDS as fp32; every wavefront then picks the reduction-major operand of each of the
-// four 32-column blocks out of it (8 rows of one column per lane), splits it into bf16 pieces
-// and multiplies it with the CBW basis blocks it owns (a quarter of them), whose fragments only
-// this wavefront fetches.  Stages are double-buffered behind one LDS-only barrier each; nothing
-// is added across wavefronts.
-// ---------------------------------------------------------------------------------------------
-constexpr int kQPitch = 128 + 4;  // floats per LDS row of a stage
-
-template <int NS, int CBW>
-__global__ __launch_bounds__(kW) void project_q_lds_kernel(PtrPack<const float *> deltas,
-                                                           const uint4 *__restrict__ afrags,
-                                                           PtrPack<float *> outs, int64_t m,
-                                                           int64_t n, int r, int64_t ksteps_per_wg,
-                                                           int64_t slab_stride) {
-    constexpr int CB = 4 * CBW;
-    __shared__ __attribute__((aligned(16))) float stage[2][32 * kQPitch];
-    const float *__restrict__ delta = deltas.p[blockIdx.y];
-    float *__restrict__ out = outs.p[blockIdx.y] + (int64_t)blockIdx.z * slab_stride;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t j0 = (int64_t)blockIdx.x * 128;
-    const int64_t s_begin = (int64_t)blockIdx.z * ksteps_per_wg;  // even
-    const int64_t nstages = ksteps_per_wg >> 1;
-
-    f32x16_t acc[CBW][4];
-#pragma unroll
-    for (int a = 0; a < CBW; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
-    // this thread's four float4 of a stage: rows (tid >> 5) + 8 u, columns 4 (tid & 31) .. + 3
-    float4 pre[4];
-    const int prow = tid >> 5, pc4 = tid & 31;
-    const bool col_ok = j0 + pc4 * 4 < n;
-    auto load_stage = [&](int64_t t) {
-        const int64_t i0 = (s_begin + 2 * t) * 16;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t i = i0 + prow + 8 * u;
-            pre[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i < m && col_ok)
-                pre[u] = stream_load4(delta + i * n + j0 + pc4 * 4);
-        }
-    };
-    // this wavefront's basis fragments of a stage, requested before the next stage of delta so
-    // that waiting for them does not wait for that stage as well; with one basis block per
-    // wavefront there are registers to fetch them a whole stage ahead (with two, that would
-    // cost the second wavefront per SIMD)
-    constexpr bool kAhead = CBW == 1;
-    uint4 a[2][CBW][NS];
-    auto load_frags = [&](uint4 (&dst)[2][CBW][NS], int64_t t) {
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int cb = 0; cb < CBW; ++cb)
-#pragma unroll
-                for (int h = 0; h < NS; ++h)
-                    dst[ks][cb][h] =
-                        afrags[(((s_begin + 2 * t + ks) * CB + wave * CBW + cb) * NS + h) * 64 + lane];
-    };
-    if (nstages > 0) {
-        if (kAhead) load_frags(a, 0);
-        load_stage(0);
-    }
-    for (int64_t t = 0; t < nstages; ++t) {
-        float *buf = stage[t & 1];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            *reinterpret_cast<float4 *>(&buf[(prow + 8 * u) * kQPitch + pc4 * 4]) = pre[u];
-        uint4 an[2][CBW][NS];  // unused (and removed by the compiler) unless kAhead
-        if (kAhead) {
-            if (t + 1 < nstages) load_frags(an, t + 1);
-        } else {
-            load_frags(a, t);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (t + 1 < nstages) load_stage(t + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        lds_barrier();
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float x[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    x[e] = buf[(ks * 16 + (lane >> 5) * 8 + e) * kQPitch + q * 32 + (lane & 31)];
-                uint4 b[NS];
-                split8<NS>(x, b);
-#pragma unroll
-                for (int cb = 0; cb < CBW; ++cb) mfma_split<NS>(a[ks][cb], b, acc[cb][q]);
-            }
-        if (kAhead && t + 1 < nstages) {
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int cb = 0; cb < CBW; ++cb)
-#pragma unroll
-                    for (int h = 0; h < NS; ++h) a[ks][cb][h] = an[ks][cb][h];
-        }
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int64_t j = j0 + q * 32 + (lane & 31);
-        if (j >= n) continue;
-#pragma unroll
-        for (int cb = 0; cb < CBW; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int c = (wave * CBW + cb) * 32 + d_row(v, lane);
-                if (c < r) out[(int64_t)c * n + j] = acc[cb][q][v];
-            }
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -975,6 +1008,142 @@ __global__ __launch_bounds__(kW) void round_mfma_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// Q phase for 4 or 8 basis blocks in the two-role form of project_p_ws_kernel.  A workgroup owns
+// 128 columns and a range of rows, swept in stages of 64 rows (4 k-steps).  Producer thread
+// (column quad c4, row group rg) requests 8 rows x 4 columns per stage -- one instruction of a
+// wavefront covers 2 rows x 512 bytes -- and holds, for each of its 4 columns, exactly the 8
+// reduction-consecutive values one lane feeds to the matrix cores: it splits them into bf16
+// pieces and writes them to LDS in operand order, so that a consumer fetches one 16 x 32 operand
+// block of one piece as 1 KB of consecutive LDS.  Consumer wavefront w owns basis blocks
+// w CBW .. and all four 32-column blocks.  Register sets, buffers, barriers and clamping as in
+// the P kernel.
+// ---------------------------------------------------------------------------------------------
+template <int NS, int CBW>
+__global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *> deltas,
+                                                           const uint4 *__restrict__ afrags,
+                                                           PtrPack<float *> outs, int64_t m,
+                                                           int64_t n, int r, int64_t ksteps_per_wg,
+                                                           int64_t slab_stride) {
+    constexpr int CB = 4 * CBW;
+    constexpr int kBuf = 16 * NS * 1024;  // 4 k-steps x 4 column blocks x NS pieces x 1 KB
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const float *__restrict__ delta = deltas.p[blockIdx.y];
+    float *__restrict__ out = outs.p[blockIdx.y] + (int64_t)blockIdx.z * slab_stride;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t j0 = (int64_t)blockIdx.x * 128;
+    const int64_t s_begin = (int64_t)blockIdx.z * ksteps_per_wg;  // a multiple of 4
+    const int64_t nstages = ksteps_per_wg >> 2;
+
+    if (wave >= 4) {  // ---------------------------------------------------------- producers
+        const int tid = threadIdx.x - kW;
+        const int c4 = tid & 31, rg = tid >> 5;
+        const bool col_ok = j0 + c4 * 4 < n;
+        auto load_stage = [&](float4 (&set)[8], int64_t t) {
+            const int64_t tc = t < nstages ? t : nstages - 1;
+            const int64_t i0 = (s_begin + 4 * tc) * 16 + rg * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool ok = col_ok && i0 + e < m;
+                set[e] = stream_load4(ok ? delta + (i0 + e) * n + j0 + c4 * 4 : delta);
+            }
+        };
+        auto store_stage = [&](const float4 (&set)[8], unsigned char *buf, int64_t t) {
+            const int64_t i0 = (s_begin + 4 * t) * 16 + rg * 8;
+            float v[4][8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool ok = col_ok && i0 + e < m;
+                v[0][e] = ok ? set[e].x : 0.f;
+                v[1][e] = ok ? set[e].y : 0.f;
+                v[2][e] = ok ? set[e].z : 0.f;
+                v[3][e] = ok ? set[e].w : 0.f;
+            }
+            // operand block (k-step rg / 2, column block c4 / 8), lane (rg % 2) 32 + column
+            unsigned char *blk = buf + ((rg >> 1) * 4 + (c4 >> 3)) * NS * 1024 +
+                                 ((rg & 1) * 32 + (c4 & 7) * 4) * 16;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                uint4 pieces[NS];
+                split8<NS>(v[x], pieces);
+#pragma unroll
+                for (int h = 0; h < NS; ++h)
+                    *reinterpret_cast<uint4 *>(blk + h * 1024 + x * 16) = pieces[h];
+            }
+        };
+        auto step = [&](float4 (&set)[8], int64_t stage, bool refill) {
+            store_stage(set, lds + (stage & 1) * kBuf, stage);
+            if (refill) load_stage(set, stage + 2);
+            lds_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        float4 set0[8], set1[8];
+        load_stage(set0, 0);
+        load_stage(set1, 1);
+        step(set0, 0, true);
+        int64_t t = 0;
+        for (; t + 1 < nstages; t += 2) {
+            step(set1, t + 1, true);
+            step(set0, t + 2, true);
+        }
+        if (t < nstages) step(set1, t + 1, false);
+        return;
+    }
+    // -------------------------------------------------------------------------------- consumers
+    f32x16_t acc[CBW][4];
+#pragma unroll
+    for (int a = 0; a < CBW; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    uint4 a[2][CBW][NS];  // fragments of k-step g in ring position g & 1
+    const int64_t gmax = s_begin + ksteps_per_wg - 1;
+    auto load_frags = [&](int64_t g, int pos) {
+        const int64_t gc = g < gmax ? g : gmax;
+#pragma unroll
+        for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+            for (int h = 0; h < NS; ++h)
+                a[pos][cb][h] = afrags[((gc * CB + wave * CBW + cb) * NS + h) * 64 + lane];
+    };
+    load_frags(s_begin, 0);
+    load_frags(s_begin + 1, 1);
+    lds_barrier();
+    for (int64_t t = 0; t < nstages; ++t) {
+        const unsigned char *buf = lds + (t & 1) * kBuf;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint4 b[4][NS];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int h = 0; h < NS; ++h)
+                    b[q][h] = *reinterpret_cast<const uint4 *>(buf + ((ks * 4 + q) * NS + h) * 1024 +
+                                                               lane * 16);
+#pragma unroll
+            for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) mfma_split<NS>(a[ks & 1][cb], b[q], acc[cb][q]);
+            load_frags(s_begin + t * 4 + ks + 2, ks & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lds_barrier();
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int64_t j = j0 + q * 32 + (lane & 31);
+        if (j >= n) continue;
+#pragma unroll
+        for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int c = (wave * CBW + cb) * 32 + d_row(v, lane);
+                if (c < r) out[(int64_t)c * n + j] = acc[cb][q][v];
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 static inline int ns_of(int mma) { return mma == DLCX_MMA_F32 ? 3 : 2; }
@@ -993,7 +1162,9 @@ static QPlan q_plan(int64_t m, int64_t n, int r, int K) {
     p.JB = 4;
     p.depth = 2;                           // k-steps (16 rows) of delta in flight per wavefront
     const int64_t col_wgs = ceil_div(n, 32 * p.JB) * K;
-    int64_t S = ceil_div(512, col_wgs);
+    // workgroups wanted: two per compute unit; one at 8 basis blocks, where the two-role kernel
+    // fills a unit by itself
+    int64_t S = ceil_div(cb == 8 ? 256 : 512, col_wgs);
     const int64_t smax = ceil_div(m, 64 * p.depth * 2);  // at least 2 pipeline rounds per wave
     if (S > smax) S = smax;
     if (S < 1) S = 1;
@@ -1046,6 +1217,27 @@ static int project_p_launch(const PtrPack<const float *> &delta, const uint4 *fr
     return DLCX_OK;
 }
 
+template <int NS, int CBW, int WC, int WR, int RB>
+static int project_p_ws_launch(const PtrPack<const float *> &delta, const uint4 *frags,
+                               const PtrPack<float *> &out, int64_t m, int64_t n, int r, int K,
+                               hipStream_t st) {
+    constexpr int lds = 2 * NS * 32 * RB * kPPitch;
+    static bool granted = false;
+    if (lds > 48 * 1024 && !granted) {
+        int rc = note_hip(
+            hipFuncSetAttribute(
+                reinterpret_cast<const void *>(project_p_ws_kernel<NS, CBW, WC, WR, RB>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, lds),
+            "project_p attribute");
+        if (rc != DLCX_OK) return rc;
+        granted = true;
+    }
+    const dim3 grid((unsigned)ceil_div(m, 32 * RB), (unsigned)K);
+    hipLaunchKernelGGL((project_p_ws_kernel<NS, CBW, WC, WR, RB>), grid, dim3(kWs), lds, st, delta,
+                       frags, out, m, n, r);
+    return DLCX_OK;
+}
+
 template <int NS>
 static int project_p_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const float *> &delta,
                         const float *q_in, const PtrPack<float *> &out, void *workspace,
@@ -1059,11 +1251,16 @@ static int project_p_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
     switch (cb) {
         case 1: rc = project_p_launch<NS, 1, 1, 2, 2, 2>(delta, frags, out, m, n, r, K, st); break;
         case 2: rc = project_p_launch<NS, 2, 1, 2, 2, 2>(delta, frags, out, m, n, r, K, st); break;
-        case 4: rc = project_p_launch<NS, 2, 2, 1, 2, 2>(delta, frags, out, m, n, r, K, st); break;
+        case 4:
+            if (ceil_div(m, 128) * K >= 256)
+                rc = project_p_ws_launch<NS, 2, 2, 2, 4>(delta, frags, out, m, n, r, K, st);
+            else
+                rc = project_p_launch<NS, 2, 2, 1, 2, 2>(delta, frags, out, m, n, r, K, st);
+            break;
         default:
             // 128 rows per workgroup once that still gives every compute unit a workgroup
             if (ceil_div(m, 128) * K >= 256)
-                rc = project_p_launch<NS, 2, 4, 1, 1, 4>(delta, frags, out, m, n, r, K, st);
+                rc = project_p_ws_launch<NS, 2, 4, 1, 4>(delta, frags, out, m, n, r, K, st);
             else
                 rc = project_p_launch<NS, 2, 4, 1, 1, 2>(delta, frags, out, m, n, r, K, st);
             break;
@@ -1074,6 +1271,25 @@ static int project_p_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
 
 int launch_sum_slabs(int K, const PtrPack<const float *> &slabs, const PtrPack<float *> &outs,
                      int64_t count, int S, int64_t slab_stride, hipStream_t st);
+
+template <int NS, int CBW>
+static int project_q_ws_launch(const dim3 &grid, hipStream_t st, const PtrPack<const float *> &delta,
+                               const uint4 *frags, const PtrPack<float *> &dst, int64_t m,
+                               int64_t n, int r, int64_t ksteps_per_wg, int64_t slab) {
+    constexpr int lds = 2 * 16 * NS * 1024;
+    static bool granted = false;
+    if (lds > 48 * 1024 && !granted) {
+        int rc = note_hip(
+            hipFuncSetAttribute(reinterpret_cast<const void *>(project_q_ws_kernel<NS, CBW>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds),
+            "project_q attribute");
+        if (rc != DLCX_OK) return rc;
+        granted = true;
+    }
+    hipLaunchKernelGGL((project_q_ws_kernel<NS, CBW>), grid, dim3(kWs), lds, st, delta, frags, dst,
+                       m, n, r, ksteps_per_wg, slab);
+    return DLCX_OK;
+}
 
 template <int NS>
 static int project_q_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const float *> &delta,
@@ -1097,10 +1313,10 @@ static int project_q_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
     switch (cb) {
         case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
         case 2: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 2, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        case 4: hipLaunchKernelGGL((project_q_lds_kernel<NS, 1>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
-        default: hipLaunchKernelGGL((project_q_lds_kernel<NS, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
+        case 4: rc = project_q_ws_launch<NS, 1>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
+        default: rc = project_q_ws_launch<NS, 2>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
     }
-    rc = check_launch("project_q_mfma");
+    if (rc == DLCX_OK) rc = check_launch("project_q_mfma");
     }
     if (rc != DLCX_OK || q.S == 1) return rc;
     PtrPack<const float *> src;
