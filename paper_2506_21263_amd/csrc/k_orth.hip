@@ -107,10 +107,11 @@ int launch_gram_partials_batch(const FactorBatch &batch, hipStream_t st) {
 // in-place inversion of R column by column; w <- diag(scale) R^-1.  A dead column (pivot <=
 // 1e-12, i.e. residual <= 1e-6 of the column norm, or zero norm) gives a zero row of R and a zero
 // column of w.
-constexpr int kCT = 256;
+constexpr int kCT = 256;        // threads, small matrices
+constexpr int kCTLarge = 1024;  // threads once the matrix no longer fits LDS and lives in L2
 constexpr size_t kCholLdsMax = 140 * 1024;
 
-__global__ __launch_bounds__(kCT) void chol_inverse_kernel(FactorBatch batch) {
+__global__ __launch_bounds__(kCTLarge) void chol_inverse_kernel(FactorBatch batch) {
     extern __shared__ double smem[];
     const FactorItem it = batch.it[blockIdx.x];
     const int r = it.r, nchunks = it.nchunks;
@@ -123,20 +124,21 @@ __global__ __launch_bounds__(kCT) void chol_inverse_kernel(FactorBatch batch) {
     __shared__ double dinv[DLCX_MAX_RANK];               // 1 / R_cc (0 for a dead column)
     __shared__ double colbuf[DLCX_MAX_RANK];
     const int tid = threadIdx.x;
+    const int nt = blockDim.x, nty = nt >> 4;            // threads as nty rows of 16
     const int ty = tid >> 4, tx = tid & 15;
-    for (int a = ty; a < r; a += 16)
+    for (int a = ty; a < r; a += nty)
         for (int b = a + tx; b < r; b += 16) {  // sum of the partials in chunk order
             double s = 0.0;
             for (int c = 0; c < nchunks; ++c) s += part[(int64_t)c * r * r + a * r + b];
             g[a * rp + b] = s;
         }
     __syncthreads();
-    for (int c = tid; c < r; c += kCT) {
+    for (int c = tid; c < r; c += nt) {
         const double d = g[c * rp + c];
         dscale[c] = d > 0.0 ? 1.0 / sqrt(d) : 0.0;
     }
     __syncthreads();
-    for (int a = ty; a < r; a += 16)
+    for (int a = ty; a < r; a += nty)
         for (int b = a + tx; b < r; b += 16) g[a * rp + b] *= dscale[a] * dscale[b];
     __syncthreads();
     for (int c = 0; c < r; ++c) {
@@ -145,9 +147,9 @@ __global__ __launch_bounds__(kCT) void chol_inverse_kernel(FactorBatch batch) {
         const double inv = dead ? 0.0 : 1.0 / sqrt(piv);
         __syncthreads();  // everyone has read the pivot
         if (tid == 0) dinv[c] = inv;
-        for (int j = c + tid; j < r; j += kCT) g[c * rp + j] *= inv;  // dead: whole row -> 0
+        for (int j = c + tid; j < r; j += nt) g[c * rp + j] *= inv;  // dead: whole row -> 0
         __syncthreads();
-        for (int i = c + 1 + ty; i < r; i += 16) {
+        for (int i = c + 1 + ty; i < r; i += nty) {
             const double gi = g[c * rp + i];
             for (int j = c + 1 + tx; j < r; j += 16)
                 if (i <= j) g[i * rp + j] -= gi * g[c * rp + j];
@@ -156,10 +158,10 @@ __global__ __launch_bounds__(kCT) void chol_inverse_kernel(FactorBatch batch) {
     }
     // in-place inverse of the upper triangular R: column j from the inverted leading block
     for (int j = 0; j < r; ++j) {
-        for (int l = tid; l < j; l += kCT) colbuf[l] = g[l * rp + j];
+        for (int l = tid; l < j; l += nt) colbuf[l] = g[l * rp + j];
         __syncthreads();
         const double dj = dinv[j];
-        for (int i = tid; i < j; i += kCT) {
+        for (int i = tid; i < j; i += nt) {
             double s = 0.0;
             for (int l = i; l < j; ++l) s = fma(g[i * rp + l], colbuf[l], s);
             g[i * rp + j] = -dj * s;
@@ -167,7 +169,7 @@ __global__ __launch_bounds__(kCT) void chol_inverse_kernel(FactorBatch batch) {
         if (tid == 0) g[j * rp + j] = dj;
         __syncthreads();
     }
-    for (int x = tid; x < r * r; x += kCT) {
+    for (int x = tid; x < r * r; x += nt) {
         const int k = x / r, j = x % r;
         w[x] = k <= j ? dscale[k] * g[k * rp + j] : 0.0;
     }
@@ -233,8 +235,11 @@ static int cholqr_pass(const FactorBatch &batch, hipStream_t st) {
     if (rc != DLCX_OK) return rc;
     {
         Timed timed(KID_CHOL, st);
-        hipLaunchKernelGGL(chol_inverse_kernel, dim3((unsigned)batch.n), dim3(kCT), g_bytes, st,
-                           batch);
+        bool large = false;
+        for (int i = 0; i < batch.n; ++i)
+            large = large || (size_t)batch.it[i].r * (batch.it[i].r + 1) * sizeof(double) > kCholLdsMax;
+        hipLaunchKernelGGL(chol_inverse_kernel, dim3((unsigned)batch.n),
+                           dim3(large ? kCTLarge : kCT), g_bytes, st, batch);
         rc = check_launch("chol_inverse");
     }
     if (rc != DLCX_OK) return rc;
