@@ -171,10 +171,13 @@ int dlcx_ef_update(int K, float *const *ef_inout_host, const float *delta_hat, i
 int dlcx_requantize(float *x_inout, int64_t count, int qbits, int group, void *stream);
 
 /* Measurement aid, not a step of the method: `workgroups` workgroups of 4 wavefronts each issue
- * 8 * iters independent v_mfma_f32_32x32x16_bf16 (32768 flop each) on fixed operands; `out`
- * (workgroups * 256 floats, device) receives the accumulator sums.  Timed with the profiler
- * (kernel "mfma_peak"), it gives the matrix-core rate this GPU attains when nothing competes. */
-int dlcx_mfma_peak_probe(int workgroups, int iters, float *out, void *stream);
+ * 8 * iters independent v_mfma_f32_32x32x16_bf16 (32768 flop each); `out` (workgroups * 256
+ * floats, device) receives the accumulator sums.  Timed with the profiler (kernel "mfma_peak"),
+ * it gives the matrix-core rate this GPU attains when nothing competes.  operands = 0: every
+ * operand element is a small integer (few bits toggle); operands = 1: pseudo-random signs,
+ * exponents and mantissas, four operand pairs in rotation, which is what real data looks like to
+ * the multipliers -- the rate is lower, because the clock follows the power drawn. */
+int dlcx_mfma_peak_probe(int workgroups, int iters, int operands, float *out, void *stream);
 
 /* Communication model of Sec. 2.4.1 (host only).  A ring all-reduce between `clusters` clusters
  * moves 2 (clusters - 1) / clusters of the payload over the link between two of them;

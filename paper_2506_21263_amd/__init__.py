@@ -57,7 +57,7 @@ SYMBOLS = {
                                 C.c_double, _vp, _vp, _int, _vp, _vp, _vp]),
     "dlcx_ef_update": (_int, [_int, _vp, _vp, _i64, _vp]),
     "dlcx_requantize": (_int, [_vp, _i64, _int, _int, _vp]),
-    "dlcx_mfma_peak_probe": (_int, [_int, _int, _vp, _vp]),
+    "dlcx_mfma_peak_probe": (_int, [_int, _int, _int, _vp, _vp]),
     "dlcx_comm_seconds": (C.c_double, [C.c_double, _int, C.c_double]),
     "dlcx_plan_overlap": (_int, [_dp, _int, C.c_double, _i32, _i32, _int, C.c_double, C.c_double,
                                  _i32, _vp, _vp, _vp]),
@@ -233,9 +233,9 @@ def dlcx_ef_update(ef_inout, delta_hat, numel=None, stream=None):
            "dlcx_ef_update")
 
 
-def dlcx_mfma_peak_probe(workgroups, iters, out, stream=None):
-    _check(lib().dlcx_mfma_peak_probe(workgroups, iters, _ptr(out), _stream(stream)),
-           "dlcx_mfma_peak_probe")
+def dlcx_mfma_peak_probe(workgroups, iters, out, random_operands=False, stream=None):
+    _check(lib().dlcx_mfma_peak_probe(workgroups, iters, 1 if random_operands else 0, _ptr(out),
+                                      _stream(stream)), "dlcx_mfma_peak_probe")
 
 
 def dlcx_requantize(x_inout, count, qbits, group, stream=None):

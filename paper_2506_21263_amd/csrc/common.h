@@ -67,7 +67,7 @@ int launch_ef_update(int K, const PtrPack<float *> &ef, const float *d, int64_t 
                      hipStream_t st);
 
 // ---- measurement aid (k_peak.hip) -------------------------------------------------------
-int launch_mfma_peak(int workgroups, int iters, float *out, hipStream_t st);
+int launch_mfma_peak(int workgroups, int iters, int operands, float *out, hipStream_t st);
 
 // ---- rank-r products ------------------------------------------------------------------
 // P_k = delta_k * Q_in   (delta m x n, q_in r x n, out r x m)

@@ -278,10 +278,10 @@ int dlcx_quant_round(int64_t numel, int qbits, int group, int K,
                               has_prev, pc, ps, requant != 0, cs, ss, as_stream(stream));
 }
 
-int dlcx_mfma_peak_probe(int workgroups, int iters, float *out, void *stream) {
+int dlcx_mfma_peak_probe(int workgroups, int iters, int operands, float *out, void *stream) {
     if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24)) return DLCX_EINVAL;
-    if (!out || !aligned16(out)) return DLCX_EINVAL;
-    return launch_mfma_peak(workgroups, iters, out, as_stream(stream));
+    if ((operands != 0 && operands != 1) || !out || !aligned16(out)) return DLCX_EINVAL;
+    return launch_mfma_peak(workgroups, iters, operands, out, as_stream(stream));
 }
 
 int dlcx_ef_update(int K, float *const *ef_inout_host, const float *delta_hat, int64_t numel,

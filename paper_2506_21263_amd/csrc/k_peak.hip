@@ -1,8 +1,11 @@
 // Measurement aid, not a step of the method: the rate at which this GPU retires
 // v_mfma_f32_32x32x16_bf16 when nothing else competes.  Every wavefront keeps 8 independent
-// accumulator tiles and issues `iters` rounds of 8 MFMAs on fixed operands; the sum of the
-// accumulators is written out so that the work cannot be removed.  The result is the
-// denominator for "fraction of the attainable matrix-core rate" beside the datasheet peak.
+// accumulator tiles and issues `iters` rounds of 8 MFMAs on four operand pairs in rotation; the
+// sum of the accumulators is written out so that the work cannot be removed.  With small-integer
+// operands few bits toggle in the multipliers; with pseudo-random signs, exponents and mantissas
+// (what real data looks like) the power drawn is higher and the clock, hence the rate, lower.
+// The two results are the denominators for "fraction of the attainable matrix-core rate" beside
+// the datasheet peak.
 #include "common.h"
 
 namespace dlcx {
@@ -10,22 +13,52 @@ namespace dlcx {
 typedef __bf16 pk_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float pk_f32x16 __attribute__((ext_vector_type(16)));
 
-__global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, float *__restrict__ out) {
+__device__ __forceinline__ uint32_t peak_hash(uint32_t x) {
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+// one bf16: random sign and mantissa, exponent 2^-10 .. 2^-1
+__device__ __forceinline__ uint32_t peak_bf16(uint32_t h) {
+    return ((h & 1u) << 15) | ((0x75u + ((h >> 1) % 10u)) << 7) | ((h >> 8) & 0x7fu);
+}
+
+__global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, int operands,
+                                                        float *__restrict__ out) {
     pk_f32x16 acc[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-    pk_bf16x8 a, b;
+    uint4 ar[4], br[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
-        b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
+    for (int q = 0; q < 4; ++q) {
+        uint32_t w[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t seed = (uint32_t)threadIdx.x * 64u + (uint32_t)q * 8u + (uint32_t)e;
+            if (operands == 0) {  // bf16 small integers: 0..3 and 0..1
+                const uint32_t lo = ((threadIdx.x + e + q) & 3u), hi = ((threadIdx.x * 3 + e) & 1u);
+                const __bf16 a0 = (__bf16)(float)lo, a1 = (__bf16)(float)hi;
+                w[e] = (uint32_t)__builtin_bit_cast(uint16_t, a0) |
+                       ((uint32_t)__builtin_bit_cast(uint16_t, a1) << 16);
+            } else {
+                w[e] = peak_bf16(peak_hash(seed)) | (peak_bf16(peak_hash(seed + 0x9e3779b9u)) << 16);
+            }
+        }
+        ar[q] = make_uint4(w[0], w[1], w[2], w[3]);
+        br[q] = make_uint4(w[4], w[5], w[6], w[7]);
     }
     for (int i = 0; i < iters; ++i) {
 #pragma unroll
         for (int t = 0; t < 8; ++t)
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(pk_bf16x8, ar[t & 3]),
+                __builtin_bit_cast(pk_bf16x8, br[(t + (t >> 2)) & 3]), acc[t], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
@@ -35,9 +68,10 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, float *__rest
     out[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-int launch_mfma_peak(int workgroups, int iters, float *out, hipStream_t st) {
+int launch_mfma_peak(int workgroups, int iters, int operands, float *out, hipStream_t st) {
     Timed timed(KID_MFMA_PEAK, st);
-    hipLaunchKernelGGL(mfma_peak_kernel, dim3((unsigned)workgroups), dim3(256), 0, st, iters, out);
+    hipLaunchKernelGGL(mfma_peak_kernel, dim3((unsigned)workgroups), dim3(256), 0, st, iters,
+                       operands, out);
     return check_launch("mfma_peak");
 }
 
