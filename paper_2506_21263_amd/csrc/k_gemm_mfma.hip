@@ -1014,17 +1014,18 @@ __global__ __launch_bounds__(kW) void round_mfma_kernel(
 // wavefront covers 2 rows x 512 bytes -- and holds, for each of its 4 columns, exactly the 8
 // reduction-consecutive values one lane feeds to the matrix cores: it splits them into bf16
 // pieces and writes them to LDS in operand order, so that a consumer fetches one 16 x 32 operand
-// block of one piece as 1 KB of consecutive LDS.  Consumer wavefront w owns basis blocks
-// w CBW .. and all four 32-column blocks.  Register sets, buffers, barriers and clamping as in
-// the P kernel.
+// block of one piece as 1 KB of consecutive LDS.  The consumers form a WCB x (4 / WCB) grid:
+// wavefront w owns the CBW basis blocks of group w % WCB and WCB of the four 32-column blocks.
+// Register sets, buffers, barriers and clamping as in the P kernel.
 // ---------------------------------------------------------------------------------------------
-template <int NS, int CBW>
+template <int NS, int CBW, int WCB>
 __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *> deltas,
                                                            const uint4 *__restrict__ afrags,
                                                            PtrPack<float *> outs, int64_t m,
                                                            int64_t n, int r, int64_t ksteps_per_wg,
                                                            int64_t slab_stride) {
-    constexpr int CB = 4 * CBW;
+    constexpr int CB = WCB * CBW;
+    constexpr int QW = WCB;               // column blocks per consumer: 4 / (4 / WCB)
     constexpr int kBuf = 16 * NS * 1024;  // 4 k-steps x 4 column blocks x NS pieces x 1 KB
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const float *__restrict__ delta = deltas.p[blockIdx.y];
@@ -1089,11 +1090,12 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
         return;
     }
     // -------------------------------------------------------------------------------- consumers
-    f32x16_t acc[CBW][4];
+    const int wcb = wave % WCB, wq = wave / WCB;
+    f32x16_t acc[CBW][QW];
 #pragma unroll
     for (int a = 0; a < CBW; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < QW; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
     uint4 a[2][CBW][NS];  // fragments of k-step g in ring position g & 1
@@ -1104,7 +1106,7 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
         for (int cb = 0; cb < CBW; ++cb)
 #pragma unroll
             for (int h = 0; h < NS; ++h)
-                a[pos][cb][h] = afrags[((gc * CB + wave * CBW + cb) * NS + h) * 64 + lane];
+                a[pos][cb][h] = afrags[((gc * CB + wcb * CBW + cb) * NS + h) * 64 + lane];
     };
     load_frags(s_begin, 0);
     load_frags(s_begin + 1, 1);
@@ -1113,31 +1115,31 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
         const unsigned char *buf = lds + (t & 1) * kBuf;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            uint4 b[4][NS];
+            uint4 b[QW][NS];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < QW; ++q)
 #pragma unroll
                 for (int h = 0; h < NS; ++h)
-                    b[q][h] = *reinterpret_cast<const uint4 *>(buf + ((ks * 4 + q) * NS + h) * 1024 +
-                                                               lane * 16);
+                    b[q][h] = *reinterpret_cast<const uint4 *>(
+                        buf + ((ks * 4 + wq * QW + q) * NS + h) * 1024 + lane * 16);
 #pragma unroll
             for (int cb = 0; cb < CBW; ++cb)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) mfma_split<NS>(a[ks & 1][cb], b[q], acc[cb][q]);
+                for (int q = 0; q < QW; ++q) mfma_split<NS>(a[ks & 1][cb], b[q], acc[cb][q]);
             load_frags(s_begin + t * 4 + ks + 2, ks & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
         lds_barrier();
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int64_t j = j0 + q * 32 + (lane & 31);
+    for (int q = 0; q < QW; ++q) {
+        const int64_t j = j0 + (wq * QW + q) * 32 + (lane & 31);
         if (j >= n) continue;
 #pragma unroll
         for (int cb = 0; cb < CBW; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int c = (wave * CBW + cb) * 32 + d_row(v, lane);
+                const int c = (wcb * CBW + cb) * 32 + d_row(v, lane);
                 if (c < r) out[(int64_t)c * n + j] = acc[cb][q][v];
             }
     }
@@ -1162,9 +1164,10 @@ static QPlan q_plan(int64_t m, int64_t n, int r, int K) {
     p.JB = 4;
     p.depth = 2;                           // k-steps (16 rows) of delta in flight per wavefront
     const int64_t col_wgs = ceil_div(n, 32 * p.JB) * K;
-    // workgroups wanted: two per compute unit; one at 8 basis blocks, where the two-role kernel
-    // fills a unit by itself
-    int64_t S = ceil_div(cb == 8 ? 256 : 512, col_wgs);
+    // workgroups that run at once: two per compute unit; one at 8 basis blocks, where the
+    // two-role kernel fills a unit by itself
+    const int64_t cap = cb == 8 ? 256 : 512;
+    int64_t S = ceil_div(cap, col_wgs);
     const int64_t smax = ceil_div(m, 64 * p.depth * 2);  // at least 2 pipeline rounds per wave
     if (S > smax) S = smax;
     if (S < 1) S = 1;
@@ -1250,7 +1253,12 @@ static int project_p_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
     Timed timed(KID_PROJECT_P, st);
     switch (cb) {
         case 1: rc = project_p_launch<NS, 1, 1, 2, 2, 2>(delta, frags, out, m, n, r, K, st); break;
-        case 2: rc = project_p_launch<NS, 2, 1, 2, 2, 2>(delta, frags, out, m, n, r, K, st); break;
+        case 2:
+            if (ceil_div(m, 128) * K >= 256)
+                rc = project_p_ws_launch<NS, 1, 2, 2, 4>(delta, frags, out, m, n, r, K, st);
+            else
+                rc = project_p_launch<NS, 2, 1, 2, 2, 2>(delta, frags, out, m, n, r, K, st);
+            break;
         case 4:
             if (ceil_div(m, 128) * K >= 256)
                 rc = project_p_ws_launch<NS, 2, 2, 2, 4>(delta, frags, out, m, n, r, K, st);
@@ -1272,7 +1280,7 @@ static int project_p_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
 int launch_sum_slabs(int K, const PtrPack<const float *> &slabs, const PtrPack<float *> &outs,
                      int64_t count, int S, int64_t slab_stride, hipStream_t st);
 
-template <int NS, int CBW>
+template <int NS, int CBW, int WCB>
 static int project_q_ws_launch(const dim3 &grid, hipStream_t st, const PtrPack<const float *> &delta,
                                const uint4 *frags, const PtrPack<float *> &dst, int64_t m,
                                int64_t n, int r, int64_t ksteps_per_wg, int64_t slab) {
@@ -1280,13 +1288,13 @@ static int project_q_ws_launch(const dim3 &grid, hipStream_t st, const PtrPack<c
     static bool granted = false;
     if (lds > 48 * 1024 && !granted) {
         int rc = note_hip(
-            hipFuncSetAttribute(reinterpret_cast<const void *>(project_q_ws_kernel<NS, CBW>),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(project_q_ws_kernel<NS, CBW, WCB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds),
             "project_q attribute");
         if (rc != DLCX_OK) return rc;
         granted = true;
     }
-    hipLaunchKernelGGL((project_q_ws_kernel<NS, CBW>), grid, dim3(kWs), lds, st, delta, frags, dst,
+    hipLaunchKernelGGL((project_q_ws_kernel<NS, CBW, WCB>), grid, dim3(kWs), lds, st, delta, frags, dst,
                        m, n, r, ksteps_per_wg, slab);
     return DLCX_OK;
 }
@@ -1312,9 +1320,9 @@ static int project_q_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const 
     Timed timed(KID_PROJECT_Q, st);
     switch (cb) {
         case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        case 2: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 2, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
-        case 4: rc = project_q_ws_launch<NS, 1>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
-        default: rc = project_q_ws_launch<NS, 2>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
+        case 2: rc = project_q_ws_launch<NS, 1, 2>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
+        case 4: rc = project_q_ws_launch<NS, 1, 4>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
+        default: rc = project_q_ws_launch<NS, 2, 4>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
     }
     if (rc == DLCX_OK) rc = check_launch("project_q_mfma");
     }
