@@ -118,6 +118,11 @@ SHAPES = [  # (m, n, r, K, group): several tiles and ragged tails in both dimens
     (640, 2048, 96, 2, 128),
     (2048, 512, 256, 1, 64),
     (4096, 320, 200, 8, 64),     # enough workgroups for the 128-row form of the P kernel
+    # the two-role kernels with ragged rows and columns, a partial last stage and a partial last
+    # basis block, at 2, 4 and 8 basis blocks
+    (4240, 208, 40, 8, 16),
+    (4112, 336, 72, 8, 16),
+    (4112, 336, 130, 8, 16),
 ]
 
 
