@@ -537,7 +537,6 @@ __global__ __launch_bounds__(kW) void project_q_mfma_kernel(PtrPack<const float 
                                                             int64_t n, int r,
                                                             int64_t ksteps_per_wave,
                                                             int64_t slab_stride) {
-    typedef typename VecOf<JB>::type vec_t;
     __shared__ float red[CB * JB * 16 * 64];
     const float *__restrict__ delta = deltas.p[blockIdx.y];
     float *__restrict__ out = outs.p[blockIdx.y] + (int64_t)blockIdx.z * slab_stride;
