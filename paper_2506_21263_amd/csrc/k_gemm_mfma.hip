@@ -807,26 +807,17 @@ __global__ __launch_bounds__(kW) void round_mfma_kernel(
         const int64_t j = jt + pc4 * 4;
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
+            // outside the matrix: element 0 instead (what comes back is never used: the new
+            // delta is forced to zero there and nothing is stored), so that no lane branches
             const bool okp = j < n && row0 + 4 * p < m;
-            const int64_t off = (row0 + 4 * p) * n + j;
-            x[p] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (TLBF16) lraw[p] = *reinterpret_cast<const traw_t *>(&x[p]);
-            else lraw[p] = *reinterpret_cast<const traw_t *>(&x[p]);
-            if (okp) {
-                x[p] = stream_load4(ep.ef.p[k] + off);
-                if constexpr (TLBF16)
-                    lraw[p] = stream_load2(reinterpret_cast<const uint16_t *>(ep.tl.p[k]) + off);
-                else
-                    lraw[p] = stream_load4(reinterpret_cast<const float *>(ep.tl.p[k]) + off);
-            }
-            if (with_theta) {
-                tv[p] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (okp) tv[p] = stream_load4(ep.theta + off);
-            }
-            if (with_vel) {
-                vv[p] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (okp) vv[p] = stream_load4(ep.vel + off);
-            }
+            const int64_t off = okp ? (row0 + 4 * p) * n + j : 0;
+            x[p] = stream_load4(ep.ef.p[k] + off);
+            if constexpr (TLBF16)
+                lraw[p] = stream_load2(reinterpret_cast<const uint16_t *>(ep.tl.p[k]) + off);
+            else
+                lraw[p] = stream_load4(reinterpret_cast<const float *>(ep.tl.p[k]) + off);
+            if (with_theta) tv[p] = stream_load4(ep.theta + off);
+            if (with_vel) vv[p] = stream_load4(ep.vel + off);
         }
     };
     const int Kw = ep.K;
