@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per matrix element and launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs of
 # `bench.py --probe --layers 1 --streams 1` (config 2), scaled by a 1 GiB copy in the same run
 # (FETCH_SIZE reads 0.5 KiB per KiB copied, WRITE_SIZE 1.0): profiles/pmc_hbm_traffic_cfg2.txt
-MEASURED_TRAFFIC_BPP = {"round_fused": 61.04, "project_q": 16.76}
+MEASURED_TRAFFIC_BPP = {"round_fused": 60.40, "project_q": 16.76}
 
 
 def log(*a):
