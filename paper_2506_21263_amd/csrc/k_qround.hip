@@ -134,11 +134,13 @@ template <int kQbits, int kLanes, bool kBf16, bool kRequant>
 __global__ __launch_bounds__(kQrThreads) void quant_round_kernel(QRoundArgs a) {
     const int64_t v = (int64_t)blockIdx.x * kQrThreads + threadIdx.x;
     const bool live = v < a.nvec;  // whole groups are live or dead together
+    // a dead lane reads vector 0 instead of skipping its loads behind a per-lane condition (the
+    // loop of loads then is one block that the compiler can issue together); it stores nothing
     const int64_t vc = live ? v : 0;
     const int64_t g = vc / kLanes;
     float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
     if (a.has_prev) {
-        if (live) d = mean4<kQbits>(a.K, a.pcodes, a.pscales, vc, g, a.inv_k, a.exact_inv != 0);
+        d = mean4<kQbits>(a.K, a.pcodes, a.pscales, vc, g, a.inv_k, a.exact_inv != 0);
         if (kRequant) {  // the mean as a q-bit reduction would hand it on
             int c[4];
             float s;
@@ -146,22 +148,16 @@ __global__ __launch_bounds__(kQrThreads) void quant_round_kernel(QRoundArgs a) {
             d = make_float4((float)c[0] * s, (float)c[1] * s, (float)c[2] * s, (float)c[3] * s);
         }
     }
-    float4 t = make_float4(0.f, 0.f, 0.f, 0.f), vel = t;
-    if (live) {
-        t = stream_load4(a.theta + 4 * vc);
-        if (a.has_prev) vel = stream_load4(a.vel + 4 * vc);
-    }
+    float4 t = stream_load4(a.theta + 4 * vc), vel = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (a.has_prev) vel = stream_load4(a.vel + 4 * vc);
     for (int k = 0; k < a.K; ++k) {
-        float4 x = make_float4(0.f, 0.f, 0.f, 0.f), l = x;
-        if (live) {
-            x = stream_load4(a.ef.p[k] + 4 * vc);
-            if (kBf16) {
-                const uint2 b = reinterpret_cast<const uint2 *>(a.tl.p[k])[vc];
-                l = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
-                                __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u));
-            } else {
-                l = reinterpret_cast<const float4 *>(a.tl.p[k])[vc];
-            }
+        float4 x = stream_load4(a.ef.p[k] + 4 * vc), l;
+        if (kBf16) {
+            const uint2 b = reinterpret_cast<const uint2 *>(a.tl.p[k])[vc];
+            l = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
+                            __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u));
+        } else {
+            l = reinterpret_cast<const float4 *>(a.tl.p[k])[vc];
         }
         if (a.has_prev) {  // e = delta - d of the previous step (one fp32 rounding)
             x.x -= d.x;
