@@ -685,33 +685,37 @@ __global__ __launch_bounds__(kW) void reconstruct_mfma_kernel(
                 tile[wave][d_row(v, lane)][nb * 32 + (lane & 31)] = d[nb][v];
         __syncthreads();
         const int64_t j = jt + pc4 * 4;
-        if (jt >= jend || j >= n) continue;
+        const bool col_ok = jt < jend && j < n;
         for (int pass = 0; pass < 8; ++pass) {
             const int row = pass * 4 + prow;
             const int64_t i = ib * 32 + row;
-            if (i >= m) continue;
-            const int64_t off = i * n + j;
+            // outside the matrix a lane reads element 0 (dropped) instead of skipping its loads
+            // behind a per-lane condition, and stores nothing
+            const bool ok = col_ok && i < m;
+            const int64_t off = ok ? i * n + j : 0;
             const float4 dv = *reinterpret_cast<const float4 *>(&tile[wave][row][pc4 * 4]);
-            if (ep.out) *reinterpret_cast<float4 *>(ep.out + off) = dv;
+            if (ep.out) {
+                if (ok) stream_store4(ep.out + off, dv);
+            }
             float4 tv = make_float4(0.f, 0.f, 0.f, 0.f), vv = tv;
-            if (ep.tl_on || ep.apply) tv = *reinterpret_cast<const float4 *>(ep.theta + off);
-            if (ep.apply) vv = *reinterpret_cast<const float4 *>(ep.vel + off);
+            if (ep.tl_on || ep.apply) tv = stream_load4(ep.theta + off);
+            if (ep.apply) vv = stream_load4(ep.vel + off);
             for (int k0 = 0; k0 < ep.K; k0 += 4) {
                 float4 x[4], l[4];
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
                     if (k0 + kk < ep.K) {
-                        x[kk] = *reinterpret_cast<const float4 *>(ep.ef.p[k0 + kk] + off);
+                        x[kk] = stream_load4(ep.ef.p[k0 + kk] + off);
                         if (ep.tl_on) {
                             if (ep.tl_bf16) {
-                                const uint2 bits = *reinterpret_cast<const uint2 *>(
+                                const uint2 bits = stream_load2(
                                     reinterpret_cast<const uint16_t *>(ep.tl.p[k0 + kk]) + off);
                                 l[kk] = make_float4(__uint_as_float(bits.x << 16),
                                                     __uint_as_float(bits.x & 0xFFFF0000u),
                                                     __uint_as_float(bits.y << 16),
                                                     __uint_as_float(bits.y & 0xFFFF0000u));
                             } else {
-                                l[kk] = *reinterpret_cast<const float4 *>(
+                                l[kk] = stream_load4(
                                     reinterpret_cast<const float *>(ep.tl.p[k0 + kk]) + off);
                             }
                         }
@@ -727,11 +731,11 @@ __global__ __launch_bounds__(kW) void reconstruct_mfma_kernel(
                             e.x = (tv.x - l[kk].x) + e.x; e.y = (tv.y - l[kk].y) + e.y;
                             e.z = (tv.z - l[kk].z) + e.z; e.w = (tv.w - l[kk].w) + e.w;
                         }
-                        *reinterpret_cast<float4 *>(ep.ef.p[k0 + kk] + off) = e;
+                        if (ok) stream_store4(ep.ef.p[k0 + kk] + off, e);
                     }
                 }
             }
-            if (ep.apply) {
+            if (ep.apply && ok) {
                 float4 vn, tn;
                 vn.x = fmaf(ep.mu, vv.x, dv.x); vn.y = fmaf(ep.mu, vv.y, dv.y);
                 vn.z = fmaf(ep.mu, vv.z, dv.z); vn.w = fmaf(ep.mu, vv.w, dv.w);
@@ -739,8 +743,8 @@ __global__ __launch_bounds__(kW) void reconstruct_mfma_kernel(
                 tn.y = fmaf(-ep.lr, fmaf(ep.mu, vn.y, dv.y), tv.y);
                 tn.z = fmaf(-ep.lr, fmaf(ep.mu, vn.z, dv.z), tv.z);
                 tn.w = fmaf(-ep.lr, fmaf(ep.mu, vn.w, dv.w), tv.w);
-                *reinterpret_cast<float4 *>(ep.vel + off) = vn;
-                *reinterpret_cast<float4 *>(ep.theta + off) = tn;
+                stream_store4(ep.vel + off, vn);
+                stream_store4(ep.theta + off, tn);
             }
         }
     }
