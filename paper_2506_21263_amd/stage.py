@@ -27,6 +27,34 @@ from . import (PHASE_P, PHASE_Q, desc, dlcx_average, dlcx_batched_workspace_byte
                dlcx_payload_bytes, dlcx_requantize, dlcx_select_rank_from, dlcx_workspace_bytes)
 
 
+def plan_lanes(sizes, nstreams, chunk=0):
+    """Deal matrices (element counts `sizes`, in order) to `nstreams` streams and cut every
+    stream's share into batches.  Returns (lane_of, lane_chunks): lane_of[a] is the stream of
+    matrix a -- consecutive runs with about the same number of elements each, by the position of
+    a matrix's midpoint in the running total -- and lane_chunks[l] the list of half-open index
+    ranges stream l works through: batches of `chunk` matrices (0: the length of the run), the
+    first one cut to (l + 1) / nstreams of that, so that the streams are in different phases of
+    the step (one in its projections while another is in its sweeps)."""
+    total, acc, lane_of = sum(sizes), 0, []
+    for size in sizes:
+        mid = acc + size // 2
+        lane_of.append(min(nstreams - 1, mid * nstreams // max(total, 1)))
+        acc += size
+    lane_chunks = []
+    for lane in range(nstreams):
+        idx = [a for a, l in enumerate(lane_of) if l == lane]
+        lo, hi = (idx[0], idx[-1] + 1) if idx else (0, 0)
+        chunks, a = [], lo
+        size = chunk if chunk > 0 else max(hi - lo, 1)
+        first = max(1, size * (lane + 1) // nstreams)
+        while a < hi:
+            b = min(hi, a + (first if not chunks else size))
+            chunks.append((a, b))
+            a = b
+        lane_chunks.append(chunks)
+    return lane_of, lane_chunks
+
+
 class MatrixState:
     """Device buffers of one weight matrix: outer state, K error buffers, factors, payloads."""
 
@@ -100,29 +128,8 @@ class Stage:
         self.rprime_dev = torch.zeros(len(matrices), device=dev, dtype=torch.int32)
         self.batched = batched
         self.serial = False
-        # lanes: consecutive runs of matrices with about the same number of elements each
-        total, acc, self.lane_of = sum(m.m * m.n for m in matrices), 0, []
-        for M in matrices:
-            mid = acc + M.m * M.n // 2
-            self.lane_of.append(min(self.nstreams - 1, mid * self.nstreams // total))
-            acc += M.m * M.n
-        self.lane_ranges = []
-        for lane in range(self.nstreams):
-            idx = [a for a, l in enumerate(self.lane_of) if l == lane]
-            self.lane_ranges.append((idx[0], idx[-1] + 1) if idx else (0, 0))
-        # a lane works through its run in chunks of `chunk` matrices (0: the length of the run),
-        # the first chunk of lane l cut to (l + 1) / nstreams of that, so that the lanes are in
-        # different phases of the step (one in its projections while another is in its sweeps)
-        self.lane_chunks = []
-        for lane, (lo, hi) in enumerate(self.lane_ranges):
-            chunks, a = [], lo
-            size = chunk if chunk > 0 else max(hi - lo, 1)
-            first = max(1, size * (lane + 1) // self.nstreams)
-            while a < hi:
-                b = min(hi, a + (first if not chunks else size))
-                chunks.append((a, b))
-                a = b
-            self.lane_chunks.append(chunks)
+        self.lane_of, self.lane_chunks = plan_lanes([M.m * M.n for M in matrices],
+                                                    self.nstreams, chunk)
         self.batch_ws = [None] * self.nstreams
         if batched:
             for lane, chunks in enumerate(self.lane_chunks):

@@ -137,3 +137,31 @@ def test_comm_model_and_overlap_plan_on_the_host(golden):
             assert abs(got[2] - want[2]) <= 1e-12 * max(want[2], 1.0)
     with pytest.raises(dlcx.DlcxError):
         dlcx.dlcx_plan_overlap([dlcx.desc(512, 512, 1, 4, 64)], 0.0, 8, 4, 3, 1e9, 1.0, 1)
+
+
+def test_stage_lane_plan_covers_every_matrix_once_and_balances():
+    # host-side scheduling of a stage: consecutive runs per stream, batches inside a run
+    from paper_2506_21263_amd.stage import plan_lanes
+    layer = [8192 * 8192, 8192 * 1024, 8192 * 1024, 8192 * 8192, 8192 * 28672, 8192 * 28672,
+             28672 * 8192]
+    cases = [(layer * 10, 3, 0), (layer * 10, 3, 4), (layer * 10, 1, 0), (layer * 5, 4, 7),
+             ([5, 1, 1, 1], 3, 0), ([1], 3, 2), ([7] * 5, 2, 2)]
+    for sizes, ns, chunk in cases:
+        lane_of, lane_chunks = plan_lanes(sizes, ns, chunk)
+        assert len(lane_of) == len(sizes) and len(lane_chunks) == ns
+        assert lane_of == sorted(lane_of)                       # consecutive runs
+        covered = [a for chunks in lane_chunks for lo, hi in chunks for a in range(lo, hi)]
+        assert covered == list(range(len(sizes)))               # every matrix exactly once
+        for lane, chunks in enumerate(lane_chunks):
+            assert all(lane_of[a] == lane for lo, hi in chunks for a in range(lo, hi))
+            assert all(hi > lo for lo, hi in chunks)
+            assert all(c[1] == d[0] for c, d in zip(chunks, chunks[1:]))
+            if chunk > 0:
+                assert all(hi - lo <= chunk for lo, hi in chunks)
+    lane_of, lane_chunks = plan_lanes(layer * 10, 3, 0)
+    share = [sum(s for s, l in zip(layer * 10, lane_of) if l == lane) for lane in range(3)]
+    assert max(share) <= 1.15 * min(share)                      # about equal element counts
+    # streams out of phase: first batches of 1/3, 2/3 and all of a run
+    firsts = [c[0][1] - c[0][0] for c in lane_chunks]
+    runs = [c[-1][1] - c[0][0] for c in lane_chunks]
+    assert firsts == [max(1, runs[l] * (l + 1) // 3) for l in range(3)]
