@@ -19,6 +19,23 @@
 // 1 KB of consecutive memory; fragments are read straight from L2 into registers.  The big
 // operand delta is staged through LDS (P phase, reduction along a row) or loaded straight into
 // the operand layout with 128-byte row segments (Q phase, reduction down a column).
+//
+// Kernels in this file:
+//   pack_kcontig_kernel / pack_kstrided_kernel   fragments of a basis / of a factor
+//   project_p_mfma_kernel, project_q_mfma_kernel  projections, every wavefront does everything
+//                                                 (r <= 32, and P for matrices with few rows)
+//   project_p_ws_kernel, project_q_ws_kernel      projections with producer and consumer
+//                                                 wavefronts (r > 32)
+//   reconstruct_mfma_kernel                       Delta_hat tile by tile with the elementwise
+//                                                 steps of Alg. 2 fused in (any rank)
+//   round_mfma_kernel                             the same plus the P phase of the next
+//                                                 compression: the benchmark's hot kernel (r <= 64)
+// Two things learnt on this hardware shape all of them.  A wavefront's loads return in order, so
+// a wait for something needed soon (a fragment from L2) also waits for everything requested
+// before it (delta from HBM, needed much later): requests are issued in the order of need, or
+// the two kinds of load are given to different wavefronts.  And a load behind a per-lane
+// condition cuts the loop into small blocks that the compiler schedules one by one: lanes
+// outside the matrix read a valid address instead and the value is dropped.
 #include <type_traits>
 
 #include "common.h"
