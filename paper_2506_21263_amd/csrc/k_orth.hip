@@ -123,6 +123,7 @@ __global__ __launch_bounds__(kCTLarge) void chol_inverse_kernel(FactorBatch batc
     __shared__ double dscale[DLCX_MAX_RANK];             // 1 / column norm (0 for a zero column)
     __shared__ double dinv[DLCX_MAX_RANK];               // 1 / R_cc (0 for a dead column)
     __shared__ double colbuf[DLCX_MAX_RANK];
+    __shared__ double psum[(kCTLarge / 256) * 256];      // shares of the inverse's sums
     const int tid = threadIdx.x;
     const int nt = blockDim.x, nty = nt >> 4;            // threads as nty rows of 16
     const int ty = tid >> 4, tx = tid & 15;
@@ -156,17 +157,26 @@ __global__ __launch_bounds__(kCTLarge) void chol_inverse_kernel(FactorBatch batc
         }
         __syncthreads();
     }
-    // in-place inverse of the upper triangular R: column j from the inverted leading block
-    for (int j = 0; j < r; ++j) {
-        for (int l = tid; l < j; l += nt) colbuf[l] = g[l * rp + j];
+    // W = R^-1 in place by back substitution, row by row from the bottom (R W = I: the columns
+    // of W are independent, and the rows below row i already hold W).  Row i of R is staged;
+    // thread (group, j) adds its share of sum_{l = i+1 .. j} R[i][l] W[l][j], the shares are added
+    // in a fixed order, and W[i][j] = -sum / R[i][i] (1 / R[i][i] on the diagonal, 0 for a dead
+    // row).  Every access to the matrix in the sum is a row read by consecutive threads.
+    const int parts = nt >> 8;  // 1 or 4 groups of 256 threads
+    const int jcol = tid & 255, grp = tid >> 8;
+    for (int i = r - 1; i >= 0; --i) {
+        for (int l = i + 1 + tid; l < r; l += nt) colbuf[l] = g[i * rp + l];
         __syncthreads();
-        const double dj = dinv[j];
-        for (int i = tid; i < j; i += nt) {
-            double s = 0.0;
-            for (int l = i; l < j; ++l) s = fma(g[i * rp + l], colbuf[l], s);
-            g[i * rp + j] = -dj * s;
+        double s = 0.0;
+        if (jcol < r && jcol > i)
+            for (int l = i + 1 + grp; l <= jcol; l += parts)
+                s = fma(colbuf[l], g[l * rp + jcol], s);
+        if (parts > 1) {
+            psum[grp * 256 + jcol] = s;
+            __syncthreads();
+            if (grp == 0) s = ((psum[jcol] + psum[256 + jcol]) + psum[512 + jcol]) + psum[768 + jcol];
         }
-        if (tid == 0) g[j * rp + j] = dj;
+        if (grp == 0 && jcol < r && jcol >= i) g[i * rp + jcol] = jcol == i ? dinv[i] : -dinv[i] * s;
         __syncthreads();
     }
     for (int x = tid; x < r * r; x += nt) {
@@ -176,10 +186,13 @@ __global__ __launch_bounds__(kCTLarge) void chol_inverse_kernel(FactorBatch batc
 }
 
 // P <- P W in place, fp64 accumulation.  Workgroup: 64 rows of P (= 64 consecutive elements of
-// every factor column) staged in LDS; thread (row, wave) produces the columns c = wave, wave+4,..
-// W is upper triangular: column c needs rows k <= c only.
+// every factor column) staged in LDS; W goes through LDS as well, 16 columns at a time (a
+// wavefront's reads of it are broadcasts; straight from memory every one was a round trip to
+// L2); thread (row, wave) produces 4 of the 16 columns.  W is upper triangular and stored with
+// zeros below the diagonal: column c needs rows k <= c only, and running k up to the last of the
+// thread's four columns adds exact zeros to the others.
 __global__ __launch_bounds__(kGT) void apply_w_kernel(FactorBatch batch) {
-    extern __shared__ float fl[];  // [r][64]
+    extern __shared__ float fl[];  // [r][64] floats, then [r][16] doubles of W
     const FactorItem it = batch.it[blockIdx.y];
     float *__restrict__ p = it.f;
     const double *__restrict__ w = it.w;
@@ -196,10 +209,28 @@ __global__ __launch_bounds__(kGT) void apply_w_kernel(FactorBatch batch) {
     __syncthreads();
     const int row = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    for (int c = wave; c < r; c += 4) {
-        double acc = 0.0;
-        for (int k = 0; k <= c; ++k) acc = fma((double)fl[k * 64 + row], w[k * r + c], acc);
-        if (i0 + row < L) p[(int64_t)c * L + i0 + row] = (float)acc;
+    double *wl = reinterpret_cast<double *>(fl + (size_t)r * 64);
+    for (int c0 = 0; c0 < r; c0 += 16) {
+        const int kmax = c0 + 15 < r ? c0 + 15 : r - 1;
+        for (int idx = threadIdx.x; idx < (kmax + 1) * 16; idx += kGT) {
+            const int k = idx >> 4, ci = idx & 15;
+            wl[idx] = c0 + ci < r ? w[k * r + c0 + ci] : 0.0;
+        }
+        __syncthreads();
+        const int cw = c0 + wave * 4;  // this wavefront's four columns
+        if (cw < r) {
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            const int kend = cw + 3 < r ? cw + 3 : r - 1;
+            for (int k = 0; k <= kend; ++k) {
+                const double f = (double)fl[k * 64 + row];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] = fma(f, wl[k * 16 + wave * 4 + i], acc[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (cw + i < r && i0 + row < L) p[(int64_t)(cw + i) * L + i0 + row] = (float)acc[i];
+        }
+        __syncthreads();  // the tile of W is free again
     }
 }
 
@@ -226,7 +257,8 @@ static int cholqr_pass(const FactorBatch &batch, hipStream_t st) {
         const size_t r = (size_t)batch.it[i].r;
         const size_t gb = r * (r + 1) * sizeof(double);
         if (gb <= kCholLdsMax && gb > g_bytes) g_bytes = gb;
-        if (r * 64 * sizeof(float) > a_bytes) a_bytes = r * 64 * sizeof(float);
+        const size_t ab = r * 64 * sizeof(float) + r * 16 * sizeof(double);
+        if (ab > a_bytes) a_bytes = ab;
         if (ceil_div(batch.it[i].L, 64) > max_rows) max_rows = ceil_div(batch.it[i].L, 64);
     }
     static size_t chol_granted = 0, apply_granted = 0;
