@@ -186,13 +186,15 @@ double dlcx_comm_seconds(double payload_bytes, int clusters, double bits_per_sec
 
 /* Choice of (rank, local steps) that just hides the exchange of one outer step behind local
  * training (the one-step-delay overlap of Sec. 2.3 needs comm <= H * step time).  The payload
- * of a worker at rank r is the sum over the n_matrices descriptors of both quantised factors
- * (r clipped to each matrix's smaller side) plus extra_bytes (tensors sent without low-rank).
+ * of a worker at rank r is power_iters times the sum over the n_matrices descriptors of both
+ * quantised factors (r clipped to each matrix's smaller side; every power iteration of a round
+ * sends both factors again, 1 in the paper) plus extra_bytes (tensors sent without low-rank).
  * *r_out is the largest rank in [rmin, rmax] whose exchange fits H * step_seconds and *H_out = H;
  * if not even rmin fits, *r_out = rmin and *H_out is the smallest H that hides it.
  * *comm_seconds_out is the exchange time at the chosen rank.  Host only. */
 int dlcx_plan_overlap(const dlcx_desc *descs_host, int n_matrices, double extra_bytes,
-                      int32_t rmin, int32_t rmax, int clusters, double bits_per_second,
+                      int power_iters, int32_t rmin, int32_t rmax, int clusters,
+                      double bits_per_second,
                       double step_seconds, int32_t H, int32_t *r_out, int32_t *H_out,
                       double *comm_seconds_out);
 

@@ -23,24 +23,25 @@ def factor_payload_bytes(m, n, r, qbits, group):
     return total
 
 
-def stage_payload_bytes(shapes, r, qbits, group, extra_bytes=0):
-    return extra_bytes + sum(factor_payload_bytes(m, n, min(r, m, n), qbits, group)
-                             for m, n in shapes)
+def stage_payload_bytes(shapes, r, qbits, group, extra_bytes=0, iters=1):
+    """What one worker sends per outer step: both factors of every matrix once per power
+    iteration of the round, plus the tensors sent without low-rank."""
+    return extra_bytes + iters * sum(factor_payload_bytes(m, n, min(r, m, n), qbits, group)
+                                     for m, n in shapes)
 
 
 def plan_overlap(shapes, qbits, group, extra_bytes, rmin, rmax, clusters, bits_per_second,
-                 step_seconds, H):
+                 step_seconds, H, iters=1):
     """Largest rank whose exchange hides behind H local steps; if none does, rmin and the
     smallest H that hides it.  Exhaustive over the ranks."""
-    fits = [r for r in range(rmin, rmax + 1)
-            if comm_seconds(stage_payload_bytes(shapes, r, qbits, group, extra_bytes), clusters,
-                            bits_per_second) <= H * step_seconds]
+    def seconds(r):
+        return comm_seconds(stage_payload_bytes(shapes, r, qbits, group, extra_bytes, iters),
+                            clusters, bits_per_second)
+    fits = [r for r in range(rmin, rmax + 1) if seconds(r) <= H * step_seconds]
     if fits:
         r = max(fits)
-        return r, H, comm_seconds(stage_payload_bytes(shapes, r, qbits, group, extra_bytes),
-                                  clusters, bits_per_second)
-    t = comm_seconds(stage_payload_bytes(shapes, rmin, qbits, group, extra_bytes), clusters,
-                     bits_per_second)
+        return r, H, seconds(r)
+    t = seconds(rmin)
     h = 1
     while h * step_seconds < t:
         h += 1

@@ -59,8 +59,8 @@ SYMBOLS = {
     "dlcx_requantize": (_int, [_vp, _i64, _int, _int, _vp]),
     "dlcx_mfma_peak_probe": (_int, [_int, _int, _int, _vp, _vp]),
     "dlcx_comm_seconds": (C.c_double, [C.c_double, _int, C.c_double]),
-    "dlcx_plan_overlap": (_int, [_dp, _int, C.c_double, _i32, _i32, _int, C.c_double, C.c_double,
-                                 _i32, _vp, _vp, _vp]),
+    "dlcx_plan_overlap": (_int, [_dp, _int, C.c_double, _int, _i32, _i32, _int, C.c_double,
+                                 C.c_double, _i32, _vp, _vp, _vp]),
     "dlcx_select_rank": (_int, [_dp, _vp, _int, C.c_double, _vp, _i32, _i32, _i32, _i32, _i32,
                                 _i32, _vp, _vp, _vp, _vp, _vp]),
     "dlcx_select_rank_from": (_int, [_vp, _int, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp,
@@ -247,14 +247,15 @@ def dlcx_comm_seconds(payload_bytes, clusters, bits_per_second):
     return lib().dlcx_comm_seconds(payload_bytes, clusters, bits_per_second)
 
 
-def dlcx_plan_overlap(descs, extra_bytes, rmin, rmax, clusters, bits_per_second, step_seconds, H):
+def dlcx_plan_overlap(descs, extra_bytes, rmin, rmax, clusters, bits_per_second, step_seconds, H,
+                      power_iters=1):
     """Returns (rank, H, seconds of the exchange at that rank).  Host only."""
     n = len(descs)
     arr = (Desc * max(n, 1))(*descs)
     r, h, t = _i32(0), _i32(0), C.c_double(0.0)
-    _check(lib().dlcx_plan_overlap(arr, n, extra_bytes, rmin, rmax, clusters, bits_per_second,
-                                   step_seconds, H, C.addressof(r), C.addressof(h),
-                                   C.addressof(t)), "dlcx_plan_overlap")
+    _check(lib().dlcx_plan_overlap(arr, n, extra_bytes, power_iters, rmin, rmax, clusters,
+                                   bits_per_second, step_seconds, H, C.addressof(r),
+                                   C.addressof(h), C.addressof(t)), "dlcx_plan_overlap")
     return r.value, h.value, t.value
 
 

@@ -311,23 +311,25 @@ double dlcx_comm_seconds(double payload_bytes, int clusters, double bits_per_sec
     return between * 8.0 / bits_per_second;
 }
 
-static double stage_payload_bytes(const dlcx_desc *descs, int n, int32_t r, double extra) {
-    double total = extra;
+static double stage_payload_bytes(const dlcx_desc *descs, int n, int32_t r, double extra,
+                                  int iters) {
+    double factors = 0.0;
     for (int a = 0; a < n; ++a) {
         dlcx_desc d = descs[a];
         const int64_t side = d.m < d.n ? d.m : d.n;
         d.r = r < side ? r : (int32_t)side;
-        total += (double)dlcx_payload_bytes(&d, DLCX_PHASE_P, nullptr, nullptr);
-        total += (double)dlcx_payload_bytes(&d, DLCX_PHASE_Q, nullptr, nullptr);
+        factors += (double)dlcx_payload_bytes(&d, DLCX_PHASE_P, nullptr, nullptr);
+        factors += (double)dlcx_payload_bytes(&d, DLCX_PHASE_Q, nullptr, nullptr);
     }
-    return total;
+    return extra + (double)iters * factors;
 }
 
 int dlcx_plan_overlap(const dlcx_desc *descs_host, int n_matrices, double extra_bytes,
-                      int32_t rmin, int32_t rmax, int clusters, double bits_per_second,
-                      double step_seconds, int32_t H, int32_t *r_out, int32_t *H_out,
-                      double *comm_seconds_out) {
+                      int power_iters, int32_t rmin, int32_t rmax, int clusters,
+                      double bits_per_second, double step_seconds, int32_t H, int32_t *r_out,
+                      int32_t *H_out, double *comm_seconds_out) {
     if (n_matrices < 0 || (n_matrices > 0 && !descs_host) || !(extra_bytes >= 0.0)) return DLCX_EINVAL;
+    if (power_iters < 1 || power_iters > 1024) return DLCX_EINVAL;
     if (rmin < 1 || rmax < rmin || rmax > DLCX_MAX_RANK || clusters < 1 || H < 1) return DLCX_EINVAL;
     if (!(bits_per_second > 0.0) || !(step_seconds > 0.0)) return DLCX_EINVAL;
     if (!r_out || !H_out || !comm_seconds_out) return DLCX_EINVAL;
@@ -339,8 +341,9 @@ int dlcx_plan_overlap(const dlcx_desc *descs_host, int n_matrices, double extra_
     const double budget = (double)H * step_seconds;
     int32_t best = 0;
     for (int32_t r = rmin; r <= rmax; ++r) {  // the payload grows with r: keep the last that fits
-        const double t = dlcx_comm_seconds(stage_payload_bytes(descs_host, n_matrices, r, extra_bytes),
-                                           clusters, bits_per_second);
+        const double t = dlcx_comm_seconds(
+            stage_payload_bytes(descs_host, n_matrices, r, extra_bytes, power_iters), clusters,
+            bits_per_second);
         if (t <= budget) best = r;
         else break;
     }
@@ -348,11 +351,13 @@ int dlcx_plan_overlap(const dlcx_desc *descs_host, int n_matrices, double extra_
         *r_out = best;
         *H_out = H;
         *comm_seconds_out = dlcx_comm_seconds(
-            stage_payload_bytes(descs_host, n_matrices, best, extra_bytes), clusters, bits_per_second);
+            stage_payload_bytes(descs_host, n_matrices, best, extra_bytes, power_iters), clusters,
+            bits_per_second);
         return DLCX_OK;
     }
-    const double t = dlcx_comm_seconds(stage_payload_bytes(descs_host, n_matrices, rmin, extra_bytes),
-                                       clusters, bits_per_second);
+    const double t = dlcx_comm_seconds(
+        stage_payload_bytes(descs_host, n_matrices, rmin, extra_bytes, power_iters), clusters,
+        bits_per_second);
     double h = t / step_seconds;
     int64_t hi = (int64_t)h;
     if ((double)hi < h) ++hi;

@@ -130,13 +130,16 @@ def test_comm_model_and_overlap_plan_on_the_host(golden):
     shapes = [(8192, 8192), (8192, 1024), (8192, 28672), (28672, 8192), (512, 256)]
     for qbits, group in ((4, 128), (8, 64)):
         descs = [dlcx.desc(m, n, 1, qbits, group) for m, n in shapes]
-        for step, H, extra in ((0.05, 1, 0.0), (0.05, 3, 1e6), (1e-3, 1, 0.0), (10.0, 1, 0.0)):
-            want = planner.plan_overlap(shapes, qbits, group, extra, 4, 256, 3, 1e9, step, H)
-            got = dlcx.dlcx_plan_overlap(descs, extra, 4, 256, 3, 1e9, step, H)
+        for step, H, extra, iters in ((0.05, 1, 0.0, 1), (0.05, 3, 1e6, 1), (1e-3, 1, 0.0, 1),
+                                      (10.0, 1, 0.0, 1), (0.05, 1, 0.0, 2), (0.05, 3, 1e6, 3)):
+            want = planner.plan_overlap(shapes, qbits, group, extra, 4, 256, 3, 1e9, step, H, iters)
+            got = dlcx.dlcx_plan_overlap(descs, extra, 4, 256, 3, 1e9, step, H, iters)
             assert got[:2] == want[:2]
             assert abs(got[2] - want[2]) <= 1e-12 * max(want[2], 1.0)
     with pytest.raises(dlcx.DlcxError):
         dlcx.dlcx_plan_overlap([dlcx.desc(512, 512, 1, 4, 64)], 0.0, 8, 4, 3, 1e9, 1.0, 1)
+    with pytest.raises(dlcx.DlcxError):
+        dlcx.dlcx_plan_overlap([dlcx.desc(512, 512, 1, 4, 64)], 0.0, 4, 8, 3, 1e9, 1.0, 1, 0)
 
 
 def test_stage_lane_plan_covers_every_matrix_once_and_balances():

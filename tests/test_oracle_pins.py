@@ -610,6 +610,10 @@ def test_overlap_plan_is_the_largest_rank_that_hides():
     # nothing fits: rmin and the smallest H that hides it
     r3, H3, t3 = planner.plan_overlap(shapes, step_seconds=1e-3, H=1, **args)
     assert r3 == 4 and (H3 - 1) * 1e-3 < t3 <= H3 * 1e-3
+    # two power iterations per round send every factor twice: the rank that hides is the one a
+    # single iteration would get from half the budget (no other payload here)
+    r_it2, _, t_it2 = planner.plan_overlap(shapes, step_seconds=0.05, H=2, iters=2, **args)
+    assert r_it2 == r and abs(t_it2 - 2 * t) < 1e-12
     # factor payload accounting against the transmitted-factors reading (r = 2048 is about 2x)
     full = 8192 * 8192 * 2                       # FP16 bytes of one 8192 x 8192 matrix
     fac = planner.factor_payload_bytes(8192, 8192, 2048, 8, 128)
