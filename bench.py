@@ -30,7 +30,7 @@ def log(*a):
 
 
 def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, workers=0, iters=1,
-                chunk=0):
+                chunk=0, requant=False):
     """plain=True draws i.i.d. Gaussian replicas instead of the low-rank-plus-noise recipe (no
     library QR/GEMM kernels in the process: used for hardware-counter runs, where only the
     traffic of this library's kernels is of interest)."""
@@ -68,7 +68,7 @@ def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, worker
         log("generated layer %d/%d  (%.1f s, %.1f GB allocated)" %
             (layer + 1, layers, time.time() - t0, torch.cuda.memory_allocated() / 1e9))
     stage = Stage(mats, synth.LR, synth.MU, fused=fused, warm_start=True, streams=streams,
-                  measure_rank=True, iters=iters, chunk=chunk)
+                  measure_rank=True, iters=iters, chunk=chunk, requant=requant)
     return stage, locals_
 
 
@@ -111,7 +111,7 @@ def cpu_baseline(stage, locals_, cfg_id):
         else:
             tl.append(x.cpu().numpy())
     orc = pipeline.MatrixOracle(theta, M.K, q_in, cfg["qbits"], cfg["group"], synth.LR, synth.MU,
-                                iters=stage.iters)
+                                iters=stage.iters, requant=stage.requant)
     t0 = time.time()
     steps = 0
     while steps < 2 or (time.time() - t0) * (steps + 1) / steps < 12.0:
@@ -288,7 +288,8 @@ def main():
     ap.add_argument("--quant-only", action="store_true",
                     help="quantiser as the whole compressor (no low-rank step), all tensors flat")
     ap.add_argument("--requant", action="store_true",
-                    help="quantise-only mode: re-encode the average to q bits")
+                    help="re-encode every average (factors, or the tensor in quantise-only mode) "
+                         "to q bits before it is used")
     ap.add_argument("--chunk", type=int, default=0,
                     help="matrices per batch of a stream (0 = the stream's whole share at once)")
     ap.add_argument("--power-iters", type=int, default=1,
@@ -326,7 +327,7 @@ def main():
     fused = not args.unfused
     stage, locals_ = build_stage(args.config, args.mma, layers, device, fused, args.streams,
                                  plain=args.probe, workers=args.workers, iters=args.power_iters,
-                                 chunk=args.chunk)
+                                 chunk=args.chunk, requant=args.requant)
     if args.probe:
         x = torch.empty(1 << 28, dtype=torch.float32, device=device)
         y = torch.empty_like(x)
@@ -454,7 +455,7 @@ def main():
                    "params": params, "K": K, "rank": cfg["r"], "qbits": cfg["qbits"],
                    "group": cfg["group"], "theta_l": cfg["theta_l"], "mma": args.mma,
                    "fused": fused, "streams": stage.nstreams, "hip_graph": use_graph["on"],
-                   "power_iters": args.power_iters},
+                   "power_iters": args.power_iters, "requant": bool(args.requant)},
         "roofline": roofline,
         "stage_hbm": {"algorithmic_bytes_per_param": b_alg,
                       "achieved_GBps": b_alg * params / (dt / args.steps) / 1e9,
