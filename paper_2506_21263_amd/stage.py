@@ -242,26 +242,29 @@ class Stage:
         # each lane batches its own matrices: the latency-bound batched kernels of one lane run
         # beside the HBM-bound sweeps of the others, and no lane waits for another inside a step
         main = self._fork()
-        for lane, chunks in enumerate(self.lane_chunks):
-            for lo, hi in chunks:
-                _, st = self._lane(lo)
-                mats = self.mats[lo:hi]
-                descs = [M.desc() for M in mats]
-                for j in range(self.iters):
-                    for a in range(lo, hi):
-                        if j == 0:
-                            self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st,
-                                                    orthonormalize=False)
-                        else:
-                            self._p_phase_again(a, lane, st, orthonormalize=False)
-                    dlcx_orthonormalize_batched(descs, [M.p_hat for M in mats],
-                                                self.batch_ws[lane], stream=st)
-                    for a in range(lo, hi):
-                        self._q_phase(a, lane, st, rank=False)
-                if self.measure_rank:
-                    dlcx_effective_rank_batched(descs, [M.q_bar for M in mats], self.tau,
-                                                self.rprime_dev[lo:], self.batch_ws[lane],
-                                                stream=st)
+        # batches are issued round-robin over the lanes (each lane's own in order), so that every
+        # stream has work queued from the start of the step
+        order = [(lane, chunks[c]) for c in range(max(len(x) for x in self.lane_chunks))
+                 for lane, chunks in enumerate(self.lane_chunks) if c < len(chunks)]
+        for lane, (lo, hi) in order:
+            _, st = self._lane(lo)
+            mats = self.mats[lo:hi]
+            descs = [M.desc() for M in mats]
+            for j in range(self.iters):
+                for a in range(lo, hi):
+                    if j == 0:
+                        self._begin_and_p_phase(a, theta_l_per_matrix[a], lane, st,
+                                                orthonormalize=False)
+                    else:
+                        self._p_phase_again(a, lane, st, orthonormalize=False)
+                dlcx_orthonormalize_batched(descs, [M.p_hat for M in mats],
+                                            self.batch_ws[lane], stream=st)
+                for a in range(lo, hi):
+                    self._q_phase(a, lane, st, rank=False)
+            if self.measure_rank:
+                dlcx_effective_rank_batched(descs, [M.q_bar for M in mats], self.tau,
+                                            self.rprime_dev[lo:], self.batch_ws[lane],
+                                            stream=st)
         self._join(main)
 
 
