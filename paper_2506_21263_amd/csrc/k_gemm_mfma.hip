@@ -1071,15 +1071,19 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
                 v[3][e] = ok ? set[e].w : 0.f;
             }
             // operand block (k-step rg / 2, column block c4 / 8), lane (rg % 2) 32 + column
+            // (the two low bits of the lane slot are swizzled so that the 16 lanes of one LDS
+            // pass, which differ in c4, fall on 16 different bank groups; a consumer reads the
+            // 64 slots of a block in the same permutation)
             unsigned char *blk = buf + ((rg >> 1) * 4 + (c4 >> 3)) * NS * 1024 +
                                  ((rg & 1) * 32 + (c4 & 7) * 4) * 16;
+            const int sw = (((c4 >> 2) & 1) << 1) | ((c4 >> 3) & 1);
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 uint4 pieces[NS];
                 split8<NS>(v[x], pieces);
 #pragma unroll
                 for (int h = 0; h < NS; ++h)
-                    *reinterpret_cast<uint4 *>(blk + h * 1024 + x * 16) = pieces[h];
+                    *reinterpret_cast<uint4 *>(blk + h * 1024 + (x ^ sw) * 16) = pieces[h];
             }
         };
         auto step = [&](float4 (&set)[8], int64_t stage, bool refill) {
@@ -1132,7 +1136,8 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
 #pragma unroll
                 for (int h = 0; h < NS; ++h)
                     b[q][h] = *reinterpret_cast<const uint4 *>(
-                        buf + ((ks * 4 + wq * QW + q) * NS + h) * 1024 + lane * 16);
+                        buf + ((ks * 4 + wq * QW + q) * NS + h) * 1024 +
+                        (lane ^ ((((lane >> 4) & 1) << 1) | ((wq * QW + q) & 1))) * 16);
 #pragma unroll
             for (int cb = 0; cb < CBW; ++cb)
 #pragma unroll
