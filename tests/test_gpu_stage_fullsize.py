@@ -1,6 +1,7 @@
-"""The whole stage of the ~100B-class configuration in the launch configuration bench.py times
-(every layer resident, three HIP streams, lane-wise batches, bf16 MFMA mode, fused round kernel,
-K = 4, r = 64, int4 / 128, bf16 local replicas).
+"""The whole stage of the ~100B-class configurations in the launch configuration bench.py times
+(as many layers resident as fit, three HIP streams, lane-wise batches, bf16 MFMA mode, fused
+round kernel, bf16 local replicas): K = 4, r = 64, int4 / 128 (all ten layers); the same at
+r = 256, the first rank of the adaptive configuration; and K = 8, r = 64, int8 / 64.
 
 No oracle can sweep 8.6 G elements, so this file checks what holds at any size: the one-step
 delay of Alg. 2 (nothing applied in round 1, something applied in round 2), orthonormal P_hat,
@@ -21,7 +22,7 @@ from gpu_util import DEV, to_np
 
 pytestmark = pytest.mark.gpu
 
-CFG, STEPS = 2, 3
+STEPS = 3
 
 
 def _digest(t):
@@ -50,22 +51,23 @@ def _input_digest(stage, locals_):
     return torch.stack(out).cpu().numpy()
 
 
-def _layers_that_fit():
-    cfg = synth.CONFIGS[CFG]
+def _layers_that_fit(cfg):
     per_layer = sum(m * n for m, n in cfg["layer_shapes"]) * (8 + cfg["K"] * 6) * 1.02
     free, _ = torch.cuda.mem_get_info()
     return int(min(cfg["layers"], (free - 6e9) // per_layer))
 
 
 @pytest.mark.timeout(600)
-def test_whole_stage_three_streams_properties_and_single_stream_bits():
+@pytest.mark.parametrize("CFG", [2, 3, 4])
+def test_whole_stage_three_streams_properties_and_single_stream_bits(CFG):
     torch.cuda.empty_cache()
-    layers = _layers_that_fit()
-    print("whole-stage case: %d layers resident" % layers, flush=True)
-    assert layers >= 4, "not enough free device memory for a meaningful stage"
     cfg = synth.CONFIGS[CFG]
+    layers = _layers_that_fit(cfg)
+    print("whole-stage case: config %d, %d layers resident" % (CFG, layers), flush=True)
+    assert layers >= 4, "not enough free device memory for a meaningful stage"
     K, r, G = cfg["K"], cfg["r"], cfg["group"]
-    qmax = 2 ** (cfg["qbits"] - 1) - 1
+    qbits = cfg["qbits"]
+    qmax = 2 ** (qbits - 1) - 1
 
     stage, locals_ = bench.build_stage(CFG, dlcx.MMA_BF16, layers, DEV, True, 3)
     assert stage.nstreams == 3 and stage.batched and len(stage.mats) == 7 * layers
@@ -96,7 +98,7 @@ def test_whole_stage_three_streams_properties_and_single_stream_bits():
             k = int(rs.integers(K))
             c_host, s_host = to_np(codes[k]), to_np(scales[k])
             for g in rs.choice(M.r * L // G, 8, replace=False):
-                c = ref.unpack_codes(c_host[g * G // 2:(g + 1) * G // 2], G, cfg["qbits"])
+                c = ref.unpack_codes(c_host[g * G * qbits // 8:(g + 1) * G * qbits // 8], G, qbits)
                 top = int(np.abs(c).max())
                 # the element of largest magnitude gets +-qmax; an all-zero group has scale 0
                 assert top == qmax or (top == 0 and s_host[g] == 0.0), (a, k, int(g), top)
