@@ -2,12 +2,14 @@
 // hold at least tau of the trace (with P_hat orthonormal these are the squared singular values of
 // the decompressed average).  S is accumulated in fp64 (same partial-sum kernel as the
 // orthonormalisation).  One workgroup per matrix finds its eigenvalues, all in fp64:
-//   r <= 128: S fits in LDS; one-sided Jacobi iteration on the columns of S (S is symmetric
-//             positive semi-definite, so the column norms at convergence are the eigenvalues)
-//             with a round-robin pair schedule;
-//   r  > 128: S stays in global memory (L2); Householder reduction to tridiagonal form (each
-//             step one symmetric matrix-vector product and one rank-2 update of the trailing
-//             block), then every eigenvalue by bisection on the Sturm sequence, one thread each.
+//   r  < 32:  one-sided Jacobi iteration on the columns of S in LDS (S is symmetric positive
+//             semi-definite, so the column norms at convergence are the eigenvalues) with a
+//             round-robin pair schedule;
+//   r >= 32:  Householder reduction to tridiagonal form (each step one symmetric matrix-vector
+//             product and one rank-2 update of the trailing block; S in LDS up to r = 128, in
+//             global memory / L2 above), then every eigenvalue by bisection on the Sturm
+//             sequence, one thread each.  (Measured per batch of 12: r = 64 1.56 -> 0.55 ms,
+//             r = 128 9.6 -> 1.6 ms against the Jacobi route; r = 16 the same.)
 // Then sort, prefix sum and count.
 #include "common.h"
 
@@ -23,6 +25,7 @@ __device__ __forceinline__ double team_sum(double v) {
 }
 
 constexpr size_t kJacobiLdsMax = 128 * 1024;
+constexpr int kTriMinRank = 32;  // from here on the tridiagonal route is the faster one
 
 // Sum of one value per thread over the workgroup, in a fixed order; every thread gets it.
 __device__ __forceinline__ double block_sum(double v, double *red, int nthreads) {
@@ -37,7 +40,7 @@ __device__ __forceinline__ double block_sum(double v, double *red, int nthreads)
 }
 
 // Eigenvalues of the symmetric r x r matrix a (column-major, leading dimension ld, both halves
-// stored, in global memory), descending, negative ones clamped to zero, into out[0..r).
+// stored, in LDS or global memory), descending, negative ones clamped to zero, into out[0..r).
 // d, e, v, w: r doubles each; psum: (nthreads / 256) * 256 doubles; red: 16 doubles (all LDS).
 __device__ void tridiagonal_eigenvalues(double *a, int r, int ld, double *d, double *e, double *v,
                                         double *w, double *psum, double *red, double *out,
@@ -159,12 +162,13 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, dou
     __syncthreads();
     const int team = tid >> 4, lane = tid & 15;
     const int npairs = re / 2;
-    if (!a_in_lds) {
+    const bool tri = !a_in_lds || r >= kTriMinRank;
+    if (tri) {
         __threadfence_block();
         tridiagonal_eigenvalues(a, r, re, eig, tri_e, tri_v, tri_w, tri_psum, tri_red, sorted,
                                 nthreads);
     }
-    for (int sweep = 0; a_in_lds && sweep < kMaxSweeps; ++sweep) {
+    for (int sweep = 0; !tri && sweep < kMaxSweeps; ++sweep) {
         if (tid == 0) rotated = 0;
         __syncthreads();
         for (int step = 0; step < re - 1; ++step) {
@@ -208,7 +212,7 @@ __global__ __launch_bounds__(kJT) void jacobi_rank_kernel(FactorBatch batch, dou
         __syncthreads();
         if (!any) break;
     }
-    if (a_in_lds) {
+    if (!tri) {
         for (int c = tid; c < r; c += nthreads) {
             double s = 0.0;
             for (int i = 0; i < re; ++i) s = fma(a[c * re + i], a[c * re + i], s);
