@@ -7,9 +7,13 @@ compensation for K simulated workers, both compression phases (projection, quant
 in-memory "AllReduce" average, orthonormalisation), and the rank measurement of Alg. 3.
 Inputs are synthetic (synth/), resident in HBM before the timed region.
 
-Prints ONE JSON line (see the keys below).  `value` is stage parameters per second.
+Prints ONE JSON line (see the keys below).  `value` is stage parameters per second.  The default
+run (config 2) appends `other_configs`: the OPT-1.3B-shaped stage, its quantise-only form and the
+512 x 512 case replayed as a HIP graph, each built, timed for a few steps and freed in turn.
 """
 import argparse
+import copy
+import gc
 import json
 import os
 import sys
@@ -21,7 +25,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per matrix element and launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs of
 # `bench.py --probe --layers 1 --streams 1` (config 2), scaled by a 1 GiB copy in the same run
-# (FETCH_SIZE reads 0.5 KiB per KiB copied, WRITE_SIZE 1.0): profiles/pmc_hbm_traffic_cfg2.txt
+# (FETCH_SIZE reads 0.5 KiB per KiB copied, WRITE_SIZE 1.0): profiles/pmc_hbm_traffic_cfg2.txt.
+# The counters cannot be read from inside a timed run, so the figure of that profile is quoted.
 MEASURED_TRAFFIC_BPP = {"round_fused": 60.40, "project_q": 16.76}
 
 
@@ -30,10 +35,11 @@ def log(*a):
 
 
 def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, workers=0, iters=1,
-                chunk=0, requant=False):
+                chunk=0, requant=False, keep_uv=False, stream_pool=None):
     """plain=True draws i.i.d. Gaussian replicas instead of the low-rank-plus-noise recipe (no
     library QR/GEMM kernels in the process: used for hardware-counter runs, where only the
-    traffic of this library's kernels is of interest)."""
+    traffic of this library's kernels is of interest).  keep_uv keeps what a later round's
+    replicas are drawn from (adaptive configuration)."""
     import torch
 
     import synth
@@ -41,7 +47,7 @@ def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, worker
 
     cfg = synth.CONFIGS[cfg_id]
     K, r = workers or cfg["K"], cfg["r"]
-    mats, locals_ = [], []
+    mats, inputs = [], []
     gen = torch.Generator(device="cpu")
     gen.manual_seed(1234 + cfg_id)
     t0 = time.time()
@@ -61,15 +67,16 @@ def build_stage(cfg_id, mma, layers, device, fused, streams, plain=False, worker
             else:
                 t = synth.torch_matrix_inputs(m, n, K, r, seed=synth.seed_for(cfg_id, layer, idx),
                                               sigma=sigma, alpha=alpha, theta_l=cfg["theta_l"],
-                                              device=device)
+                                              device=device, keep_uv=keep_uv)
             mats.append(MatrixState(t["theta_g"], K, t["q_in"], cfg["qbits"], cfg["group"], mma))
-            locals_.append(t["theta_l"])
+            inputs.append(t)
             idx += 1
         log("generated layer %d/%d  (%.1f s, %.1f GB allocated)" %
             (layer + 1, layers, time.time() - t0, torch.cuda.memory_allocated() / 1e9))
     stage = Stage(mats, synth.LR, synth.MU, fused=fused, warm_start=True, streams=streams,
-                  measure_rank=True, iters=iters, chunk=chunk, requant=requant)
-    return stage, locals_
+                  measure_rank=True, iters=iters, chunk=chunk, requant=requant,
+                  stream_pool=stream_pool)
+    return stage, inputs, gen
 
 
 def algorithmic_bytes_per_param(kernel, K, tl_bytes, fused):
@@ -88,43 +95,136 @@ def algorithmic_bytes_per_param(kernel, K, tl_bytes, fused):
     return table.get(kernel)
 
 
-def cpu_baseline(stage, locals_, cfg_id):
-    """The oracle, as it stands, on one matrix of the workload: outer steps of the smallest
-    matrix shape of the stage (K workers), single thread, for about 12 s (at least two steps:
-    the first applies nothing)."""
+# ---------------------------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands, on the machine's host cores
+# ---------------------------------------------------------------------------------------------
+def _cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(cfg_id, K, r, iters=1, requant=False, target_elems=1 << 21):
+    """The oracle (plain C, one thread per matrix, nothing tuned) on a bounded sample of the
+    stage: for every distinct matrix shape one slab of whole rows -- m_s x n with the shape's own
+    n, the configuration's K, rank, quantiser and replica type, about 2 M elements -- stepped
+    three times (the first step has no feedback and no update and is left out of the timing).
+    1 thread: the slabs one after the other.  All cores: independent slabs side by side, one
+    thread each (the arithmetic per matrix is unchanged, so are its results).  The stage figure
+    extrapolates the per-element rate of each shape over the stage's matrices of that shape,
+    which are independent."""
+    import threading
+
     import numpy as np
-    import torch
 
     import synth
     from oracle import pipeline
 
     cfg = synth.CONFIGS[cfg_id]
-    sizes = [M.m * M.n for M in stage.mats]
-    a = sizes.index(min(sizes))
-    M = stage.mats[a]
-    theta = M.theta_g.cpu().numpy()
-    q_in = M.q_in[: M.r].cpu().numpy()
-    tl = []
-    for x in locals_[a]:
-        if x.dtype.is_floating_point and x.element_size() == 2:
-            tl.append(x.view(torch.int16).cpu().numpy().view(np.uint16))
-        else:
-            tl.append(x.cpu().numpy())
-    orc = pipeline.MatrixOracle(theta, M.K, q_in, cfg["qbits"], cfg["group"], synth.LR, synth.MU,
-                                iters=stage.iters, requant=stage.requant)
-    t0 = time.time()
-    steps = 0
-    while steps < 2 or (time.time() - t0) * (steps + 1) / steps < 12.0:
-        orc.step(tl)
-        orc.set_basis(orc.q_bar)
-        steps += 1
-    dt = (time.time() - t0) / steps
-    return {"value": M.m * M.n / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
-            "sample": "%d outer steps of one %dx%d matrix of the stage (K=%d, r=%d, int%d/%d), "
-                      "%.1f s per step" % (steps, M.m, M.n, M.K, M.r, cfg["qbits"], cfg["group"],
-                                           dt)}
+    shapes = []
+    for s in synth.stage_shapes(cfg_id):
+        if s not in shapes:
+            shapes.append(s)
+    counts = {s: synth.stage_shapes(cfg_id).count(s) for s in shapes}
+    group = cfg["group"]
+
+    def slab_rows(m, n):
+        rows = max(target_elems // n, r, group)
+        rows = (rows + group - 1) // group * group
+        return min(rows, m)
+
+    def make(shape, seed):
+        m, n = shape
+        ms = slab_rows(m, n)
+        alpha = cfg["alpha"] if isinstance(cfg["alpha"], float) else 1.0
+        inp = synth.MatrixInputs(ms, n, K, min(r, ms, n), seed=seed,
+                                 sigma=float(synth.noise_sigma(cfg_id, m, n)), alpha=alpha,
+                                 theta_l=cfg["theta_l"])
+        orc = pipeline.MatrixOracle(inp.theta_g, K, inp.q_in, cfg["qbits"], group, synth.LR,
+                                    synth.MU, iters=iters, requant=requant)
+        return inp, orc, ms * n
+
+    def make_raw(inp, steps):
+        # the replicas' raw pseudo-gradients of every round, drawn before anything is timed
+        return [[inp.raw_pseudo_gradient(t, i) for i in range(K)] for t in range(1, steps + 1)]
+
+    def run(inp, orc, raw, barrier=None):
+        times = []
+        for t in range(1, len(raw) + 1):
+            tl = []
+            for i in range(K):   # theta_l,i = cast(theta_g - G_i), as synth.MatrixInputs does
+                x = (orc.theta.astype(np.float64) - raw[t - 1][i]).astype(np.float32)
+                tl.append(synth.f32_to_bf16_bits(x) if cfg["theta_l"] == "bf16" else x)
+            if barrier is not None and t == 2:
+                barrier.wait()
+            t0 = time.perf_counter()
+            orc.step(tl)
+            orc.set_basis(orc.q_bar)
+            times.append(time.perf_counter() - t0)
+        return times
+
+    # ---- one thread
+    per_shape, serial_batch = [], 0.0
+    for a, shape in enumerate(shapes):
+        inp, orc, elems = make(shape, 7000 + a)
+        times = run(inp, orc, make_raw(inp, 3))
+        dt = sum(times[1:]) / 2.0
+        serial_batch += sum(times[1:])
+        per_shape.append({"shape": "%dx%d" % shape, "slab": "%dx%d" % (inp.m, inp.n),
+                          "s_per_step": dt, "params_per_s": elems / dt})
+    stage_params = sum(m * n * c for (m, n), c in counts.items())
+    stage_s_1t = sum(counts[s] * s[0] * s[1] / p["params_per_s"] for s, p in zip(shapes, per_shape))
+    value_1t = stage_params / stage_s_1t
+    # ---- all host cores: independent slabs side by side, one thread each
+    cores_total = os.cpu_count() or 1
+    try:
+        cores_total = min(cores_total, len(os.sched_getaffinity(0)))
+    except AttributeError:
+        pass
+    env_cap = int(os.environ.get("OMP_NUM_THREADS", "0") or 0)  # the box's CPU share, if stated
+    threads = max(1, min(cores_total, env_cap) if env_cap > 0 else cores_total)
+    tasks = [make(shapes[i % len(shapes)], 7100 + i) for i in range(threads)]
+    raws = [make_raw(task[0], 3) for task in tasks]
+    barrier = threading.Barrier(threads + 1, timeout=900)
+    done = []
+
+    def worker(task, raw):
+        run(task[0], task[1], raw, barrier)
+        done.append(time.perf_counter())
+
+    ths = [threading.Thread(target=worker, args=(task, raw)) for task, raw in zip(tasks, raws)]
+    for th in ths:
+        th.start()
+    barrier.wait()
+    t0 = time.perf_counter()
+    for th in ths:
+        th.join()
+    wall = max(done) - t0
+    # the same batch of slabs, one after the other, would take threads / len(shapes) times the
+    # serial batch measured above
+    speedup = (threads / float(len(shapes))) * serial_batch / wall
+    value_all = value_1t * speedup
+    return {"value": value_all, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "value_1t": value_1t, "value_all": value_all, "cores_total": cores_total,
+            "cpu_model": _cpu_model(), "parallel_speedup": speedup, "extrapolated": True,
+            "per_shape_1t": per_shape,
+            "sample": "one row slab of about %.1f M elements of each of the %d matrix shapes "
+                      "(K=%d, r=%d, int%d/%d, %s replicas), steps 2 and 3 of three outer steps "
+                      "timed: 1 thread %.1f s; %d threads, one independent slab each, %.1f s; "
+                      "per-element rates extrapolated over the %d matrices of the stage"
+                      % (target_elems / 1e6, len(shapes), K, r, cfg["qbits"], group,
+                         cfg["theta_l"], serial_batch, threads, wall,
+                         len(synth.stage_shapes(cfg_id)))}
 
 
+# ---------------------------------------------------------------------------------------------
+# quantise-only outer step
+# ---------------------------------------------------------------------------------------------
 def quant_only(args):
     """The outer step with the quantiser as the whole compressor (the Int4-only setting of the
     paper's smaller model, Sec. 4.1): every tensor of the stage, matrices and vectors alike, is
@@ -180,7 +280,7 @@ def quant_only(args):
             one_step()
         torch.cuda.synchronize()
         print("probe done: %d tensors, 3 steps" % len(tensors), file=sys.stderr)
-        return
+        return None
     for _ in range(max(args.warmup, 1)):   # the first outer step has no previous payload
         one_step()
     torch.cuda.synchronize()
@@ -233,11 +333,15 @@ def quant_only(args):
             nsteps += 1
         dtc = (time.time() - t1) / nsteps
         out["cpu_baseline"] = {"value": T["numel"] / dtc, "unit": "params/s", "cores": 1,
-                               "kind": "oracle",
+                               "kind": "oracle", "cores_total": os.cpu_count(),
+                               "cpu_model": _cpu_model(),
                                "sample": "%d outer steps of one tensor of %d elements (K=%d, "
                                          "int%d/%d), %.2f s per step" %
                                          (nsteps, T["numel"], K, qbits, group, dtc)}
-    print(json.dumps(out), flush=True)
+    del tensors
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
 
 
 def mfma_peak(args):
@@ -269,6 +373,324 @@ def mfma_peak(args):
                       "workgroups": wgs, "mfma_per_wavefront": iters * 8}), flush=True)
 
 
+# ---------------------------------------------------------------------------------------------
+# streams restricted to a subset of the compute units (config 4: the outer step and a synthetic
+# inner-step load side by side)
+# ---------------------------------------------------------------------------------------------
+def masked_stream(device, cu_lo, cu_hi, total_cus=256):
+    """A HIP stream (default priority) whose kernels may only use compute units cu_lo .. cu_hi-1
+    of the mask handed to hipExtStreamCreateWithCUMask, wrapped for torch."""
+    import ctypes as C
+
+    import torch
+
+    hip = C.CDLL("libamdhip64.so")
+    words = (total_cus + 31) // 32
+    mask = (C.c_uint32 * words)()
+    for cu in range(cu_lo, cu_hi):
+        mask[cu // 32] |= 1 << (cu % 32)
+    handle = C.c_void_p()
+    rc = hip.hipExtStreamCreateWithCUMask(C.byref(handle), C.c_uint32(words), mask)
+    if rc != 0:
+        raise RuntimeError("hipExtStreamCreateWithCUMask failed: %d" % rc)
+    return torch.cuda.ExternalStream(handle.value, device=device)
+
+
+# ---------------------------------------------------------------------------------------------
+# low-rank outer step (the headline)
+# ---------------------------------------------------------------------------------------------
+def lowrank(args):
+    import torch
+
+    import paper_2506_21263_amd as dlcx
+    import synth
+    from paper_2506_21263_amd.stage import RankSelector
+
+    dlcx.lib()  # fail loudly if the HIP library is missing
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    layers = args.layers or cfg["layers"]
+    if args.config == 4 and not args.layers:
+        # K = 8 replicas of the full stage need 479 GB: time a window of 5 of the 10 identical,
+        # independent layers with persistent state (value stays parameters per second)
+        layers = 5
+    fused = not args.unfused
+    adaptive = args.config == 3
+    gemm_load = args.gemm_load
+    if gemm_load < 0:
+        gemm_load = 20 if args.config == 4 else 0
+    # config 4: the outer step's streams keep off the compute units reserved for the load
+    stream_pool = None
+    load_cus = args.load_cus if gemm_load else 0
+    if load_cus:
+        stream_pool = [masked_stream(device, 0, 256 - load_cus) for _ in range(max(args.streams, 1))]
+    stage, inputs, gen = build_stage(args.config, args.mma, layers, device, fused, args.streams,
+                                     plain=args.probe, workers=args.workers,
+                                     iters=args.power_iters, chunk=args.chunk,
+                                     requant=args.requant, keep_uv=adaptive,
+                                     stream_pool=stream_pool)
+    locals_ = [t["theta_l"] for t in inputs]
+    if args.probe:
+        x = torch.empty(1 << 28, dtype=torch.float32, device=device)
+        y = torch.empty_like(x)
+        y.copy_(x)  # the plain copy of known size (1 GiB in, 1 GiB out) the counters are scaled by
+        for _ in range(2):
+            stage.step(locals_)
+        torch.cuda.synchronize()
+        print("probe done: %d matrices, 2 steps" % len(stage.mats), file=sys.stderr)
+        return None
+    K = args.workers or cfg["K"]
+    params = stage.params()
+    selector = RankSelector(stage, c=cfg.get("window", 5), r1=cfg["r"], rmin=cfg.get("rmin", 4),
+                            rmax=cfg.get("rmax", cfg["r"]), H1=125)
+    selector.first()
+    ranks = []
+    load = None
+    if gemm_load:
+        # synthetic inner-step load: bf16 GEMMs 8192^3 on a stream of their own
+        load = {"stream": (masked_stream(device, 256 - load_cus, 256) if load_cus
+                           else torch.cuda.Stream(device=device)),
+                "a": torch.randn(8192, 8192, device=device, dtype=torch.bfloat16),
+                "b": torch.randn(8192, 8192, device=device, dtype=torch.bfloat16),
+                "c": torch.empty(8192, 8192, device=device, dtype=torch.bfloat16)}
+    log("stage: %d matrices, %.3f G params, K=%d, %.1f GB allocated" %
+        (len(stage.mats), params / 1e9, K, torch.cuda.memory_allocated() / 1e9))
+
+    use_graph = {"on": False}
+
+    def issue_load():
+        with torch.cuda.stream(load["stream"]):
+            for _ in range(gemm_load):
+                torch.matmul(load["a"], load["b"], out=load["c"])
+
+    def one_step(serial=False, with_load=True):
+        if use_graph["on"] and not serial:
+            stage.replay()
+            rp, r_next, _ = selector.next(stage.t + 1)
+            ranks.append((rp, r_next))
+            return
+        if load is not None and with_load:
+            load["stream"].wait_stream(torch.cuda.current_stream())
+            issue_load()
+        stage.step(locals_, serial=serial)
+        # Alg. 3: measure r' on this round's averages and apply the window rule; only the
+        # adaptive configuration lets the result change the rank of the next compression
+        rp, r_next, _ = selector.next(stage.t + 1)
+        ranks.append((rp, r_next, stage.mats[0].r))
+        if load is not None and with_load:
+            torch.cuda.current_stream().wait_stream(load["stream"])
+
+    def timed_steps(n, **kw):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            one_step(**kw)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    per_round = None
+    overlap = None
+    if adaptive:
+        # Alg. 3 drives the rank; every round the replicas are redrawn with a fresh spectrum
+        # exponent alpha ~ U[0.5, 2] against the current theta_g, OUTSIDE the timed region; each
+        # outer step is timed on its own with events on the issuing stream
+        per_round = []
+        total_ms = 0.0
+        for rnd in range(args.warmup + args.steps):
+            alpha = float(0.5 + 1.5 * torch.rand(1, generator=gen).item())
+            for M, t in zip(stage.mats, inputs):
+                synth.torch_redraw_replicas(t, M.theta_g, alpha)
+            torch.cuda.synchronize()
+            r_now = stage.mats[0].r
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            t0 = time.perf_counter()
+            one_step()
+            e1.record()
+            torch.cuda.synchronize()
+            wall_ms = (time.perf_counter() - t0) * 1e3
+            rp, r_next = ranks[-1][0], ranks[-1][1]
+            if r_next != r_now:
+                fresh = None
+                if r_next > r_now:  # cannot happen with r' <= r_t, kept for other bounds
+                    fresh = [torch.randn(r_next - r_now, M.n, device=device) for M in stage.mats]
+                stage.set_rank(r_next, fresh)
+            timed = rnd >= args.warmup
+            per_round.append({"round": rnd + 1, "alpha": round(alpha, 3), "rank": r_now,
+                              "rprime": rp, "rank_next": r_next, "ms": wall_ms,
+                              "ms_events": e0.elapsed_time(e1), "timed": timed})
+            if timed:
+                total_ms += wall_ms
+            log("round %d: alpha %.2f rank %d r' %d -> %d  %.1f ms" %
+                (rnd + 1, alpha, r_now, rp, r_next, wall_ms))
+        dt_step = total_ms * 1e-3 / args.steps
+    else:
+        for _ in range(args.warmup):
+            one_step()
+        torch.cuda.synchronize()
+        # fixed ranks and no foreign stream: the steady outer step can be recorded once into a
+        # HIP graph (all launches on all streams) and replayed; measured, it changes nothing at
+        # the large configurations, the host is not what the step waits for
+        if args.graph and load is None and stage.t >= 2:
+            stage.capture(locals_)
+            use_graph["on"] = True
+            one_step()
+            torch.cuda.synchronize()
+        dt_step = timed_steps(args.steps)
+        if load is not None:
+            # the same steps without the load, the load without the steps
+            t_a = timed_steps(args.steps, with_load=False)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                issue_load()
+            torch.cuda.synchronize()
+            t_c = (time.perf_counter() - t0) / args.steps
+            overlap = {"t_step_alone_ms": t_a * 1e3, "t_load_alone_ms": t_c * 1e3,
+                       "t_both_ms": dt_step * 1e3,
+                       "sum_ms": (t_a + t_c) * 1e3, "max_ms": max(t_a, t_c) * 1e3,
+                       # 1.0: the shorter of the two is fully hidden behind the longer
+                       "hidden_frac": (t_a + t_c - dt_step) / min(t_a, t_c),
+                       "both_over_max": dt_step / max(t_a, t_c),
+                       "load": "%d bf16 GEMMs 8192^3 per outer step (%.1f TFLOP) on a stream of "
+                               "their own" % (gemm_load, gemm_load * 2 * 8192.0 ** 3 / 1e12),
+                       "cus_reserved_for_load": load_cus,
+                       "cus_for_outer_step": 256 - load_cus if load_cus else 256}
+    ms_per_step = dt_step * 1e3
+    value = params / dt_step
+
+    # per-kernel durations: the same steps again with HIP events around every launch, all on
+    # one stream so that a kernel's events bracket that kernel alone
+    kernels, roofline, dt_prof = {}, None, None
+    tl_bytes = 2 if cfg["theta_l"] == "bf16" else 4
+    if True:
+        # (adaptive configuration: one such step, at the rank the rounds ended on)
+        nprof = 1 if adaptive else args.steps
+        dlcx.dlcx_profile_enable(True)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(nprof):
+            one_step(serial=True, with_load=False)
+        torch.cuda.synchronize()
+        dt_prof = (time.perf_counter() - t1) * args.steps / nprof
+        prof = dlcx.dlcx_profile_read()
+        dlcx.dlcx_profile_enable(False)
+        for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+            kernels[name] = {"ms_per_step": ms / nprof, "launches_per_step": cnt / nprof}
+        dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+        bpp = algorithmic_bytes_per_param(dom, K, tl_bytes, fused)
+        if bpp is not None:
+            per_worker = dom == "delta_ef"
+            launches = kernels[dom]["launches_per_step"]
+            # bytes of all launches of the kernel in one step / their summed duration
+            total_bytes = bpp * params * (K if per_worker else 1)
+            achieved = total_bytes / (kernels[dom]["ms_per_step"] * 1e-3) / 1e9
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                        "traffic": (MEASURED_TRAFFIC_BPP[dom] * params / launches
+                                    if dom in MEASURED_TRAFFIC_BPP and args.config == 2 else None),
+                        "traffic_source": "profiles/pmc_hbm_traffic_cfg2.txt (counter runs cannot "
+                                          "share a process with the timed run)",
+                        "algorithmic_bytes_per_param_per_launch": bpp,
+                        "avg_launch_ms": kernels[dom]["ms_per_step"] / launches,
+                        "launches_per_step": launches}
+            if adaptive:
+                roofline["at_rank"] = stage.mats[0].r_prev
+            if dom == "round_fused" and args.mma != 0 and not adaptive:
+                # matrix-core work of the same kernel: r (reconstruction) + r K (projection)
+                # multiply-adds per element, each as 3 (bf16x2) or 6 (bf16x3) bf16 piece products
+                pieces = 3 if args.mma == 2 else 6
+                useful = 2.0 * cfg["r"] * (1 + K) * params
+                sec = kernels[dom]["ms_per_step"] * 1e-3
+                roofline["mfma"] = {
+                    "useful_TFLOPs": useful / sec / 1e12,
+                    "useful_frac_of_peak": useful / sec / 1e12 / 2500.0,
+                    "executed_bf16_TFLOPs": useful * pieces / sec / 1e12,
+                    "peak_bf16_TFLOPs": 2500.0,
+                    "note": "HBM-bound: %.0f executed flop per byte against a ridge of 312"
+                            % (2.0 * cfg["r"] * (1 + K) * pieces / bpp)}
+    # every further power iteration reads each worker's pseudo-gradient twice more
+    b_alg = (14 if tl_bytes == 2 else 16) * K + 20 + 8 * K * (args.power_iters - 1)
+    out = {
+        "metric": "outer-step params/sec per stage (compress+avg+Nesterov)",
+        "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": {0: "f32 (fp64 accumulate)", 1: "bf16x3-split MFMA (fp32-accurate), f32 accumulate",
+                  2: "bf16x2-split MFMA, f32 accumulate"}[args.mma],
+        "data": "synthetic",
+        "config": {"workload": cfg["name"], "layers": layers, "matrices": len(stage.mats),
+                   "params": params, "K": K, "rank": cfg["r"], "qbits": cfg["qbits"],
+                   "group": cfg["group"], "theta_l": cfg["theta_l"], "mma": args.mma,
+                   "fused": fused, "streams": stage.nstreams, "hip_graph": use_graph["on"],
+                   "power_iters": args.power_iters, "requant": bool(args.requant)},
+        "roofline": roofline,
+        "stage_hbm": {"algorithmic_bytes_per_param": b_alg,
+                      "achieved_GBps": b_alg * params / dt_step / 1e9,
+                      "frac_of_8TBps": b_alg * params / dt_step / 1e9 / HBM_PEAK_GBS},
+        "kernels": kernels,
+        "rank_trace": [list(x) for x in ranks[-(2 * args.steps):][:args.steps]],
+    }
+    if dt_prof is not None:
+        out["ms_per_step_serial_with_events"] = dt_prof / args.steps * 1e3
+    if per_round is not None:
+        out["config"]["timing"] = ("each outer step timed on its own; replicas redrawn with a "
+                                   "fresh alpha ~ U[0.5, 2] between steps, outside the timing")
+        out["per_round"] = per_round
+        out["rank_trace"] = [[p["rprime"], p["rank_next"], p["rank"]] for p in per_round]
+        # matrix-core work at each round's own rank: 2 r (3 K + 1) useful flop per element
+        timed = [p for p in per_round if p["timed"]]
+        useful = sum(2.0 * p["rank"] * (3 * K + 1) * params for p in timed)
+        sec = sum(p["ms"] for p in timed) * 1e-3
+        pieces = 3 if args.mma == 2 else 6
+        out["mfma"] = {"useful_TFLOPs": useful / sec / 1e12,
+                       "useful_frac_of_peak": useful / sec / 1e12 / 2500.0,
+                       "executed_bf16_TFLOPs": useful * pieces / sec / 1e12,
+                       "peak_bf16_TFLOPs": 2500.0}
+    if overlap is not None:
+        out["overlap"] = overlap
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, K, cfg["r"], iters=args.power_iters,
+                                           requant=args.requant)
+    del stage, inputs, locals_, load, selector
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
+
+
+def other_configs(args):
+    """Compact figures of three more workloads under the same clock as the headline: each is
+    built, warmed, timed for a few outer steps and freed before the next."""
+    res = {}
+
+    def compact(o):
+        c = {"workload": o["config"]["workload"], "ms_per_step": o["ms_per_step"],
+             "params_per_s": o["value"], "steps": o["steps"], "warmup": o["warmup"]}
+        if o.get("stage_hbm"):
+            c["stage_frac_of_8TBps"] = o["stage_hbm"]["frac_of_8TBps"]
+            c["stage_bytes_per_param"] = o["stage_hbm"]["algorithmic_bytes_per_param"]
+        if o.get("roofline"):
+            c["dominant_kernel"] = o["roofline"]["kernel"]
+            c["dominant_kernel_frac"] = o["roofline"]["frac"]
+        if o.get("kernels"):
+            c["launches_per_step"] = sum(k["launches_per_step"] for k in o["kernels"].values())
+        c["hip_graph"] = o["config"].get("hip_graph", False)
+        return c
+
+    a = copy.copy(args)
+    a.config, a.steps, a.warmup, a.layers, a.no_cpu_baseline = 1, 10, 3, 0, True
+    a.graph, a.workers, a.gemm_load, a.load_cus = False, 0, 0, 0
+    res["cfg1"] = compact(lowrank(a))
+    q = copy.copy(a)
+    q.quant_only = True
+    res["cfg1-quant-only"] = compact(quant_only(q))
+    g = copy.copy(a)
+    g.config, g.steps, g.warmup, g.graph, g.streams = 0, 200, 5, True, 1
+    res["cfg0-graph"] = compact(lowrank(g))
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -280,8 +702,14 @@ def main():
     ap.add_argument("--unfused", action="store_true", help="separate decompress / Nesterov kernels")
     ap.add_argument("--streams", type=int, default=3, help="HIP streams the matrices are dealt to")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--gemm-load", type=int, default=0,
-                    help="bf16 8192^3 GEMMs issued on a second stream per outer step (config 4)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="leave out the other_configs block of the default run")
+    ap.add_argument("--gemm-load", type=int, default=-1,
+                    help="bf16 8192^3 GEMMs issued on a stream of their own per outer step "
+                         "(default: 20 at config 4, else 0)")
+    ap.add_argument("--load-cus", type=int, default=0,
+                    help="compute units reserved for the GEMM load (the outer step's streams are "
+                         "created with a mask that leaves them out; 0 = no masks)")
     ap.add_argument("--graph", action="store_true",
                     help="record the steady outer step into a HIP graph and replay it (fixed ranks)")
     ap.add_argument("--workers", type=int, default=0, help="K (0 = the configuration's)")
@@ -306,166 +734,13 @@ def main():
 
     if args.mfma_peak:
         return mfma_peak(args)
-    if args.quant_only:
-        return quant_only(args)
-
-    import torch
-
-    import paper_2506_21263_amd as dlcx
-    import synth
-    from paper_2506_21263_amd.stage import RankSelector
-
-    dlcx.lib()  # fail loudly if the HIP library is missing
-    device = "cuda:0"
-    torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[args.config]
-    layers = args.layers or cfg["layers"]
-    if args.config == 4 and not args.layers:
-        # K = 8 replicas of the full stage need 479 GB: time a window of 5 of the 10 identical,
-        # independent layers with persistent state (value stays parameters per second)
-        layers = 5
-    fused = not args.unfused
-    stage, locals_ = build_stage(args.config, args.mma, layers, device, fused, args.streams,
-                                 plain=args.probe, workers=args.workers, iters=args.power_iters,
-                                 chunk=args.chunk, requant=args.requant)
-    if args.probe:
-        x = torch.empty(1 << 28, dtype=torch.float32, device=device)
-        y = torch.empty_like(x)
-        y.copy_(x)  # the plain copy of known size (1 GiB in, 1 GiB out) the counters are scaled by
-        for _ in range(2):
-            stage.step(locals_)
-        torch.cuda.synchronize()
-        print("probe done: %d matrices, 2 steps" % len(stage.mats), file=sys.stderr)
+    out = quant_only(args) if args.quant_only else lowrank(args)
+    if out is None:
         return
-    K = args.workers or cfg["K"]
-    params = stage.params()
-    selector = RankSelector(stage, c=cfg.get("window", 5), r1=cfg["r"], rmin=cfg.get("rmin", 4),
-                            rmax=cfg.get("rmax", cfg["r"]), H1=125)
-    selector.first()
-    adaptive = args.config == 3
-    ranks = []
-    load = None
-    if args.gemm_load:
-        # synthetic inner-step load: bf16 GEMMs 8192^3 on a stream of their own
-        load = {"stream": torch.cuda.Stream(device=device),
-                "a": torch.randn(8192, 8192, device=device, dtype=torch.bfloat16),
-                "b": torch.randn(8192, 8192, device=device, dtype=torch.bfloat16),
-                "c": torch.empty(8192, 8192, device=device, dtype=torch.bfloat16), "n": 0}
-    log("stage: %d matrices, %.3f G params, K=%d, %.1f GB allocated" %
-        (len(stage.mats), params / 1e9, K, torch.cuda.memory_allocated() / 1e9))
-
-    use_graph = {"on": False}
-
-    def one_step(serial=False):
-        if use_graph["on"] and not serial:
-            stage.replay()
-            rp, r_next, _ = selector.next(stage.t + 1)
-            ranks.append((rp, r_next))
-            return
-        if load is not None:
-            with torch.cuda.stream(load["stream"]):
-                for _ in range(args.gemm_load):
-                    torch.matmul(load["a"], load["b"], out=load["c"])
-            load["n"] += args.gemm_load
-        stage.step(locals_, serial=serial)
-        # Alg. 3: measure r' on this round's averages and apply the window rule; only the
-        # adaptive configuration lets the result change the rank of the next compression
-        rp, r_next, _ = selector.next(stage.t + 1)
-        ranks.append((rp, r_next))
-        if adaptive:
-            for M in stage.mats:
-                if r_next > M.r:  # fresh seeded columns for a basis that grows
-                    M.q_bar[M.r:r_next].normal_()
-                M.r = r_next
-        if load is not None:
-            torch.cuda.current_stream().wait_stream(load["stream"])
-
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    # fixed ranks and no foreign stream: the steady outer step can be recorded once into a HIP
-    # graph (all launches on all streams) and replayed; measured, it changes nothing here, the
-    # host is not what the step waits for
-    if args.graph and not adaptive and load is None and stage.t >= 2:
-        stage.capture(locals_)
-        use_graph["on"] = True
-        one_step()
-        torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    value = params / (dt / args.steps)
-
-    # per-kernel durations: the same steps again with HIP events around every launch, all on
-    # one stream so that a kernel's events bracket that kernel alone
-    dlcx.dlcx_profile_enable(True)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step(serial=True)
-    torch.cuda.synchronize()
-    dt_prof = time.perf_counter() - t1
-    prof = dlcx.dlcx_profile_read()
-    dlcx.dlcx_profile_enable(False)
-    tl_bytes = 2 if cfg["theta_l"] == "bf16" else 4
-    kernels = {}
-    for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
-        kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps}
-    dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
-    bpp = algorithmic_bytes_per_param(dom, K, tl_bytes, fused)
-    roofline = None
-    if bpp is not None:
-        per_worker = dom == "delta_ef"
-        launches = kernels[dom]["launches_per_step"]
-        # bytes of all launches of the kernel in one step / their summed duration
-        total_bytes = bpp * params * (K if per_worker else 1)
-        achieved = total_bytes / (kernels[dom]["ms_per_step"] * 1e-3) / 1e9
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": (MEASURED_TRAFFIC_BPP[dom] * params / launches
-                                if dom in MEASURED_TRAFFIC_BPP and args.config == 2 else None),
-                    "algorithmic_bytes_per_param_per_launch": bpp,
-                    "avg_launch_ms": kernels[dom]["ms_per_step"] / launches,
-                    "launches_per_step": launches}
-        if dom == "round_fused" and args.mma != 0:
-            # matrix-core work of the same kernel: r (reconstruction) + r K (projection)
-            # multiply-adds per element, each as 3 (bf16x2) or 6 (bf16x3) bf16 piece products
-            pieces = 3 if args.mma == 2 else 6
-            useful = 2.0 * cfg["r"] * (1 + K) * params
-            roofline["mfma"] = {
-                "useful_TFLOPs": useful / (kernels[dom]["ms_per_step"] * 1e-3) / 1e12,
-                "executed_bf16_TFLOPs": useful * pieces / (kernels[dom]["ms_per_step"] * 1e-3) / 1e12,
-                "peak_bf16_TFLOPs": 2500.0,
-                "note": "HBM-bound: %.0f executed flop per byte against a ridge of 312"
-                        % (2.0 * cfg["r"] * (1 + K) * pieces / bpp)}
-    # every further power iteration reads each worker's pseudo-gradient twice more
-    b_alg = (14 if tl_bytes == 2 else 16) * K + 20 + 8 * K * (args.power_iters - 1)
-    out = {
-        "metric": "outer-step params/sec per stage (compress+avg+Nesterov)",
-        "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None,
-        "dtype": {0: "f32 (fp64 accumulate)", 1: "bf16x3-split MFMA (fp32-accurate), f32 accumulate",
-                  2: "bf16x2-split MFMA, f32 accumulate"}[args.mma],
-        "data": "synthetic",
-        "config": {"workload": cfg["name"], "layers": layers, "matrices": len(stage.mats),
-                   "params": params, "K": K, "rank": cfg["r"], "qbits": cfg["qbits"],
-                   "group": cfg["group"], "theta_l": cfg["theta_l"], "mma": args.mma,
-                   "fused": fused, "streams": stage.nstreams, "hip_graph": use_graph["on"],
-                   "power_iters": args.power_iters, "requant": bool(args.requant)},
-        "roofline": roofline,
-        "stage_hbm": {"algorithmic_bytes_per_param": b_alg,
-                      "achieved_GBps": b_alg * params / (dt / args.steps) / 1e9,
-                      "frac_of_8TBps": b_alg * params / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
-        "kernels": kernels,
-        "ms_per_step_serial_with_events": dt_prof / args.steps * 1e3,
-        "rank_trace": ranks[-(2 * args.steps):][:args.steps],
-    }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(stage, locals_, args.config)
+    headline = (args.config == 2 and not args.quant_only and not args.layers and not args.workers
+                and args.mma == 2 and not args.unfused)
+    if headline and not args.no_other_configs:
+        out["other_configs"] = other_configs(args)
     print(json.dumps(out), flush=True)
 
 

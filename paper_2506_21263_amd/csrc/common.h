@@ -19,6 +19,12 @@ int note_hip(hipError_t e, const char *where);
 
 inline int check_launch(const char *where) { return note_hip(hipGetLastError(), where); }
 
+// Raises `kernel`'s limit of dynamic LDS to at least `bytes` (needed above 48 KB).  *granted
+// remembers the largest value set so far for that kernel; check, call and update happen under
+// one process-wide lock, so two host threads that launch on two streams can neither skip a
+// needed call nor leave a smaller limit behind a larger request.
+int grant_dynamic_lds(const void *kernel, size_t bytes, size_t *granted, const char *what);
+
 // Optional per-kernel timing (dlcx_profile_*): when enabled, a Timed object brackets one kernel
 // launch with two HIP events on the launch stream.  Off by default; costs nothing when off.
 enum KernelId {
@@ -32,6 +38,7 @@ struct Timed {
     ~Timed();
     int slot;
     hipStream_t st;
+    void *stop;  // the closing event of this launch's record
 };
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -2,6 +2,7 @@
 // Nothing here allocates or synchronises, except dlcx_select_rank which returns integers.
 #include <string.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -17,25 +18,47 @@ int note_hip(hipError_t e, const char *where) {
     return DLCX_ELAUNCH;
 }
 
+int grant_dynamic_lds(const void *kernel, size_t bytes, size_t *granted, const char *what) {
+    if (bytes <= 48 * 1024) return DLCX_OK;
+    static std::mutex mu;
+    std::lock_guard<std::mutex> lock(mu);
+    if (bytes <= *granted) return DLCX_OK;
+    int rc = note_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)bytes), what);
+    if (rc == DLCX_OK) *granted = bytes;
+    return rc;
+}
+
 // ---- optional per-kernel timing ---------------------------------------------------------
 struct ProfRec {
     int kid;
     hipEvent_t a, b;
 };
+static std::mutex g_prof_mutex;  // guards g_prof_on and g_prof (launches may come from several threads)
 static bool g_prof_on = false;
 static std::vector<ProfRec> g_prof;
 
-Timed::Timed(int kid, hipStream_t s) : slot(-1), st(s) {
+Timed::Timed(int kid, hipStream_t s) : slot(-1), st(s), stop(nullptr) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     if (!g_prof_on) return;
     ProfRec r;
     r.kid = kid;
-    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
-    if (hipEventRecord(r.a, st) != hipSuccess) return;
+    if (hipEventCreate(&r.a) != hipSuccess) return;
+    if (hipEventCreate(&r.b) != hipSuccess) {
+        (void)hipEventDestroy(r.a);
+        return;
+    }
+    if (hipEventRecord(r.a, st) != hipSuccess) {
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+        return;
+    }
     g_prof.push_back(r);
     slot = (int)g_prof.size() - 1;
+    stop = r.b;  // the record may move when another thread appends: keep the handle itself
 }
 Timed::~Timed() {
-    if (slot >= 0) (void)hipEventRecord(g_prof[slot].b, st);
+    if (slot >= 0) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(stop), st);
 }
 
 // k_gemm_fma.hip
@@ -135,6 +158,7 @@ static const char *const kKernelNames[KID_COUNT] = {
     "mfma_peak"};
 
 int dlcx_profile_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     for (auto &r : g_prof) {
         (void)hipEventDestroy(r.a);
         (void)hipEventDestroy(r.b);
@@ -155,6 +179,7 @@ int dlcx_profile_read(int kernel_id, double *total_ms_host, int64_t *launches_ho
         return DLCX_EINVAL;
     double total = 0.0;
     int64_t count = 0;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     for (auto &r : g_prof) {
         if (r.kid != kernel_id) continue;
         int rc = note_hip(hipEventSynchronize(r.b), "profile sync");

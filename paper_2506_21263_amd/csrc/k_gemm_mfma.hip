@@ -1220,16 +1220,11 @@ static int project_p_launch(const PtrPack<const float *> &delta, const uint4 *fr
                             const PtrPack<float *> &out, int64_t m, int64_t n, int r, int K,
                             hipStream_t st) {
     constexpr int lds = project_p_lds_bytes<NS, CBW, WC, WK, WR, RB>();
-    static bool granted = false;
-    if (lds > 48 * 1024 && !granted) {
-        int rc = note_hip(
-            hipFuncSetAttribute(
-                reinterpret_cast<const void *>(project_p_mfma_kernel<NS, CBW, WC, WK, WR, RB>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, lds),
-            "project_p attribute");
-        if (rc != DLCX_OK) return rc;
-        granted = true;
-    }
+    static size_t granted = 0;
+    int rc = grant_dynamic_lds(
+        reinterpret_cast<const void *>(project_p_mfma_kernel<NS, CBW, WC, WK, WR, RB>), lds,
+        &granted, "project_p attribute");
+    if (rc != DLCX_OK) return rc;
     const dim3 grid((unsigned)ceil_div(m, 32 * RB), (unsigned)K);
     hipLaunchKernelGGL((project_p_mfma_kernel<NS, CBW, WC, WK, WR, RB>), grid, dim3(kW), lds, st,
                        delta, frags, out, m, n, r);
@@ -1241,16 +1236,11 @@ static int project_p_ws_launch(const PtrPack<const float *> &delta, const uint4 
                                const PtrPack<float *> &out, int64_t m, int64_t n, int r, int K,
                                hipStream_t st) {
     constexpr int lds = 2 * NS * 32 * RB * kPPitch;
-    static bool granted = false;
-    if (lds > 48 * 1024 && !granted) {
-        int rc = note_hip(
-            hipFuncSetAttribute(
-                reinterpret_cast<const void *>(project_p_ws_kernel<NS, CBW, WC, WR, RB>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, lds),
-            "project_p attribute");
-        if (rc != DLCX_OK) return rc;
-        granted = true;
-    }
+    static size_t granted = 0;
+    int rc = grant_dynamic_lds(
+        reinterpret_cast<const void *>(project_p_ws_kernel<NS, CBW, WC, WR, RB>), lds, &granted,
+        "project_p attribute");
+    if (rc != DLCX_OK) return rc;
     const dim3 grid((unsigned)ceil_div(m, 32 * RB), (unsigned)K);
     hipLaunchKernelGGL((project_p_ws_kernel<NS, CBW, WC, WR, RB>), grid, dim3(kWs), lds, st, delta,
                        frags, out, m, n, r);
@@ -1301,15 +1291,10 @@ static int project_q_ws_launch(const dim3 &grid, hipStream_t st, const PtrPack<c
                                const uint4 *frags, const PtrPack<float *> &dst, int64_t m,
                                int64_t n, int r, int64_t ksteps_per_wg, int64_t slab) {
     constexpr int lds = 2 * 16 * NS * 1024;
-    static bool granted = false;
-    if (lds > 48 * 1024 && !granted) {
-        int rc = note_hip(
-            hipFuncSetAttribute(reinterpret_cast<const void *>(project_q_ws_kernel<NS, CBW, WCB>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds),
-            "project_q attribute");
-        if (rc != DLCX_OK) return rc;
-        granted = true;
-    }
+    static size_t granted = 0;
+    int rc = grant_dynamic_lds(reinterpret_cast<const void *>(project_q_ws_kernel<NS, CBW, WCB>),
+                               lds, &granted, "project_q attribute");
+    if (rc != DLCX_OK) return rc;
     hipLaunchKernelGGL((project_q_ws_kernel<NS, CBW, WCB>), grid, dim3(kWs), lds, st, delta, frags, dst,
                        m, n, r, ksteps_per_wg, slab);
     return DLCX_OK;
@@ -1481,14 +1466,9 @@ static int round_launch_t(const uint4 *pf, const uint4 *qf, int ks, const uint4 
     const size_t red = (size_t)KC * CB * 16 * 64 * 4;
     const size_t lds = tiles > red ? tiles : red;
     static size_t granted = 0;
-    if (lds > 48 * 1024 && lds > granted) {
-        int rc = note_hip(hipFuncSetAttribute(
-                              reinterpret_cast<const void *>(round_mfma_kernel<NS, CB, KC, TLBF16>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
-                          "round kernel attribute");
-        if (rc != DLCX_OK) return rc;
-        granted = lds;
-    }
+    int rc = grant_dynamic_lds(reinterpret_cast<const void *>(round_mfma_kernel<NS, CB, KC, TLBF16>),
+                               lds, &granted, "round kernel attribute");
+    if (rc != DLCX_OK) return rc;
     const dim3 grid((unsigned)pl.chunks, (unsigned)ceil_div(m, 32));
     Timed timed(KID_ROUND, st);
     hipLaunchKernelGGL((round_mfma_kernel<NS, CB, KC, TLBF16>), grid, dim3(kW), lds, st, pf, qf, ks,

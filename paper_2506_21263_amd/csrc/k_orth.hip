@@ -240,14 +240,6 @@ size_t orth_workspace_bytes(int64_t L, int r) {
                  sizeof(double));
 }
 
-static int set_lds_limit(const void *kernel, size_t bytes, size_t *granted, const char *what) {
-    if (bytes <= 48 * 1024 || bytes <= *granted) return DLCX_OK;
-    int rc = note_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                          (int)bytes), what);
-    if (rc == DLCX_OK) *granted = bytes;
-    return rc;
-}
-
 static int cholqr_pass(const FactorBatch &batch, hipStream_t st) {
     int rc = launch_gram_partials_batch(batch, st);
     if (rc != DLCX_OK) return rc;
@@ -262,7 +254,7 @@ static int cholqr_pass(const FactorBatch &batch, hipStream_t st) {
         if (ceil_div(batch.it[i].L, 64) > max_rows) max_rows = ceil_div(batch.it[i].L, 64);
     }
     static size_t chol_granted = 0, apply_granted = 0;
-    rc = set_lds_limit(reinterpret_cast<const void *>(chol_inverse_kernel), g_bytes, &chol_granted,
+    rc = grant_dynamic_lds(reinterpret_cast<const void *>(chol_inverse_kernel), g_bytes, &chol_granted,
                        "chol_inverse attribute");
     if (rc != DLCX_OK) return rc;
     {
@@ -275,7 +267,7 @@ static int cholqr_pass(const FactorBatch &batch, hipStream_t st) {
         rc = check_launch("chol_inverse");
     }
     if (rc != DLCX_OK) return rc;
-    rc = set_lds_limit(reinterpret_cast<const void *>(apply_w_kernel), a_bytes, &apply_granted,
+    rc = grant_dynamic_lds(reinterpret_cast<const void *>(apply_w_kernel), a_bytes, &apply_granted,
                        "apply_w attribute");
     if (rc != DLCX_OK) return rc;
     Timed timed(KID_APPLY_W, st);

@@ -274,13 +274,9 @@ int launch_effective_rank_batch(const FactorBatch &batch, double tau, hipStream_
         if (b <= kJacobiLdsMax && b > bytes) bytes = b;
     }
     static size_t granted = 0;
-    if (bytes > 48 * 1024 && bytes > granted) {
-        rc = note_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(jacobi_rank_kernel),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes),
-                      "jacobi attribute");
-        if (rc != DLCX_OK) return rc;
-        granted = bytes;
-    }
+    rc = grant_dynamic_lds(reinterpret_cast<const void *>(jacobi_rank_kernel), bytes, &granted,
+                           "jacobi attribute");
+    if (rc != DLCX_OK) return rc;
     Timed timed(KID_JACOBI, st);
     int rmax = 0;
     for (int i = 0; i < batch.n; ++i) rmax = batch.it[i].r > rmax ? batch.it[i].r : rmax;

@@ -99,11 +99,13 @@ class Stage:
     averaged factor to q bits (dlcx_requantize), as a reduction that carries q-bit values would
     deliver it, before it is used.  iters > 1 repeats the two compression phases on the round's
     pseudo-gradients, each repeat starting from the Q average just formed (more power iterations
-    per round: a closer rank-r fit for two more averages each).
+    per round: a closer rank-r fit for two more averages each).  stream_pool hands in the HIP
+    streams to use (at least `streams` of them) instead of creating them.
     """
 
     def __init__(self, matrices, lr, mu, fused=False, warm_start=False, streams=1,
-                 measure_rank=False, tau=0.99, batched=True, requant=False, iters=1, chunk=0):
+                 measure_rank=False, tau=0.99, batched=True, requant=False, iters=1, chunk=0,
+                 stream_pool=None):
         assert iters >= 1 and chunk >= 0
         self.mats = matrices
         self.requant = requant
@@ -123,8 +125,13 @@ class Stage:
         if not fused:
             self.delta_hats = [torch.empty(big, device=dev, dtype=torch.float32)
                                for _ in range(self.nstreams)]
-        self.side = [torch.cuda.Stream(device=dev) for _ in range(self.nstreams)] \
-            if self.nstreams > 1 else []
+        if stream_pool:
+            # the caller's streams (e.g. created with a compute-unit mask), one per lane
+            assert len(stream_pool) >= self.nstreams
+            self.side = list(stream_pool[: self.nstreams])
+        else:
+            self.side = [torch.cuda.Stream(device=dev) for _ in range(self.nstreams)] \
+                if self.nstreams > 1 else []
         self.rprime_dev = torch.zeros(len(matrices), device=dev, dtype=torch.int32)
         self.batched = batched
         self.serial = False
@@ -267,6 +274,25 @@ class Stage:
                                             stream=st)
         self._join(main)
 
+
+    def set_rank(self, r_next, fresh=None):
+        """Rank of the next compression (Alg. 3's r_t) for every matrix of the stage, with the
+        warm start resized to it: the first min(r_old, r_next) columns of the basis stay where
+        they are, and when the rank grows, columns r_old .. r_next - 1 of matrix a are copied
+        from fresh[a] (a device tensor with at least r_next - r_old rows of length n; the draws
+        are the caller's, nothing is generated here).  The basis is Q_bar of the round just
+        finished when the stage warm-starts and a round has run, else Q_in.  A matrix's rank is
+        clipped to its smaller side and to the capacity its buffers were allocated for.  The
+        previous round's factors (and their rank) are untouched: the next step still feeds back
+        and applies the average at the rank it was formed with."""
+        for a, M in enumerate(self.mats):
+            r_new = max(1, min(r_next, M.r_max, M.m, M.n))
+            grow = r_new - M.r
+            if grow > 0:
+                assert fresh is not None and fresh[a].shape[0] >= grow and fresh[a].shape[1] == M.n
+                basis = M.q_bar if (self.warm_start and self.t >= 1) else M.q_in
+                basis[M.r:r_new].copy_(fresh[a][:grow])
+            M.r = r_new
 
     def capture(self, theta_l_per_matrix):
         """Record one outer step into a HIP graph (every launch of `step`, on all its streams)

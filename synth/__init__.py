@@ -140,9 +140,10 @@ class MatrixInputs:
 # ---------------------------------------------------------------------------
 # torch generator (bench at full size): tensors are drawn directly in HBM
 # ---------------------------------------------------------------------------
-def torch_matrix_inputs(m, n, K, r, seed, sigma, alpha, theta_l, device, kmax=512):
+def torch_matrix_inputs(m, n, K, r, seed, sigma, alpha, theta_l, device, kmax=512, keep_uv=False):
     """Same recipe with torch ops on `device`.  Returns a dict of device tensors:
-    theta_g (m,n) f32, theta_l list of K (m,n) f32|bf16, q_in (r,n) f32."""
+    theta_g (m,n) f32, theta_l list of K (m,n) f32|bf16, q_in (r,n) f32; with keep_uv also U, V,
+    sigma and the generator, which torch_redraw_replicas needs to draw a later round."""
     import torch
 
     g = torch.Generator(device=device)
@@ -157,16 +158,32 @@ def torch_matrix_inputs(m, n, K, r, seed, sigma, alpha, theta_l, device, kmax=51
     U, V = orth(m), orth(n)
     theta_g = 0.02 * torch.randn(m, n, generator=g, device=device, dtype=torch.float32)
     q_in = torch.randn(r, n, generator=g, device=device, dtype=torch.float32)
-    s0 = torch.arange(1, k + 1, device=device, dtype=torch.float32) ** (-alpha)
-    replicas = []
-    for _ in range(K):
-        s = s0 * (1.0 + 0.1 * (2.0 * torch.rand(k, generator=g, device=device) - 1.0))
+    dt = torch.bfloat16 if theta_l == "bf16" else torch.float32
+    replicas = [torch.empty(m, n, device=device, dtype=dt) for _ in range(K)]
+    out = dict(theta_g=theta_g, theta_l=replicas, q_in=q_in, U=U, V=V, sigma=sigma, gen=g)
+    torch_redraw_replicas(out, theta_g, alpha)
+    if not keep_uv:
+        for key in ("U", "V", "gen", "sigma"):
+            del out[key]
+    return out
+
+
+def torch_redraw_replicas(t, theta_g_now, alpha):
+    """Local replicas of a new round, written over t["theta_l"]: theta_l,i = cast(theta_g_now -
+    G_i) with G_i = U diag(s_i) V^T + E_i, s_k = k^-alpha perturbed by +-10 % per worker, fresh
+    noise E_i -- the recipe of torch_matrix_inputs with this round's spectrum exponent."""
+    import torch
+
+    U, V, g, sigma = t["U"], t["V"], t["gen"], t["sigma"]
+    k, dev = U.shape[1], U.device
+    s0 = torch.arange(1, k + 1, device=dev, dtype=torch.float32) ** (-alpha)
+    for tl in t["theta_l"]:
+        s = s0 * (1.0 + 0.1 * (2.0 * torch.rand(k, generator=g, device=dev) - 1.0))
         G = (U * s) @ V.T
-        G.add_(torch.randn(m, n, generator=g, device=device, dtype=torch.float32), alpha=sigma)
-        tl = theta_g - G
-        replicas.append(tl.to(torch.bfloat16) if theta_l == "bf16" else tl)
+        G.add_(torch.randn(G.shape, generator=g, device=dev, dtype=torch.float32), alpha=sigma)
+        torch.sub(theta_g_now, G, out=G)
+        tl.copy_(G)
         del G
-    return dict(theta_g=theta_g, theta_l=replicas, q_in=q_in)
 
 
 def hadamard(k):

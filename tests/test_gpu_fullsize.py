@@ -16,13 +16,14 @@ import torch
 import paper_2506_21263_amd as dlcx
 import synth
 from oracle import ref
-from gpu_util import DEV, code_mismatch_report, payload_buffers, rel_l2, to_dev, to_np, ws_for
+from gpu_util import (DEV, GUARD, close, code_mismatch_report, payload_buffers, rel_l2, to_dev,
+                      to_np, ws_for)
 
 pytestmark = pytest.mark.gpu
 
 POOL = 16
 K, R, QBITS, GROUP, MMA = 4, 64, 4, 128, dlcx.MMA_BF16
-TOL = 2e-3
+TOL = GUARD[dlcx.MMA_BF16]
 
 
 def _bits(t):
@@ -70,7 +71,7 @@ def _check_groups(codes_gpu, scales_gpu, factor_ref, L, groups, what, r=R, ref_o
         got_c = np.stack([codes_gpu[(c * L + g * G) // 2:(c * L + (g + 1) * G) // 2]
                           for c in range(r)]).reshape(-1)
         got_s = np.array([scales_gpu[(c * L) // G + g] for c in range(r)], np.float32)
-        assert rel_l2(got_s, sw) <= TOL, what
+        assert close(got_s, sw, TOL), what
         nb, ok = code_mismatch_report(got_c, cw, blk, sw, r * G, QBITS, G, ref.unpack_codes)
         assert ok, (what, g, "code mismatch that is not a one-step boundary flip")
         flips += nb
@@ -138,7 +139,7 @@ def test_full_size_matrix_sampled(m, n):
             got_c = np.stack([cg[(c * n + g * GROUP) // 2:(c * n + (g + 1) * GROUP) // 2]
                               for c in range(R)]).reshape(-1)
             got_s = np.array([sg[(c * n) // GROUP + g] for c in range(R)], np.float32)
-            assert rel_l2(got_s, sw) <= TOL, ("Q scales", k)
+            assert close(got_s, sw, TOL), ("Q scales", k)
             nb, ok = code_mismatch_report(got_c, cw, blk, sw, R * GROUP, QBITS, GROUP,
                                           ref.unpack_codes)
             assert ok, ("Q", k, g)
@@ -173,12 +174,12 @@ def test_full_size_matrix_sampled(m, n):
     ref.outer_nesterov(th_w.reshape(-1), v_w.reshape(-1), d_hat_rows.reshape(-1), synth.LR, synth.MU)
     for k in range(K):
         got = efs2[k][idx].cpu().numpy()
-        assert rel_l2(got, new_delta[k]) <= TOL, ("delta round 2", k)
+        assert close(got, new_delta[k], TOL), ("delta round 2", k)
         # the part the kernel subtracts is the decompressed average: check it at the MFMA bar
         base = deltas[k][rows] + (theta0[rows] - synth.bf16_bits_to_f32(tl2[k][rows]))
-        assert rel_l2(base - got, d_hat_rows) <= TOL, ("delta_hat via delta", k)
-    assert rel_l2(theta0[rows] - th2[idx].cpu().numpy(), theta0[rows] - th_w) <= TOL
-    assert rel_l2(v2[idx].cpu().numpy(), v_w) <= TOL
+        assert close(base - got, d_hat_rows, TOL), ("delta_hat via delta", k)
+    assert close(theta0[rows] - th2[idx].cpu().numpy(), theta0[rows] - th_w, TOL)
+    assert close(v2[idx].cpu().numpy(), v_w, TOL)
     # P phase of round 2 on the sampled groups needs the full new delta: rows of whole groups
     g0 = int(groups_m[0])
     grp_rows = np.arange(g0 * GROUP, (g0 + 1) * GROUP)
@@ -194,7 +195,7 @@ def test_full_size_matrix_sampled(m, n):
         got_s = np.array([sg[(c * m) // GROUP + g0] for c in range(R)], np.float32)
         got_c = np.stack([cg[(c * m + g0 * GROUP) // 2:(c * m + (g0 + 1) * GROUP) // 2]
                           for c in range(R)]).reshape(-1)
-        assert rel_l2(got_s, sw) <= TOL, ("P round 2 scales", k)
+        assert close(got_s, sw, TOL), ("P round 2 scales", k)
         nb, ok = code_mismatch_report(got_c, cw, p_rows, sw, R * GROUP, QBITS, GROUP, ref.unpack_codes)
         assert ok and nb <= 0.02 * R * GROUP, ("P round 2 payload", k, nb)
 
@@ -414,11 +415,11 @@ def test_matrix_beyond_2_31_elements():
     th_w, v_w = theta0[rows].copy(), v_rows.copy()
     ref.outer_nesterov(th_w.reshape(-1), v_w.reshape(-1), d_hat_rows.reshape(-1), synth.LR, synth.MU)
     got = efs[0][idx].cpu().numpy()
-    assert rel_l2(got, nd) <= TOL
+    assert close(got, nd, TOL)
     base = delta[rows] + (theta0[rows] - synth.bf16_bits_to_f32(tl2_rows))
-    assert rel_l2(base - got, d_hat_rows) <= TOL
-    assert rel_l2(theta0[rows] - th[idx].cpu().numpy(), theta0[rows] - th_w) <= TOL
-    assert rel_l2(v[idx].cpu().numpy(), v_w) <= TOL
+    assert close(base - got, d_hat_rows, TOL)
+    assert close(theta0[rows] - th[idx].cpu().numpy(), theta0[rows] - th_w, TOL)
+    assert close(v[idx].cpu().numpy(), v_w, TOL)
     # the P payload of round 2 for the last group of rows (all beyond element 2^31)
     g0 = m // GROUP - 1
     grp = np.arange(g0 * GROUP, m)

@@ -13,11 +13,11 @@ import torch
 import paper_2506_21263_amd as dlcx
 import synth
 from oracle import ref
-from gpu_util import DEV, payload_buffers, rel_l2, to_dev, to_np, ws_for
+from gpu_util import DEV, GUARD, close, payload_buffers, rel_l2, to_dev, to_np, ws_for
 
 pytestmark = pytest.mark.gpu
 
-TOL = {dlcx.MMA_FMA: 1e-5, dlcx.MMA_F32: 1e-5, dlcx.MMA_BF16: 2e-3}
+TOL = GUARD
 MODES = [dlcx.MMA_FMA, dlcx.MMA_F32, dlcx.MMA_BF16]
 MODE_IDS = ["mma_fma", "mma_f32", "mma_bf16"]
 
@@ -144,14 +144,14 @@ def test_project_p_and_q(mma, m, n, r, K, group):
     outs = [torch.zeros(r, m, device=DEV) for _ in range(K)]
     dlcx.dlcx_project(d, dlcx.PHASE_P, d_deltas, to_dev(inp.q_in), outs, ws)
     for k in range(K):
-        assert rel_l2(to_np(outs[k]), want_p[k]) <= TOL[mma], ("P", k)
+        assert close(to_np(outs[k]), want_p[k], TOL[mma]), ("P", k)
     # Q phase with the oracle's orthonormal basis
     p_hat = ref.orthonormalize(np.mean(want_p, axis=0).astype(np.float32))
     want_q = [ref.project_q(x, p_hat) for x in deltas]
     outs = [torch.zeros(r, n, device=DEV) for _ in range(K)]
     dlcx.dlcx_project(d, dlcx.PHASE_Q, d_deltas, to_dev(p_hat), outs, ws)
     for k in range(K):
-        assert rel_l2(to_np(outs[k]), want_q[k]) <= TOL[mma], ("Q", k)
+        assert close(to_np(outs[k]), want_q[k], TOL[mma]), ("Q", k)
 
 
 @pytest.mark.parametrize("mma", MODES, ids=MODE_IDS)
@@ -168,10 +168,10 @@ def test_decompress_and_error_buffer(mma, m, n, r, K, group):
     efs = [to_dev(x) for x in deltas]
     ws = ws_for(d, max(K, 1))
     dlcx.dlcx_decompress(d, to_dev(p_hat), to_dev(q_bar), out, efs, workspace=ws)
-    assert rel_l2(to_np(out), want) <= TOL[mma]
+    assert close(to_np(out), want, TOL[mma])
     for k in range(K):
         # e = delta - delta_hat: compare the correction, not the (larger) buffer
-        assert rel_l2(deltas[k] - to_np(efs[k]), deltas[k] - want_e[k]) <= TOL[mma]
+        assert close(deltas[k] - to_np(efs[k]), deltas[k] - want_e[k], TOL[mma])
     # error buffers only (no materialised delta_hat) gives the same buffers
     efs2 = [to_dev(x) for x in deltas]
     dlcx.dlcx_decompress(d, to_dev(p_hat), to_dev(q_bar), None, efs2, workspace=ws)
@@ -189,8 +189,8 @@ def test_decompress_and_error_buffer(mma, m, n, r, K, group):
                                workspace=ws)
     for k in range(K):
         assert torch.equal(efs3[k], efs[k])
-    assert rel_l2(th - to_np(d_th), th - th_w) <= TOL[mma]
-    assert rel_l2(to_np(d_v), v_w) <= TOL[mma]
+    assert close(th - to_np(d_th), th - th_w, TOL[mma])
+    assert close(to_np(d_v), v_w, TOL[mma])
 
 
 # ------------------------------------------------------------------ compress = project + quantise
@@ -209,7 +209,7 @@ def test_compress_codes_are_the_quantiser_of_its_own_factor(mma, qbits):
         factors = to_np(ws[: K * r * L * 4].view(torch.float32)).reshape(K, r, L)
         for k in range(K):
             want_f = (ref.project_p if phase == dlcx.PHASE_P else ref.project_q)(deltas[k], basis)
-            assert rel_l2(factors[k], want_f) <= TOL[mma]
+            assert close(factors[k], want_f, TOL[mma])
             cw, sw = ref.quantize(factors[k], qbits, group)   # oracle quantiser on the GPU's factor
             assert np.array_equal(to_np(codes[k]), cw)
             assert np.array_equal(to_np(scales[k]).view(np.uint32), sw.view(np.uint32))

@@ -640,3 +640,53 @@ def test_quantised_lowrank_pipeline_is_exact_on_representable_input(qbits, K):
     orc.step([theta0.copy() for _ in range(K)])               # replicas did not move
     assert np.array_equal(orc.trace["e"][0], np.zeros((m, n), np.float32))
     assert np.array_equal(orc.theta, (-0.5 * delta).astype(np.float32))
+
+
+# ---------------------------------------------------------------------------
+# warm start across a rank change (Alg. 3 resizes the basis between two rounds)
+# ---------------------------------------------------------------------------
+def test_next_basis_hand_values_shrink_grow_same():
+    q_bar = np.array([[1, 2], [3, 4], [5, 6]], np.float32)            # r_old = 3 columns, n = 2
+    fresh = np.array([[7, 8], [9, 10], [11, 12]], np.float32)
+    # shrink: the FIRST columns survive, in order; nothing of `fresh` is used
+    assert pipeline.next_basis(q_bar, 2, fresh).tolist() == [[1, 2], [3, 4]]
+    assert pipeline.next_basis(q_bar, 1, None).tolist() == [[1, 2]]
+    # same rank: the basis itself (a copy, not a view of the oracle's state)
+    same = pipeline.next_basis(q_bar, 3, fresh)
+    assert same.tolist() == q_bar.tolist() and same is not q_bar and same.dtype == np.float32
+    # grow: all old columns first, then the first r_new - r_old fresh columns, in order
+    assert pipeline.next_basis(q_bar, 5, fresh).tolist() == [[1, 2], [3, 4], [5, 6], [7, 8], [9, 10]]
+    assert pipeline.next_basis(q_bar, 4, fresh).tolist() == [[1, 2], [3, 4], [5, 6], [7, 8]]
+
+
+def test_rank_change_rounds_keep_the_leading_subspace_and_the_schedule():
+    """Three rounds of the oracle with the rank going 6 -> 3 -> 5 on one worker's exactly
+    rank-3 pseudo-gradient whose right singular vectors are the first basis columns.  What the
+    mathematics fixes: a basis cut to the first 3 columns still spans the gradient's row space,
+    so the round reproduces it exactly; grown back with arbitrary fresh columns it still does
+    (the fresh directions only add zero components); and the feedback of every round uses the
+    factors at the rank they were formed with (the error buffer stays at rounding level)."""
+    rng = np.random.default_rng(11)
+    m, n = 24, 32
+    U = synth.orthonormal_columns(rng, m, 3)
+    V = synth.orthonormal_columns(rng, n, 6)
+    G = ((U * np.array([3.0, 2.0, 1.0])) @ V[:, :3].T)                 # rank 3
+    theta0 = rng.standard_normal((m, n)).astype(np.float32)
+    orc = pipeline.MatrixOracle(theta0, 1, V.T.astype(np.float32), None, 16)
+    ranks = [6, 3, 5]
+    for t, r in enumerate(ranks, start=1):
+        assert orc.q_in.shape[0] == r
+        tl = [(orc.theta.astype(np.float64) - G).astype(np.float32)]
+        orc.step(tl)
+        assert orc.p_hat.shape == (r, m) and orc.q_bar.shape == (r, n)
+        want = orc.trace["delta"][0].astype(np.float64)
+        assert np.linalg.norm(orc.delta_hat() - want) <= 2e-6 * np.linalg.norm(want), (t, r)
+        if t < len(ranks):
+            fresh = rng.standard_normal((8, n)).astype(np.float32)
+            nb = pipeline.next_basis(orc.q_bar, ranks[t], fresh)
+            keep = min(r, ranks[t])
+            assert np.array_equal(nb[:keep], orc.q_bar[:keep])
+            orc.set_basis(nb)
+    # feedback at the old rank: e = delta - Delta_hat stayed at rounding level throughout
+    assert np.abs(orc.trace["e"][0]).max() <= 1e-5
+    assert orc.n_applied == len(ranks) - 1
