@@ -373,6 +373,53 @@ def mfma_peak(args):
                       "workgroups": wgs, "mfma_per_wavefront": iters * 8}), flush=True)
 
 
+def traffic_probe(args):
+    """What the memory system gives the fused kernel's mix of streams under the simplest access
+    pattern: dlcx_traffic_probe (flat sweep of the same K + K + 2 arrays, same bytes per element,
+    no matrix-core work) on one matrix-sized set of arrays per shape of the configuration."""
+    import torch
+
+    import paper_2506_21263_amd as dlcx
+    import synth
+
+    dlcx.lib()
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    cfg = synth.CONFIGS[args.config]
+    K = args.workers or cfg["K"]
+    dt = torch.bfloat16 if cfg["theta_l"] == "bf16" else torch.float32
+    tl_bytes = 2 if cfg["theta_l"] == "bf16" else 4
+    bpp = (8 + tl_bytes) * K + 16
+    shapes = []
+    for sh in cfg["layer_shapes"]:
+        if sh not in shapes:
+            shapes.append(sh)
+    res = []
+    for (m, n) in shapes:
+        numel = m * n
+        theta, v = torch.randn(numel, device=dev), torch.zeros(numel, device=dev)
+        ef = [torch.zeros(numel, device=dev) for _ in range(K)]
+        tl = [torch.randn(numel, device=dev).to(dt) for _ in range(K)]
+        for _ in range(2):
+            dlcx.dlcx_traffic_probe(tl, ef, theta, v)
+        torch.cuda.synchronize()
+        dlcx.dlcx_profile_enable(True)
+        for _ in range(args.steps):
+            dlcx.dlcx_traffic_probe(tl, ef, theta, v)
+        torch.cuda.synchronize()
+        ms, cnt = dlcx.dlcx_profile_read()["traffic_probe"]
+        dlcx.dlcx_profile_enable(False)
+        res.append({"arrays_of": "%dx%d" % (m, n), "ms_per_launch": ms / cnt,
+                    "GBps": bpp * numel / (ms / cnt * 1e-3) / 1e9})
+        del theta, v, ef, tl
+        torch.cuda.empty_cache()
+    worst = min(r["GBps"] for r in res)
+    print(json.dumps({"metric": "flat sweep of the fused kernel's traffic mix (dlcx_traffic_probe)",
+                      "value": worst, "unit": "GB/s", "frac_of_8TBps": worst / HBM_PEAK_GBS,
+                      "bytes_per_element": bpp, "K": K, "theta_l": cfg["theta_l"],
+                      "per_shape": res}), flush=True)
+
+
 # ---------------------------------------------------------------------------------------------
 # streams restricted to a subset of the compute units (config 4: the outer step and a synthetic
 # inner-step load side by side)
@@ -458,6 +505,12 @@ def lowrank(args):
         (len(stage.mats), params / 1e9, K, torch.cuda.memory_allocated() / 1e9))
 
     use_graph = {"on": False}
+    if load is not None:
+        # Everything of this run is issued from a stream of torch's own (non-blocking) instead of
+        # the null stream: streams created with a compute-unit mask are ordinary blocking streams,
+        # and every operation on the null stream (the fork and join events of a step) would wait
+        # for, and be waited for by, all work on them -- the load and the step would serialise.
+        torch.cuda.set_stream(torch.cuda.Stream(device=device))
 
     def issue_load():
         with torch.cuda.stream(load["stream"]):
@@ -724,6 +777,8 @@ def main():
                     help="power iterations per round (1 = the paper's compressor)")
     ap.add_argument("--mfma-peak", action="store_true",
                     help="measure the attainable bf16 matrix-core rate and exit")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="time the flat sweep of the fused kernel's traffic mix and exit")
     ap.add_argument("--probe", action="store_true",
                     help="counter run: plain random inputs, one 1 GiB copy, two steps, no timing")
     args = ap.parse_args()
@@ -734,6 +789,8 @@ def main():
 
     if args.mfma_peak:
         return mfma_peak(args)
+    if args.traffic_probe:
+        return traffic_probe(args)
     out = quant_only(args) if args.quant_only else lowrank(args)
     if out is None:
         return

@@ -113,8 +113,11 @@ int dlcx_decompress_apply(const dlcx_desc *desc, const float *p_hat, const float
 /* One pass over the matrix for everything Alg. 2 does between two compressions (outer step
  * t >= 2), in its order:  e_i <- delta_i - Delta_hat  (previous round's average, P_hat Q_bar^T,
  * never written to memory);  delta_i <- (theta_g - theta_l,i) + e_i  with theta_g still the
- * value of step t-1;  then  theta_g <- OuterOpt(theta_g, Delta_hat).  Same result as
- * dlcx_decompress (error buffers), K x dlcx_delta_ef and dlcx_outer_nesterov in that order. */
+ * value of step t-1;  then  theta_g <- OuterOpt(theta_g, Delta_hat).  The same steps as
+ * dlcx_decompress (error buffers), K x dlcx_delta_ef and dlcx_outer_nesterov in that order, equal
+ * to them up to fp32 rounding and not bit for bit: dlcx_delta_ef evaluates (theta_g - theta_l) + e
+ * in fp64 and rounds once, this pass rounds theta_g - theta_l, delta_i - Delta_hat and their sum
+ * to fp32 one after the other (at most one unit in the last place of each apart). */
 int dlcx_ef_delta_apply(const dlcx_desc *desc, const float *p_hat, const float *q_bar, int K,
                         const void *const *theta_l_host, int theta_l_dtype,
                         float *const *ef_inout_host, float *theta_g, float *v, float lr, float mu,
@@ -127,7 +130,12 @@ int dlcx_ef_delta_apply(const dlcx_desc *desc, const float *p_hat, const float *
  * (r_prev == 0: outer step 1, there is no previous average: only delta_i <- (theta_g -
  * theta_l,i) + e_i and the projection; p_hat, q_bar and v are then unused).  On return the
  * workspace starts with the K fp32 factors, as after dlcx_compress_batched.  The workspace must
- * be sized (dlcx_workspace_bytes) for a descriptor whose r is the larger of the two ranks. */
+ * be sized (dlcx_workspace_bytes) for a descriptor whose r is the larger of the two ranks.
+ * Which arithmetic forms delta_i depends on the path taken: the one-sweep kernel (MFMA modes,
+ * desc->r <= 64) and dlcx_ef_delta_apply (MFMA modes above that rank, and the FMA mode with
+ * r_prev > 0) use the three fp32 roundings described there; the FMA mode at r_prev == 0 calls
+ * dlcx_delta_ef (fp64 sum, one rounding).  The last bit of delta_i may therefore differ between
+ * paths; every path is within the mode's tolerance of the oracle, which follows dlcx_delta_ef. */
 int dlcx_ef_delta_apply_compress(const dlcx_desc *desc, int32_t r_prev, const float *p_hat,
                                  const float *q_bar, int K, const void *const *theta_l_host,
                                  int theta_l_dtype, float *const *ef_inout_host, float *theta_g,
@@ -178,6 +186,17 @@ int dlcx_requantize(float *x_inout, int64_t count, int qbits, int group, void *s
  * exponents and mantissas, four operand pairs in rotation, which is what real data looks like to
  * the multipliers -- the rate is lower, because the clock follows the power drawn. */
 int dlcx_mfma_peak_probe(int workgroups, int iters, int operands, float *out, void *stream);
+
+/* Measurement aid, not a step of the method: the HBM traffic of one launch of the fused kernel
+ * behind dlcx_ef_delta_apply_compress -- per element, K error buffers read and written, K
+ * replicas read, theta_g and v read and written -- as a flat sweep: one 16-byte position of every
+ * array per thread, workgroups in address order, no matrix-core work.  All K + 2 fp32 arrays are
+ * OVERWRITTEN with sums of what was read, which mean nothing.  numel is a multiple of 1024.  Timed
+ * with the profiler (kernel "traffic_probe"), it gives the rate the memory system reaches for
+ * this mix of streams under the simplest access pattern, the yardstick for the fused kernel. */
+int dlcx_traffic_probe(int K, const void *const *theta_l_host, int theta_l_dtype,
+                       float *const *ef_inout_host, float *theta_g, float *v, int64_t numel,
+                       void *stream);
 
 /* Communication model of Sec. 2.4.1 (host only).  A ring all-reduce between `clusters` clusters
  * moves 2 (clusters - 1) / clusters of the payload over the link between two of them;
@@ -230,29 +249,45 @@ int dlcx_select_rank_from(const int32_t *rprime_dev, int n_matrices, int32_t *rp
 
 /* ---- helpers: the steps the entry points above are made of ---------------------------- */
 
-/* Size of one payload; returns codes + scales bytes, 0 on a bad descriptor. */
+/* Size of one worker's payload for one factor: what Alg. 1 hands to the AllReduce of Alg. 2 is
+ * the quantised FACTORS (Sec. 4.1: r_1 = 2048 is "about 2x" on a hidden-8192 model, i.e.
+ * (m + n) r / (m n) = 0.5), r * L codes of qbits bits plus one fp32 scale per group.  Returns
+ * codes + scales bytes (also through the two pointers, either may be NULL), 0 on a bad
+ * descriptor.  Host only. */
 size_t dlcx_payload_bytes(const dlcx_desc *desc, int phase, size_t *codes_bytes,
                           size_t *scales_bytes);
-/* Workspace needed by any per-matrix call with up to K workers. */
+/* Device scratch needed by any per-matrix entry point above for this descriptor with up to K
+ * workers (fp32 factors of Alg. 1 before quantisation, operand fragments, partial sums, the
+ * fp64 scratch of the orthonormalisation and of Alg. 3's r').  0 on a bad descriptor.  Host only. */
 size_t dlcx_workspace_bytes(const dlcx_desc *desc, int K);
+/* Device scratch of dlcx_select_rank (Alg. 3) for these matrices.  Host only. */
 size_t dlcx_select_rank_workspace_bytes(const dlcx_desc *descs_host, int n_matrices);
 
-/* Projection only: factors_out_host[k] (r x L fp32) = delta_k * Q_in or delta_k^T * P_hat. */
+/* The LOWRANK step (1) of Alg. 1 alone, one of its two products for K workers:
+ * factors_out_host[k] (r x L fp32) = delta_k * Q_in (phase P) or delta_k^T * P_hat (phase Q),
+ * unquantised. */
 int dlcx_project(const dlcx_desc *desc, int phase, int K, const float *const *deltas_host,
                  const float *basis, float *const *factors_out_host, void *workspace,
                  void *stream);
-/* Quantiser only (Alg. 1 step 2) on `count` floats in consecutive groups. */
+/* The QUANTIZE step (2) of Alg. 1 alone on `count` floats in consecutive groups: per group
+ * scale = amax / qmax and code = clamp(rint(x * (qmax / amax))), qmax = 2^(qbits-1) - 1, round
+ * half to even; a group whose amax is below 2^-100 gives scale 0 and codes 0. */
 int dlcx_quantize(const float *x, int64_t count, int qbits, int group, uint8_t *codes_out,
                   float *scales_out, void *stream);
-/* Mean of K dequantised payloads of `count` elements, no orthonormalisation. */
+/* The AllReduce-average of Alg. 2 alone: mean_out = (1/K) sum_k dequant(codes_k, scales_k) over
+ * `count` elements, workers added in index order (fp64 sum, one rounding), no
+ * orthonormalisation. */
 int dlcx_dequant_average(int K, const uint8_t *const *codes_host,
                          const float *const *scales_host, int64_t count, int qbits, int group,
                          float *mean_out, void *stream);
-/* Thin-QR Q-factor with positive diagonal of R of the L x r factor p_inout (r x L storage),
- * in place.  A column whose component orthogonal to the earlier columns is at most 1e-6 of
+/* Orthonormalisation of the averaged P factor between the two products of Alg. 1's LOWRANK
+ * step (the shared-basis power iteration the paper cites for it; the paper itself is silent on
+ * the method).  Thin-QR Q-factor with positive diagonal of R of the L x r factor p_inout (r x L
+ * storage), in place.  A column whose component orthogonal to the earlier columns is at most 1e-6 of
  * its norm (or that is zero) becomes the zero column. */
 int dlcx_orthonormalize(int64_t L, int32_t r, float *p_inout, void *workspace, void *stream);
-/* The orthonormalisation and the effective rank for ALL matrices of a stage at once (these
+/* The orthonormalisation (Alg. 1, LOWRANK step) and the effective rank r' (Alg. 3's
+ * "calculate r'_t with the averaged gradient") for ALL matrices of a stage at once (these
  * steps are short and latency-bound per matrix; batched, each matrix gets its own workgroups of
  * one launch).  Matrix i has shape descs_host[i]; p_inout_host[i] is its r x m factor,
  * q_bars_host[i] its r x n factor; rprime_out_dev receives n_matrices ints.  The workspace
@@ -263,7 +298,9 @@ int dlcx_orthonormalize_batched(const dlcx_desc *descs_host, float *const *p_ino
 int dlcx_effective_rank_batched(const dlcx_desc *descs_host, const float *const *q_bars_host,
                                 int n_matrices, double tau, int32_t *rprime_out_dev,
                                 void *workspace, void *stream);
-/* r' of one matrix, written to a DEVICE int32 (0 when Q_bar is all zero); asynchronous. */
+/* Alg. 3's r'_t for one matrix (the paper gives no formula; see dlcx_select_rank for the
+ * definition used): the smallest k whose k largest eigenvalues of Q_bar^T Q_bar hold at least
+ * tau of the trace, written to a DEVICE int32 (0 when Q_bar is all zero); asynchronous. */
 int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,
                         int32_t *rprime_out_dev, void *workspace, void *stream);
 

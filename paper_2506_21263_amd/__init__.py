@@ -58,6 +58,7 @@ SYMBOLS = {
     "dlcx_ef_update": (_int, [_int, _vp, _vp, _i64, _vp]),
     "dlcx_requantize": (_int, [_vp, _i64, _int, _int, _vp]),
     "dlcx_mfma_peak_probe": (_int, [_int, _int, _int, _vp, _vp]),
+    "dlcx_traffic_probe": (_int, [_int, _vp, _int, _vp, _vp, _vp, _i64, _vp]),
     "dlcx_comm_seconds": (C.c_double, [C.c_double, _int, C.c_double]),
     "dlcx_plan_overlap": (_int, [_dp, _int, C.c_double, _int, _i32, _i32, _int, C.c_double,
                                  C.c_double, _i32, _vp, _vp, _vp]),
@@ -236,6 +237,15 @@ def dlcx_ef_update(ef_inout, delta_hat, numel=None, stream=None):
 def dlcx_mfma_peak_probe(workgroups, iters, out, random_operands=False, stream=None):
     _check(lib().dlcx_mfma_peak_probe(workgroups, iters, 1 if random_operands else 0, _ptr(out),
                                       _stream(stream)), "dlcx_mfma_peak_probe")
+
+
+def dlcx_traffic_probe(theta_l, ef_inout, theta_g, v, numel=None, stream=None):
+    dt = BF16 if theta_l[0].dtype == torch.bfloat16 else F32
+    n = theta_g.numel() if numel is None else numel
+    tp, k1 = _ptr_array(list(theta_l))
+    ep, k2 = _ptr_array(list(ef_inout))
+    _check(lib().dlcx_traffic_probe(len(ef_inout), tp, dt, ep, _ptr(theta_g), _ptr(v), n,
+                                    _stream(stream)), "dlcx_traffic_probe")
 
 
 def dlcx_requantize(x_inout, count, qbits, group, stream=None):

@@ -31,7 +31,7 @@ enum KernelId {
     KID_DELTA_EF = 0, KID_NESTEROV, KID_QUANTIZE, KID_DEQUANT_AVG, KID_PACK, KID_PROJECT_P,
     KID_PROJECT_Q, KID_SUM_SLABS, KID_RECONSTRUCT, KID_GRAM, KID_CHOL, KID_APPLY_W, KID_JACOBI,
     KID_ROUND, KID_QUANT_ROUND, KID_REQUANT, KID_EF_UPDATE,
-    KID_MFMA_PEAK, KID_COUNT
+    KID_MFMA_PEAK, KID_TRAFFIC_PROBE, KID_COUNT
 };
 struct Timed {
     Timed(int kid, hipStream_t st);
@@ -75,6 +75,8 @@ int launch_ef_update(int K, const PtrPack<float *> &ef, const float *d, int64_t 
 
 // ---- measurement aid (k_peak.hip) -------------------------------------------------------
 int launch_mfma_peak(int workgroups, int iters, int operands, float *out, hipStream_t st);
+int launch_traffic_probe(int K, const PtrPack<float *> &ef, const PtrPack<const void *> &tl,
+                         bool tl_bf16, float *theta, float *vel, int64_t numel, hipStream_t st);
 
 // ---- rank-r products ------------------------------------------------------------------
 // P_k = delta_k * Q_in   (delta m x n, q_in r x n, out r x m)

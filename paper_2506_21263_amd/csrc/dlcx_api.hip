@@ -155,7 +155,7 @@ static const char *const kKernelNames[KID_COUNT] = {
     "delta_ef", "outer_nesterov", "quantize", "dequant_average", "pack_fragments", "project_p",
     "project_q", "sum_slabs", "reconstruct", "gram_partials", "chol_inverse", "apply_w",
     "jacobi_rank", "round_fused", "quant_round", "requantize", "ef_update",
-    "mfma_peak"};
+    "mfma_peak", "traffic_probe"};
 
 int dlcx_profile_enable(int on) {
     std::lock_guard<std::mutex> lock(g_prof_mutex);
@@ -307,6 +307,28 @@ int dlcx_mfma_peak_probe(int workgroups, int iters, int operands, float *out, vo
     if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24)) return DLCX_EINVAL;
     if ((operands != 0 && operands != 1) || !out || !aligned16(out)) return DLCX_EINVAL;
     return launch_mfma_peak(workgroups, iters, operands, out, as_stream(stream));
+}
+
+int dlcx_traffic_probe(int K, const void *const *theta_l_host, int theta_l_dtype,
+                       float *const *ef_inout_host, float *theta_g, float *v, int64_t numel,
+                       void *stream) {
+    if (K < 1 || K > DLCX_MAX_WORKERS || numel < 0 || numel % 1024) return DLCX_EINVAL;
+    if (theta_l_dtype != DLCX_F32 && theta_l_dtype != DLCX_BF16) return DLCX_EINVAL;
+    if (numel / 1024 > 0x7fffffff) return DLCX_EINVAL;
+    if (numel == 0) return DLCX_OK;
+    if (!theta_l_host || !ef_inout_host || !theta_g || !v || !aligned16(theta_g) || !aligned16(v))
+        return DLCX_EINVAL;
+    PtrPack<float *> ef;
+    PtrPack<const void *> tl;
+    for (int k = 0; k < K; ++k) {
+        if (!theta_l_host[k] || !ef_inout_host[k] || !aligned16(theta_l_host[k]) ||
+            !aligned16(ef_inout_host[k]))
+            return DLCX_EINVAL;
+        ef.p[k] = ef_inout_host[k];
+        tl.p[k] = theta_l_host[k];
+    }
+    return launch_traffic_probe(K, ef, tl, theta_l_dtype == DLCX_BF16, theta_g, v, numel,
+                                as_stream(stream));
 }
 
 int dlcx_ef_update(int K, float *const *ef_inout_host, const float *delta_hat, int64_t numel,
@@ -605,10 +627,13 @@ int dlcx_ef_delta_apply_compress(const dlcx_desc *desc, int32_t r_prev, const fl
             !aligned16(codes_out_host[k]) || !aligned16(scales_out_host[k]))
             return DLCX_EINVAL;
     }
-    // No fused kernel in the FMA mode.  Above rank 64 the fused kernel would need one launch per
-    // worker (its accumulators are r x 32 per worker and wavefront) and re-read the fragments of
-    // both products for every tile and worker; the feedback / update sweep followed by the
-    // projection kernel moves 16 more bytes per element and is about twice as fast there.
+    // No fused kernel in the FMA mode.  Above rank 64 the fused kernel needs a launch per two
+    // workers (ranks up to 128; its accumulators are r x 32 per worker and wavefront) or per
+    // worker (above), each launch reconstructing the previous average again and re-reading the
+    // fragments of both products; the feedback / update sweep followed by the projection kernel
+    // moves 16 more bytes per element and is faster there (measured at ranks 96 and 128 on the
+    // benchmark shapes with two workers per launch: 0.91 against 1.30 ms for an 8192 x 8192
+    // matrix with four workers, 3.45 against 4.30 ms for 8192 x 28672).
     if (desc->mma == DLCX_MMA_FMA || desc->r > 64) {
         if (r_prev > 0) {
             dlcx_desc dp = *desc;

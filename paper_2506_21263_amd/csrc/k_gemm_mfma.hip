@@ -1404,7 +1404,6 @@ int launch_reconstruct_mfma(int mma, int64_t m, int64_t n, int r, const float *p
 }
 
 // ---- fused round: workspace layout and launch ------------------------------------------------
-constexpr int kRoundWgTarget = 512;  // workgroups wanted per launch (column ranges per row block)
 constexpr int kComputeUnits = 256;
 struct RoundPlan {
     int chunks;        // column ranges per row block = slabs per worker
@@ -1415,30 +1414,20 @@ struct RoundPlan {
 static RoundPlan round_plan(int64_t m, int64_t n, int r) {
     RoundPlan p;
     (void)r;
-    p.kc = 4;
+    p.kc = 4;  // workers per launch: 4 x 2 basis blocks x 16 accumulator registers per wavefront
+    // Column ranges per row block, from sweeps of this kernel over the benchmark shapes (one
+    // workgroup occupies a compute unit): four ranges once the matrix is 2048 columns wide (at
+    // 8192 columns 13 % faster than one or two, whatever the number of rows; at 28672 columns
+    // the count does not matter), one for narrower matrices; more, up to eight, when that is
+    // what it takes to give every compute unit two workgroups, but never ranges under 512
+    // columns (two tiles per wavefront), where start-up and the slab sums cost more than a
+    // fuller machine gains.
     const int64_t rows = ceil_div(m, 32);
-    int64_t chunks = ceil_div(kRoundWgTarget, rows);
-    const int64_t max_chunks = ceil_div(n, 256);
-    if (chunks > max_chunks) chunks = max_chunks;
-    if (chunks > 4) chunks = 4;
-    if (chunks < 1) chunks = 1;
-    // One workgroup occupies a compute unit, so the launch runs in rounds of kComputeUnits
-    // workgroups: among the admissible numbers of column ranges from there up, take the one
-    // that leaves the last round fullest (the first such, for the least slab traffic).
-    {
-        const int64_t top = max_chunks < 4 ? max_chunks : 4;
-        double best = 0.0;
-        int64_t pick = chunks;
-        for (int64_t c = chunks; c <= top; ++c) {
-            const int64_t wgs = rows * c;
-            const double eff = (double)wgs / (double)(ceil_div(wgs, kComputeUnits) * kComputeUnits);
-            if (eff > best + 1e-9) {
-                best = eff;
-                pick = c;
-            }
-        }
-        chunks = pick;
-    }
+    int64_t chunks = n >= 2048 ? 4 : 1;
+    const int64_t need = ceil_div(2 * kComputeUnits, rows);
+    if (chunks < need) chunks = need < 8 ? need : 8;
+    const int64_t widest = n / 512 > 1 ? n / 512 : 1;
+    if (chunks > widest) chunks = widest;
     p.cols = ceil_div(ceil_div(n, chunks), 256) * 256;
     p.chunks = (int)ceil_div(n, p.cols);
     return p;

@@ -68,6 +68,60 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, int operands,
     out[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// Second measurement aid: the HBM traffic of one launch of the fused round kernel (per element,
+// K error buffers read and written, K replicas read, theta and v read and written) as a flat
+// sweep -- one 16-byte position of every array per thread, workgroups in address order, no
+// matrix-core work, the same non-temporal accesses.  What it reaches is what the memory system
+// gives this mix of streams under the simplest access pattern; the values written are sums of
+// what was read and mean nothing.
+template <bool TLBF16>
+__global__ __launch_bounds__(256) void traffic_probe_kernel(PtrPack<float *> ef,
+                                                            PtrPack<const void *> tl, int K,
+                                                            float *__restrict__ theta,
+                                                            float *__restrict__ vel) {
+    typedef float pv4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t pu2 __attribute__((ext_vector_type(2)));
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    const pv4 t = __builtin_nontemporal_load(reinterpret_cast<const pv4 *>(theta + i));
+    const pv4 v = __builtin_nontemporal_load(reinterpret_cast<const pv4 *>(vel + i));
+    pv4 x[DLCX_MAX_WORKERS / 2], l[DLCX_MAX_WORKERS / 2];
+    for (int k0 = 0; k0 < K; k0 += DLCX_MAX_WORKERS / 2) {
+#pragma unroll
+        for (int kk = 0; kk < DLCX_MAX_WORKERS / 2; ++kk) {
+            if (k0 + kk < K) {
+                x[kk] = __builtin_nontemporal_load(reinterpret_cast<const pv4 *>(ef.p[k0 + kk] + i));
+                if (TLBF16) {
+                    const pu2 b = __builtin_nontemporal_load(reinterpret_cast<const pu2 *>(
+                        reinterpret_cast<const uint16_t *>(tl.p[k0 + kk]) + i));
+                    l[kk] = pv4{__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
+                                __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u)};
+                } else {
+                    l[kk] = __builtin_nontemporal_load(reinterpret_cast<const pv4 *>(
+                        reinterpret_cast<const float *>(tl.p[k0 + kk]) + i));
+                }
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < DLCX_MAX_WORKERS / 2; ++kk)
+            if (k0 + kk < K)
+                __builtin_nontemporal_store((t - l[kk]) + x[kk],
+                                            reinterpret_cast<pv4 *>(ef.p[k0 + kk] + i));
+    }
+    __builtin_nontemporal_store(t + v, reinterpret_cast<pv4 *>(theta + i));
+    __builtin_nontemporal_store(t - v, reinterpret_cast<pv4 *>(vel + i));
+}
+
+int launch_traffic_probe(int K, const PtrPack<float *> &ef, const PtrPack<const void *> &tl,
+                         bool tl_bf16, float *theta, float *vel, int64_t numel, hipStream_t st) {
+    Timed timed(KID_TRAFFIC_PROBE, st);
+    const dim3 grid((unsigned)(numel / 1024));
+    if (tl_bf16)
+        hipLaunchKernelGGL(traffic_probe_kernel<true>, grid, dim3(256), 0, st, ef, tl, K, theta, vel);
+    else
+        hipLaunchKernelGGL(traffic_probe_kernel<false>, grid, dim3(256), 0, st, ef, tl, K, theta, vel);
+    return check_launch("traffic_probe");
+}
+
 int launch_mfma_peak(int workgroups, int iters, int operands, float *out, hipStream_t st) {
     Timed timed(KID_MFMA_PEAK, st);
     hipLaunchKernelGGL(mfma_peak_kernel, dim3((unsigned)workgroups), dim3(256), 0, st, iters,

@@ -43,6 +43,7 @@ CASES = [
     ("ragged", 528, 336, 3, 20, 4, 16, "bf16", 2, 1e-3),
     # ranks above 64: the fused entry point takes the sweep-plus-projection form
     ("rank96", 640, 2048, 2, 96, 4, 128, "bf16", 2, 1e-3),
+    ("rank128-K3", 768, 1280, 3, 128, 4, 128, "bf16", 2, 1e-3),
     ("rank256-K5", 2048, 512, 5, 256, 8, 64, "f32", 2, 1e-3),
 ]
 
@@ -627,3 +628,105 @@ def test_free_running_across_rank_changes(mma, fused):
     for i in range(K):
         e_next = to_np(M.ef[i]).astype(np.float64) - to_np(d_hat)
         assert rel_l2(sum_d + e_next, sum_g[i]) <= 1e-6 * len(ranks)
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+def test_resume_two_plus_one_equals_three_rounds(fused):
+    """Checkpoint / resume: the whole outer state is caller-owned -- theta_g, v, the K error
+    buffers, the last factors P_hat / Q_bar (Q_bar is also the warm start), their rank and the
+    round counter.  Three outer steps in one go against two steps, the state copied to the host
+    and into brand-new device buffers behind a new stage driver, then the third step: every
+    buffer bit for bit the same."""
+    shapes = [(384, 512), (512, 256)]
+    K, r, qbits, group = 3, 24, 4, 64
+    inps = [synth.MatrixInputs(m, n, K, r, seed=7700 + a, sigma=1e-3, alpha=1.0, theta_l="bf16")
+            for a, (m, n) in enumerate(shapes)]
+
+    def fresh_stage(states=None, t=0):
+        mats = []
+        for a, inp in enumerate(inps):
+            M = MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), qbits, group, dlcx.MMA_BF16)
+            if states is not None:
+                s = states[a]
+                M.theta_g.copy_(to_dev(s["theta_g"]))
+                M.v.copy_(to_dev(s["v"]))
+                for k in range(K):
+                    M.ef[k].copy_(to_dev(s["ef"][k]))
+                M.p_hat.copy_(to_dev(s["p_hat"]))
+                M.q_bar.copy_(to_dev(s["q_bar"]))
+                M.r, M.r_prev = s["r"], s["r_prev"]
+            mats.append(M)
+        st = Stage(mats, synth.LR, synth.MU, fused=fused, warm_start=True, streams=2,
+                   measure_rank=True)
+        st.t = t
+        return st
+
+    def locals_for(st, t):
+        # replicas depend on the round only (not on the state), so both runs see the same bytes
+        return [[to_dev(inp.theta_local(inp.theta_g, t, i)) for i in range(K)] for inp in inps]
+
+    def snapshot(st):
+        torch.cuda.synchronize()
+        return [dict(theta_g=to_np(M.theta_g), v=to_np(M.v), ef=[to_np(e) for e in M.ef],
+                     p_hat=to_np(M.p_hat), q_bar=to_np(M.q_bar), r=M.r, r_prev=M.r_prev)
+                for M in st.mats]
+
+    straight = fresh_stage()
+    for t in (1, 2, 3):
+        straight.step(locals_for(straight, t))
+    want = snapshot(straight)
+    first = fresh_stage()
+    for t in (1, 2):
+        first.step(locals_for(first, t))
+    saved = snapshot(first)
+    saved_t = first.t
+    del first
+    resumed = fresh_stage(saved, saved_t)
+    resumed.step(locals_for(resumed, 3))
+    got = snapshot(resumed)
+    assert resumed.t == 3
+    for a in range(len(shapes)):
+        for key in ("theta_g", "v", "p_hat", "q_bar"):
+            assert np.array_equal(got[a][key].view(np.uint32), want[a][key].view(np.uint32)), (a, key)
+        for k in range(K):
+            assert np.array_equal(got[a]["ef"][k].view(np.uint32), want[a]["ef"][k].view(np.uint32))
+        assert (got[a]["r"], got[a]["r_prev"]) == (want[a]["r"], want[a]["r_prev"])
+    assert torch.equal(resumed.rprime_dev, straight.rprime_dev)
+
+
+def test_step_beside_a_foreign_busy_stream_is_bit_equal():
+    """The one-step-delay scheme runs the outer step while local training keeps the GPU busy
+    (Sec. 2.3).  Outer steps issued while another stream runs a queue of bf16 GEMMs (the
+    stand-in for the inner steps) leave, bit for bit, the state they leave when run alone."""
+    shapes = [(512, 768), (768, 512), (1024, 256)]
+    K, r = 4, 32
+
+    def run(busy):
+        mats, tls = [], []
+        for a, (m, n) in enumerate(shapes):
+            inp = synth.MatrixInputs(m, n, K, r, seed=8800 + a, sigma=1e-3, alpha=1.0, theta_l="bf16")
+            mats.append(MatrixState(to_dev(inp.theta_g), K, to_dev(inp.q_in), 8, 64, dlcx.MMA_BF16))
+            tls.append([to_dev(inp.theta_local(inp.theta_g, 1, i)) for i in range(K)])
+        st = Stage(mats, synth.LR, synth.MU, fused=True, warm_start=True, streams=2,
+                   measure_rank=True)
+        load = torch.cuda.Stream(device=DEV)
+        a = torch.randn(2048, 2048, device=DEV, dtype=torch.bfloat16)
+        b = torch.randn(2048, 2048, device=DEV, dtype=torch.bfloat16)
+        c = torch.empty(2048, 2048, device=DEV, dtype=torch.bfloat16)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            if busy:
+                with torch.cuda.stream(load):
+                    for _ in range(40):
+                        torch.matmul(a, b, out=c)
+            st.step(tls)
+        torch.cuda.synchronize()
+        return st
+
+    alone, beside = run(False), run(True)
+    for A, B in zip(alone.mats, beside.mats):
+        assert torch.equal(A.theta_g, B.theta_g) and torch.equal(A.v, B.v)
+        assert torch.equal(A.q_bar, B.q_bar) and torch.equal(A.p_hat, B.p_hat)
+        for x, y in zip(A.ef, B.ef):
+            assert torch.equal(x, y)
+    assert torch.equal(alone.rprime_dev, beside.rprime_dev)

@@ -69,7 +69,8 @@ def test_whole_stage_three_streams_properties_and_single_stream_bits(CFG):
     qbits = cfg["qbits"]
     qmax = 2 ** (qbits - 1) - 1
 
-    stage, locals_ = bench.build_stage(CFG, dlcx.MMA_BF16, layers, DEV, True, 3)
+    stage, inputs_, _ = bench.build_stage(CFG, dlcx.MMA_BF16, layers, DEV, True, 3)
+    locals_ = [t["theta_l"] for t in inputs_]
     assert stage.nstreams == 3 and stage.batched and len(stage.mats) == 7 * layers
     inputs = _input_digest(stage, locals_)
     theta0 = torch.stack([_digest(M.theta_g) for M in stage.mats]).cpu().numpy()
@@ -108,9 +109,10 @@ def test_whole_stage_three_streams_properties_and_single_stream_bits(CFG):
             assert bool(torch.isfinite(e[:64]).all())
     multi = _state_digest(stage)
 
-    del stage, locals_, M, e, codes, scales
+    del stage, locals_, inputs_, M, e, codes, scales
     torch.cuda.empty_cache()
-    stage, locals_ = bench.build_stage(CFG, dlcx.MMA_BF16, layers, DEV, True, 3)
+    stage, inputs_, _ = bench.build_stage(CFG, dlcx.MMA_BF16, layers, DEV, True, 3)
+    locals_ = [t["theta_l"] for t in inputs_]
     assert np.array_equal(_input_digest(stage, locals_), inputs), "the seeded generator did not repeat"
     for _ in range(STEPS):
         stage.step(locals_, serial=True)

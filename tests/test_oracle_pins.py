@@ -690,3 +690,30 @@ def test_rank_change_rounds_keep_the_leading_subspace_and_the_schedule():
     # feedback at the old rank: e = delta - Delta_hat stayed at rounding level throughout
     assert np.abs(orc.trace["e"][0]).max() <= 1e-5
     assert orc.n_applied == len(ranks) - 1
+
+
+def test_oracle_resume_two_plus_one_equals_three_rounds():
+    """The outer state is {theta, v, e_i, P_hat, Q_bar, basis, t}: three rounds in one object
+    equal two rounds, the state copied into a new object, and the third round there."""
+    m, n, K, r = 48, 64, 2, 6
+    inp = synth.MatrixInputs(m, n, K, r, seed=31, sigma=1e-3, alpha=1.0)
+
+    def tl(t):
+        return [inp.theta_local(inp.theta_g, t, i) for i in range(K)]
+
+    a = pipeline.MatrixOracle(inp.theta_g, K, inp.q_in, 4, 16)
+    for t in (1, 2, 3):
+        a.step(tl(t))
+        a.set_basis(a.q_bar)
+    b = pipeline.MatrixOracle(inp.theta_g, K, inp.q_in, 4, 16)
+    for t in (1, 2):
+        b.step(tl(t))
+        b.set_basis(b.q_bar)
+    c = pipeline.MatrixOracle(b.theta.copy(), K, b.q_in.copy(), 4, 16)
+    c.v, c.ef = b.v.copy(), [e.copy() for e in b.ef]
+    c.p_hat, c.q_bar, c.t, c.n_applied = b.p_hat.copy(), b.q_bar.copy(), b.t, b.n_applied
+    c.step(tl(3))
+    assert np.array_equal(c.theta, a.theta) and np.array_equal(c.v, a.v)
+    assert np.array_equal(c.q_bar, a.q_bar) and np.array_equal(c.p_hat, a.p_hat)
+    assert all(np.array_equal(x, y) for x, y in zip(c.ef, a.ef))
+    assert c.n_applied == 2
