@@ -43,6 +43,8 @@ extern "C" {
 #define DLCX_EINVAL (-1)       /* NULL/misaligned pointer, shape or parameter out of range */
 #define DLCX_EUNSUPPORTED (-2) /* valid request this build has no kernel for              */
 #define DLCX_ELAUNCH (-3)      /* the HIP runtime reported an error                       */
+#define DLCX_ETOOBIG (-4)      /* larger than the fixed scratch of an entry point that does
+                                  not allocate (dlcx_average_static)                      */
 
 #define DLCX_MAX_RANK 256
 #define DLCX_MAX_WORKERS 16
@@ -95,6 +97,24 @@ int dlcx_compress_batched(const dlcx_desc *desc, int phase, int K,
 int dlcx_average(const dlcx_desc *desc, int phase, int K, const uint8_t *const *codes_host,
                  const float *const *scales_host, float *factor_out, void *workspace,
                  void *stream);
+
+/* dlcx_average for callers that cannot allocate device memory and cannot hand in a workspace
+ * either: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and bitwise the same result as dlcx_average, but the scratch of
+ * the orthonormalisation (phase P) lives in a fixed array inside the library's device image:
+ * dlcx_static_scratch_bytes() bytes (32 MiB) per GPU the library runs on, held until the process
+ * ends.  A factor whose orthonormalisation needs more (dlcx_static_scratch_need reports the need;
+ * r = 256 fits up to m = 31232, r = 64 up to m = 522752) is rejected with DLCX_ETOOBIG before
+ * anything is launched.  The call allocates nothing, frees nothing and does not synchronise.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two host threads) race on it and must be ordered by the caller; nothing in the array
+ * has to survive from one call to the next and nothing has to be cleared. */
+int dlcx_average_static(const dlcx_desc *desc, int phase, int K, const uint8_t *const *codes_host,
+                        const float *const *scales_host, float *factor_out, void *stream);
+size_t dlcx_static_scratch_bytes(void);
+/* Scratch bytes dlcx_average_static needs for this descriptor and phase (0 for phase Q and for a
+ * bad descriptor). */
+size_t dlcx_static_scratch_need(const dlcx_desc *desc, int phase);
 
 /* Decompression Delta_hat = P_hat * Q_bar^T and the error buffer of Alg. 2,
  * e_i <- delta_i - Delta_hat, for K >= 0 workers.  delta_hat_out (m x n) may be NULL when only

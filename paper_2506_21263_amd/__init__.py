@@ -13,7 +13,7 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libdlcx_hip.so")
 
-OK, EINVAL, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3
+OK, EINVAL, EUNSUPPORTED, ELAUNCH, ETOOBIG = 0, -1, -2, -3, -4
 PHASE_P, PHASE_Q = 0, 1
 F32, BF16 = 0, 1
 MMA_FMA, MMA_F32, MMA_BF16 = 0, 1, 2
@@ -45,6 +45,9 @@ SYMBOLS = {
     "dlcx_compress": (_int, [_dp, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
     "dlcx_compress_batched": (_int, [_dp, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
     "dlcx_average": (_int, [_dp, _int, _int, _vp, _vp, _vp, _vp, _vp]),
+    "dlcx_average_static": (_int, [_dp, _int, _int, _vp, _vp, _vp, _vp]),
+    "dlcx_static_scratch_bytes": (C.c_size_t, []),
+    "dlcx_static_scratch_need": (C.c_size_t, [_dp, _int]),
     "dlcx_decompress": (_int, [_dp, _vp, _vp, _vp, _int, _vp, _vp, _vp]),
     "dlcx_decompress_apply": (_int, [_dp, _vp, _vp, _int, _vp, _vp, _vp, C.c_float, C.c_float, _vp,
                                      _vp]),
@@ -166,6 +169,21 @@ def dlcx_average(d, phase, codes, scales, factor_out, workspace, stream=None):
     sp, k2 = _ptr_array(scales)
     _check(lib().dlcx_average(C.byref(d), phase, len(codes), cp, sp, _ptr(factor_out),
                               _ptr(workspace), _stream(stream)), "dlcx_average")
+
+
+def dlcx_average_static(d, phase, codes, scales, factor_out, stream=None):
+    cp, k1 = _ptr_array(codes)
+    sp, k2 = _ptr_array(scales)
+    _check(lib().dlcx_average_static(C.byref(d), phase, len(codes), cp, sp, _ptr(factor_out),
+                                     _stream(stream)), "dlcx_average_static")
+
+
+def dlcx_static_scratch_bytes():
+    return lib().dlcx_static_scratch_bytes()
+
+
+def dlcx_static_scratch_need(d, phase):
+    return lib().dlcx_static_scratch_need(C.byref(d), phase)
 
 
 def dlcx_decompress(d, p_hat, q_bar, delta_hat_out, ef_inout=(), workspace=None, stream=None):

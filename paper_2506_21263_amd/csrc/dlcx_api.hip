@@ -145,6 +145,7 @@ const char *dlcx_strerror(int code) {
         case DLCX_EINVAL: return "invalid argument";
         case DLCX_EUNSUPPORTED: return "unsupported configuration";
         case DLCX_ELAUNCH: return "HIP runtime error";
+        case DLCX_ETOOBIG: return "larger than the fixed scratch of this entry point";
         default: return "unknown error code";
     }
 }
@@ -532,6 +533,62 @@ int dlcx_average(const dlcx_desc *desc, int phase, int K, const uint8_t *const *
                               desc->group, factor_out, stream);
     if (rc != DLCX_OK || phase == DLCX_PHASE_Q) return rc;
     return dlcx_orthonormalize(L, desc->r, factor_out, workspace, stream);
+}
+
+// ---- dlcx_average without a workspace argument and without any allocation -----------------
+// The scratch of the orthonormalisation in the library's own device image.  In host code the
+// array's name is only a handle: the device address comes from hipGetSymbolAddress, once per
+// device with that device current, and only that address is ever handed to a kernel.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];  // per device, nullptr until first use there
+
+static int static_scratch_ptr(void **out) {
+    int dev = -1;
+    int rc = note_hip(hipGetDevice(&dev), "static scratch: current device");
+    if (rc != DLCX_OK) return rc;
+    if (dev < 0 || dev >= kMaxDevices) return DLCX_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        rc = note_hip(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "static scratch: address");
+        if (rc != DLCX_OK) return rc;
+        if (!ptr) return DLCX_ELAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return DLCX_OK;
+}
+
+size_t dlcx_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+size_t dlcx_static_scratch_need(const dlcx_desc *desc, int phase) {
+    if (check_desc(desc) != DLCX_OK || phase != DLCX_PHASE_P) return 0;
+    return orth_workspace_bytes(desc->m, desc->r);
+}
+
+int dlcx_average_static(const dlcx_desc *desc, int phase, int K, const uint8_t *const *codes_host,
+                        const float *const *scales_host, float *factor_out, void *stream) {
+    int rc = check_desc(desc);
+    if (rc != DLCX_OK) return rc;
+    if (phase != DLCX_PHASE_P && phase != DLCX_PHASE_Q) return DLCX_EINVAL;
+    // everything dlcx_average would reject is rejected here, before the runtime is touched
+    if (K < 1 || K > DLCX_MAX_WORKERS || !codes_host || !scales_host || !factor_out ||
+        !aligned16(factor_out))
+        return DLCX_EINVAL;
+    for (int k = 0; k < K; ++k)
+        if (!codes_host[k] || !scales_host[k] || !aligned16(codes_host[k]) ||
+            !aligned16(scales_host[k]))
+            return DLCX_EINVAL;
+    if (dlcx_static_scratch_need(desc, phase) > kStaticScratchBytes) return DLCX_ETOOBIG;
+    void *ws = nullptr;
+    if (phase == DLCX_PHASE_P) {
+        rc = static_scratch_ptr(&ws);
+        if (rc != DLCX_OK) return rc;
+    }
+    return dlcx_average(desc, phase, K, codes_host, scales_host, factor_out, ws, stream);
 }
 
 static int decompress_common(const dlcx_desc *desc, const float *p_hat, const float *q_bar,

@@ -168,3 +168,32 @@ def test_stage_lane_plan_covers_every_matrix_once_and_balances():
     firsts = [c[0][1] - c[0][0] for c in lane_chunks]
     runs = [c[-1][1] - c[0][0] for c in lane_chunks]
     assert firsts == [max(1, runs[l] * (l + 1) // 3) for l in range(3)]
+
+
+def test_static_scratch_entry_point_limits_and_argument_errors():
+    """dlcx_average_static rejects on the host, before any HIP call: bad arguments as
+    dlcx_average does, and factors whose orthonormalisation scratch exceeds the fixed array."""
+    L = dlcx.lib()
+    cap = dlcx.dlcx_static_scratch_bytes()
+    assert cap == 32 << 20
+    for r, m_fits in ((256, 31232), (64, 522752)):
+        fits = dlcx.desc(m_fits, 256, r, 4, 128, 2)
+        over = dlcx.desc(m_fits + 512, 256, r, 4, 128, 2)
+        assert 0 < dlcx.dlcx_static_scratch_need(fits, dlcx.PHASE_P) <= cap
+        assert dlcx.dlcx_static_scratch_need(over, dlcx.PHASE_P) > cap
+        assert dlcx.dlcx_static_scratch_need(over, dlcx.PHASE_Q) == 0
+    # every shape of the benchmark configurations fits at the largest rank
+    for m in (512, 2048, 8192, 28672):
+        assert dlcx.dlcx_static_scratch_need(dlcx.desc(m, 1024, min(m, 256), 4, 128, 2), 0) <= cap
+    fake = 0x1000
+    arr = (C.c_void_p * 2)(fake, fake)
+    over = dlcx.desc(65536, 256, 256, 4, 128, 2)
+    ok = dlcx.desc(512, 512, 8, 4, 64, 2)
+    assert L.dlcx_average_static(C.byref(over), 0, 2, arr, arr, fake, None) == dlcx.ETOOBIG
+    assert L.dlcx_average_static(C.byref(ok), 0, 0, arr, arr, fake, None) == dlcx.EINVAL
+    assert L.dlcx_average_static(C.byref(ok), 2, 2, arr, arr, fake, None) == dlcx.EINVAL
+    assert L.dlcx_average_static(C.byref(ok), 0, 2, arr, arr, fake + 4, None) == dlcx.EINVAL
+    assert L.dlcx_average_static(C.byref(ok), 0, 2, None, arr, fake, None) == dlcx.EINVAL
+    bad = (C.c_void_p * 2)(fake, None)
+    assert L.dlcx_average_static(C.byref(ok), 0, 2, bad, arr, fake, None) == dlcx.EINVAL
+    assert L.dlcx_strerror(dlcx.ETOOBIG) == b"larger than the fixed scratch of this entry point"
