@@ -469,7 +469,9 @@ def lowrank(args):
         gemm_load = 20 if args.config == 4 else 0
     # config 4: the outer step's streams keep off the compute units reserved for the load
     stream_pool = None
-    load_cus = args.load_cus if gemm_load else 0
+    load_cus = args.load_cus if args.load_cus >= 0 else (64 if args.config == 4 else 0)
+    if not gemm_load:
+        load_cus = 0
     if load_cus:
         stream_pool = [masked_stream(device, 0, 256 - load_cus) for _ in range(max(args.streams, 1))]
     stage, inputs, gen = build_stage(args.config, args.mma, layers, device, fused, args.streams,
@@ -760,9 +762,10 @@ def main():
     ap.add_argument("--gemm-load", type=int, default=-1,
                     help="bf16 8192^3 GEMMs issued on a stream of their own per outer step "
                          "(default: 20 at config 4, else 0)")
-    ap.add_argument("--load-cus", type=int, default=0,
+    ap.add_argument("--load-cus", type=int, default=-1,
                     help="compute units reserved for the GEMM load (the outer step's streams are "
-                         "created with a mask that leaves them out; 0 = no masks)")
+                         "created with a mask that leaves them out; 0 = no masks; default 64 at "
+                         "config 4)")
     ap.add_argument("--graph", action="store_true",
                     help="record the steady outer step into a HIP graph and replay it (fixed ranks)")
     ap.add_argument("--workers", type=int, default=0, help="K (0 = the configuration's)")
