@@ -23,11 +23,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-# HBM bytes per matrix element and launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs of
-# `bench.py --probe --layers 1 --streams 1` (config 2), scaled by a 1 GiB copy in the same run
-# (FETCH_SIZE reads 0.5 KiB per KiB copied, WRITE_SIZE 1.0): profiles/pmc_hbm_traffic_cfg2.txt.
-# The counters cannot be read from inside a timed run, so the figure of that profile is quoted.
-MEASURED_TRAFFIC_BPP = {"round_fused": 60.40, "project_q": 16.76}
+# HBM bytes per matrix element and launch of the two sweeping kernels from rocprofv3 counter runs
+# of `bench.py --probe --layers 1 --streams 1` (config 2).  Round kernel: TCC_EA0_RDREQ (128-byte
+# requests) and TCC_EA0_WRREQ_64B over the stage's mix of shapes,
+# profiles/pmc_memory_system_round_kernel_vs_flat_sweep_cfg2.txt; Q kernel: FETCH_SIZE / WRITE_SIZE
+# scaled by a 1 GiB copy in the same run, profiles/pmc_hbm_traffic_cfg2.txt.  The counters cannot
+# be read from inside a timed run, so the figures of those profiles are quoted.
+MEASURED_TRAFFIC_BPP = {"round_fused": 59.17, "project_q": 16.76}
 
 
 def log(*a):
@@ -645,8 +647,9 @@ def lowrank(args):
                         "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                         "traffic": (MEASURED_TRAFFIC_BPP[dom] * params / launches
                                     if dom in MEASURED_TRAFFIC_BPP and args.config == 2 else None),
-                        "traffic_source": "profiles/pmc_hbm_traffic_cfg2.txt (counter runs cannot "
-                                          "share a process with the timed run)",
+                        "traffic_source": "profiles/pmc_memory_system_round_kernel_vs_flat_sweep_"
+                                          "cfg2.txt, profiles/pmc_hbm_traffic_cfg2.txt (counter "
+                                          "runs cannot share a process with the timed run)",
                         "algorithmic_bytes_per_param_per_launch": bpp,
                         "avg_launch_ms": kernels[dom]["ms_per_step"] / launches,
                         "launches_per_step": launches}
@@ -655,7 +658,7 @@ def lowrank(args):
             if dom == "round_fused" and args.mma != 0 and not adaptive:
                 # matrix-core work of the same kernel: r (reconstruction) + r K (projection)
                 # multiply-adds per element, each as 3 (bf16x2) or 6 (bf16x3) bf16 piece products
-                pieces = 3 if args.mma == 2 else 6
+                pieces = 6 if args.mma == 1 else 3
                 useful = 2.0 * cfg["r"] * (1 + K) * params
                 sec = kernels[dom]["ms_per_step"] * 1e-3
                 roofline["mfma"] = {
@@ -673,7 +676,9 @@ def lowrank(args):
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "f32 (fp64 accumulate)", 1: "bf16x3-split MFMA (fp32-accurate), f32 accumulate",
-                  2: "bf16x2-split MFMA, f32 accumulate"}[args.mma],
+                  2: "bf16x2-split MFMA, f32 accumulate",
+                  3: "bf16x2-split MFMA, projections above rank 64 as one fp16 MFMA product, "
+                     "f32 accumulate"}[args.mma],
         "data": "synthetic",
         "config": {"workload": cfg["name"], "layers": layers, "matrices": len(stage.mats),
                    "params": params, "K": K, "rank": cfg["r"], "qbits": cfg["qbits"],
@@ -694,15 +699,21 @@ def lowrank(args):
                                    "fresh alpha ~ U[0.5, 2] between steps, outside the timing")
         out["per_round"] = per_round
         out["rank_trace"] = [[p["rprime"], p["rank_next"], p["rank"]] for p in per_round]
-        # matrix-core work at each round's own rank: 2 r (3 K + 1) useful flop per element
+        # matrix-core work at each round's own rank: both projections for K workers and one
+        # reconstruction, 2 r (2 K + 1) useful flop per element; executed: every product as 3
+        # (bf16 x 2) or 6 (bf16 x 3) piece products, the projections above rank 64 as one fp16
+        # product in mode 3
         timed = [p for p in per_round if p["timed"]]
-        useful = sum(2.0 * p["rank"] * (3 * K + 1) * params for p in timed)
         sec = sum(p["ms"] for p in timed) * 1e-3
-        pieces = 3 if args.mma == 2 else 6
+        pieces = 6 if args.mma == 1 else 3
+        useful = sum(2.0 * p["rank"] * (2 * K + 1) * params for p in timed)
+        executed = sum(2.0 * p["rank"] * params *
+                       (2 * K * (1 if args.mma == 3 and p["rank"] > 64 else pieces) + pieces)
+                       for p in timed)
         out["mfma"] = {"useful_TFLOPs": useful / sec / 1e12,
                        "useful_frac_of_peak": useful / sec / 1e12 / 2500.0,
-                       "executed_bf16_TFLOPs": useful * pieces / sec / 1e12,
-                       "peak_bf16_TFLOPs": 2500.0}
+                       "executed_TFLOPs": executed / sec / 1e12,
+                       "peak_bf16_fp16_TFLOPs": 2500.0}
     if overlap is not None:
         out["overlap"] = overlap
     if not args.no_cpu_baseline:
@@ -752,7 +763,10 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration (synth.CONFIGS)")
-    ap.add_argument("--mma", type=int, default=2, help="0 fma/fp64-acc, 1 fp32-accurate MFMA, 2 bf16 MFMA")
+    ap.add_argument("--mma", type=int, default=-1,
+                    help="0 fma/fp64-acc, 1 fp32-accurate MFMA, 2 bf16 MFMA, 3 bf16 MFMA with fp16 "
+                         "projections above rank 64 (default: 3 at config 3, whose ranks are "
+                         "above 64, else 2; at ranks up to 64 the two are the same kernels)")
     ap.add_argument("--layers", type=int, default=0, help="layers resident (0 = the whole stage)")
     ap.add_argument("--unfused", action="store_true", help="separate decompress / Nesterov kernels")
     ap.add_argument("--streams", type=int, default=3, help="HIP streams the matrices are dealt to")
@@ -785,6 +799,8 @@ def main():
     ap.add_argument("--probe", action="store_true",
                     help="counter run: plain random inputs, one 1 GiB copy, two steps, no timing")
     args = ap.parse_args()
+    if args.mma < 0:
+        args.mma = 3 if args.config == 3 else 2
     if args.gpus != 1:
         print("bench.py: this build measures ONE MI355X; --gpus %d is not supported "
               "(no collectives, no second GPU in this run)" % args.gpus, file=sys.stderr)

@@ -56,8 +56,15 @@ enum {
     DLCX_MMA_FMA = 0,  /* fp32 operands, fp64 accumulation on the vector ALU                   */
     DLCX_MMA_F32 = 1,  /* fp32-accurate on the bf16 matrix cores: operands split into three
                           bf16 pieces, six piece products, fp32 accumulation (rel-L2 <= 1e-5) */
-    DLCX_MMA_BF16 = 2  /* bf16 matrix cores, operands split into two bf16 pieces, three piece
+    DLCX_MMA_BF16 = 2, /* bf16 matrix cores, operands split into two bf16 pieces, three piece
                           products, fp32 accumulation (rel-L2 <= 2e-3 with a wide margin)     */
+    DLCX_MMA_F16 = 3   /* as DLCX_MMA_BF16, except the two projections at ranks above 64 (where
+                          the matrix cores, not the stream of delta, set the pace): there one
+                          fp16 product per block, operands scaled by exact powers of two into
+                          fp16's range, fp32 accumulation (rel-L2 <= 2e-3, measured 2e-5 .. 4e-4).
+                          A launch whose largest |delta| lies outside [2^-14, 15.99) is redone
+                          in the DLCX_MMA_BF16 arithmetic by a stand-by launch, without a
+                          synchronisation; the result never depends on fp16's range             */
 };
 
 typedef struct {

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libdlcx_hip.so")
 OK, EINVAL, EUNSUPPORTED, ELAUNCH, ETOOBIG = 0, -1, -2, -3, -4
 PHASE_P, PHASE_Q = 0, 1
 F32, BF16 = 0, 1
-MMA_FMA, MMA_F32, MMA_BF16 = 0, 1, 2
+MMA_FMA, MMA_F32, MMA_BF16, MMA_F16 = 0, 1, 2, 3
 MAX_RANK, MAX_WORKERS = 256, 16
 
 

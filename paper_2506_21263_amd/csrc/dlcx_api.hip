@@ -91,7 +91,7 @@ static int check_desc(const dlcx_desc *d) {
     if (!group_ok(d->group)) return DLCX_EINVAL;
     if (d->m % d->group || d->n % d->group) return DLCX_EINVAL;
     if (d->r < 1 || d->r > DLCX_MAX_RANK || d->r > d->m || d->r > d->n) return DLCX_EINVAL;
-    if (d->mma < DLCX_MMA_FMA || d->mma > DLCX_MMA_BF16) return DLCX_EINVAL;
+    if (d->mma < DLCX_MMA_FMA || d->mma > DLCX_MMA_F16) return DLCX_EINVAL;
     return DLCX_OK;
 }
 

@@ -54,9 +54,21 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {  // round-to
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
 }
 
-// pieces of the pair (a, b): out[h] holds piece h of a in its low half, of b in its high half
+__device__ __forceinline__ uint32_t pack_f16x2(float a, float b) {  // round-to-nearest-even
+    typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2_t));
+}
+
+// pieces of the pair (a, b): out[h] holds piece h of a in its low half, of b in its high half.
+// NS == 1 is the fp16 form of an operand: one piece, the fp16 rounding of the value (the caller
+// has scaled it into fp16's range by a power of two).
 template <int NS>
 __device__ __forceinline__ void split2(float a, float b, uint32_t (&out)[NS]) {
+    if constexpr (NS == 1) {
+        out[0] = pack_f16x2(a, b);
+        return;
+    }
 #pragma unroll
     for (int h = 0; h < NS; ++h) {
         const uint32_t p = pack_bf16x2(a, b);
@@ -86,6 +98,12 @@ __device__ __forceinline__ f32x16_t mfma(const uint4 &a, const uint4 &b, f32x16_
 template <int NS>
 __device__ __forceinline__ void mfma_split(const uint4 (&a)[NS], const uint4 (&b)[NS],
                                            f32x16_t &c) {
+    if constexpr (NS == 1) {  // one fp16 product
+        typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a[0]),
+                                                   __builtin_bit_cast(f16x8_t, b[0]), c, 0, 0, 0);
+        return;
+    }
     if (NS == 3) {  // smallest terms first
         c = mfma(a[2], b[0], c);
         c = mfma(a[0], b[2], c);
@@ -129,7 +147,8 @@ __device__ __forceinline__ void stream_store4(float *p, const float4 &a) {
 template <int NS>
 __global__ __launch_bounds__(kW) void pack_kcontig_kernel(const float *__restrict__ src,
                                                           int nrows, int64_t L, int RB,
-                                                          int64_t KS, uint4 *__restrict__ frags) {
+                                                          int64_t KS, uint4 *__restrict__ frags,
+                                                          const float *__restrict__ row_scale) {
     const int64_t f = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (f >= KS * RB) return;
@@ -143,11 +162,66 @@ __global__ __launch_bounds__(kW) void pack_kcontig_kernel(const float *__restric
         const float4 b = *reinterpret_cast<const float4 *>(src + (int64_t)row * L + k0 + 4);
         x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
         x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+        if (row_scale) {  // a power of two per row: exact
+            const float sc = row_scale[row];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] *= sc;
+        }
     }
     uint4 out[NS];
     split8<NS>(x, out);
 #pragma unroll
     for (int h = 0; h < NS; ++h) frags[(f * NS + h) * 64 + lane] = out[h];
+}
+
+// The fp16 form of a projection (NS == 1) needs its operands inside fp16's range.  delta is
+// multiplied by 2^kF16DeltaShift, which is safe while the largest |delta| of the launch lies in
+// [2^-14, 15.99) (the kernel records it; outside that window the bf16 kernel redoes the launch).
+// Every row of the basis (one factor column) gets its own power of two that puts its largest
+// entry into [2^7, 2^8): in_scale[c] for the fragments, out_scale[c] = 2^-kF16DeltaShift /
+// in_scale[c] for the result, so that scaling is exact and invisible.  Workgroup c handles row c;
+// workgroup 0 also clears the launch's record of the largest |delta|.
+constexpr int kF16DeltaShift = 12;
+__global__ __launch_bounds__(kW) void basis_scale_kernel(const float *__restrict__ src, int64_t L,
+                                                         float *__restrict__ in_scale,
+                                                         float *__restrict__ out_scale,
+                                                         uint32_t *__restrict__ amax_record) {
+    __shared__ float red[kW];
+    const int c = blockIdx.x;
+    float a = 0.f;
+    for (int64_t i = threadIdx.x * 4; i < L; i += kW * 4) {  // L is a multiple of 8
+        const float4 v = *reinterpret_cast<const float4 *>(src + (int64_t)c * L + i);
+        a = fmaxf(fmaxf(a, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    }
+    red[threadIdx.x] = a;
+    __syncthreads();
+    for (int s = kW / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const float amax = red[0];
+        int e = 0;
+        if (amax > 0.f && amax < 3.0e38f) e = 7 - ilogbf(amax);
+        e = e < -100 ? -100 : (e > 100 ? 100 : e);
+        in_scale[c] = ldexpf(1.f, e);
+        out_scale[c] = ldexpf(1.f, -e - kF16DeltaShift);
+        if (c == 0) *amax_record = 0u;
+    }
+}
+
+// Did the fp16 form of the launch see its operands in range?  (largest |delta| as fp32 bits)
+__device__ __forceinline__ bool f16_range_ok(uint32_t amax_bits) {
+    const float a = __uint_as_float(amax_bits);
+    return a >= 0x1p-14f && a < 15.99f;
+}
+
+// largest |x| over a wavefront, then one atomic per wavefront (bit patterns of non-negative
+// floats order like the floats)
+__device__ __forceinline__ void record_amax(float a, uint32_t *record) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
+    if ((threadIdx.x & 63) == 0) atomicMax(record, __float_as_uint(a));
 }
 
 // src is r x L with the reduction index c strided (a factor used in the reconstruction).
@@ -362,11 +436,18 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
 // ---------------------------------------------------------------------------------------------
 constexpr int kWs = 512;  // threads of the two-role workgroup
 
+// NS == 1 is the fp16 form (one product per block instead of three): the producers multiply
+// delta by 2^kF16DeltaShift and record its largest magnitude in *amax_record, the consumers undo
+// the scales through out_scale.  `guard` (NS >= 2) makes the launch a stand-by: it returns at
+// once if the fp16 launch before it saw its operands in range.
 template <int NS, int CBW, int WC, int WR, int RB>
 __global__ __launch_bounds__(kWs) void project_p_ws_kernel(PtrPack<const float *> deltas,
                                                            const uint4 *__restrict__ afrags,
                                                            PtrPack<float *> outs, int64_t m,
-                                                           int64_t n, int r) {
+                                                           int64_t n, int r,
+                                                           uint32_t *__restrict__ amax_record,
+                                                           const float *__restrict__ out_scale,
+                                                           const uint32_t *__restrict__ guard) {
     constexpr int CB = CBW * WC;
     constexpr int RBW = RB / WR;
     constexpr int kRows = 32 * RB;
@@ -375,6 +456,7 @@ __global__ __launch_bounds__(kWs) void project_p_ws_kernel(PtrPack<const float *
     constexpr int kBuf = NS * kRows * kPPitch;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
+    if (guard != nullptr && f16_range_ok(*guard)) return;  // uniform over the launch
     const float *__restrict__ delta = deltas.p[blockIdx.y];
     float *__restrict__ out = outs.p[blockIdx.y];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -383,6 +465,7 @@ __global__ __launch_bounds__(kWs) void project_p_ws_kernel(PtrPack<const float *
 
     if (wave >= 4) {  // ---------------------------------------------------------- producers
         const int tid = threadIdx.x - kW;
+        float amax = 0.f;  // NS == 1: largest |delta| this thread has laid down
         auto load_stage = [&](float4 (&set)[kVec], int64_t t) {
             const int64_t tc = t < nstages ? t : nstages - 1;
 #pragma unroll
@@ -402,8 +485,14 @@ __global__ __launch_bounds__(kWs) void project_p_ws_kernel(PtrPack<const float *
                 const int idx = tid + kW * u;
                 const int row = idx >> 4, c4 = idx & 15;
                 const bool ok = i0 + row < m && t * 64 + c4 * 4 < n;
-                const float4 x = make_float4(ok ? set[u].x : 0.f, ok ? set[u].y : 0.f,
-                                             ok ? set[u].z : 0.f, ok ? set[u].w : 0.f);
+                float4 x = make_float4(ok ? set[u].x : 0.f, ok ? set[u].y : 0.f,
+                                       ok ? set[u].z : 0.f, ok ? set[u].w : 0.f);
+                if constexpr (NS == 1) {
+                    amax = fmaxf(fmaxf(amax, fmaxf(fabsf(x.x), fabsf(x.y))),
+                                 fmaxf(fabsf(x.z), fabsf(x.w)));
+                    constexpr float kUp = (float)(1 << kF16DeltaShift);
+                    x = make_float4(x.x * kUp, x.y * kUp, x.z * kUp, x.w * kUp);
+                }
                 uint32_t lo[NS], hi[NS];
                 split2<NS>(x.x, x.y, lo);
                 split2<NS>(x.z, x.w, hi);
@@ -437,6 +526,7 @@ __global__ __launch_bounds__(kWs) void project_p_ws_kernel(PtrPack<const float *
         }
         // an odd number of stages: the consumers' last iteration needs its barrier
         if (t < nstages) step(set1, t + 1, false);
+        if constexpr (NS == 1) record_amax(amax, amax_record);
         return;
     }
     // -------------------------------------------------------------------------------- consumers
@@ -496,7 +586,8 @@ __global__ __launch_bounds__(kWs) void project_p_ws_kernel(PtrPack<const float *
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int c = (wc * CBW + cb) * 32 + d_row(v, lane);
-                if (c < r && i < m) out[(int64_t)c * m + i] = acc[cb][rb][v];
+                if (c < r && i < m)
+                    out[(int64_t)c * m + i] = NS == 1 ? acc[cb][rb][v] * out_scale[c] : acc[cb][rb][v];
             }
         }
 }
@@ -1038,11 +1129,15 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
                                                            const uint4 *__restrict__ afrags,
                                                            PtrPack<float *> outs, int64_t m,
                                                            int64_t n, int r, int64_t ksteps_per_wg,
-                                                           int64_t slab_stride) {
+                                                           int64_t slab_stride,
+                                                           uint32_t *__restrict__ amax_record,
+                                                           const float *__restrict__ out_scale,
+                                                           const uint32_t *__restrict__ guard) {
     constexpr int CB = WCB * CBW;
     constexpr int QW = WCB;               // column blocks per consumer: 4 / (4 / WCB)
     constexpr int kBuf = 16 * NS * 1024;  // 4 k-steps x 4 column blocks x NS pieces x 1 KB
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    if (guard != nullptr && f16_range_ok(*guard)) return;  // uniform over the launch
     const float *__restrict__ delta = deltas.p[blockIdx.y];
     float *__restrict__ out = outs.p[blockIdx.y] + (int64_t)blockIdx.z * slab_stride;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1054,6 +1149,7 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
         const int tid = threadIdx.x - kW;
         const int c4 = tid & 31, rg = tid >> 5;
         const bool col_ok = j0 + c4 * 4 < n;
+        float amax = 0.f;  // NS == 1: largest |delta| this thread has laid down
         auto load_stage = [&](float4 (&set)[8], int64_t t) {
             const int64_t tc = t < nstages ? t : nstages - 1;
             const int64_t i0 = (s_begin + 4 * tc) * 16 + rg * 8;
@@ -1073,6 +1169,16 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
                 v[1][e] = ok ? set[e].y : 0.f;
                 v[2][e] = ok ? set[e].z : 0.f;
                 v[3][e] = ok ? set[e].w : 0.f;
+            }
+            if constexpr (NS == 1) {
+                constexpr float kUp = (float)(1 << kF16DeltaShift);
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        amax = fmaxf(amax, fabsf(v[x][e]));
+                        v[x][e] *= kUp;
+                    }
             }
             // operand block (k-step rg / 2, column block c4 / 8), lane (rg % 2) 32 + column
             // (the two low bits of the lane slot are swizzled so that the 16 lanes of one LDS
@@ -1106,6 +1212,7 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
             step(set0, t + 2, true);
         }
         if (t < nstages) step(set1, t + 1, false);
+        if constexpr (NS == 1) record_amax(amax, amax_record);
         return;
     }
     // -------------------------------------------------------------------------------- consumers
@@ -1160,7 +1267,7 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int c = (wcb * CBW + cb) * 32 + d_row(v, lane);
-                if (c < r) out[(int64_t)c * n + j] = acc[cb][q][v];
+                if (c < r) out[(int64_t)c * n + j] = NS == 1 ? acc[cb][q][v] * out_scale[c] : acc[cb][q][v];
             }
     }
 }
@@ -1199,24 +1306,47 @@ static QPlan q_plan(int64_t m, int64_t n, int r, int K) {
     return p;
 }
 
+// scratch of the fp16 form at the end of the fragment area: in_scale[256], out_scale[256], record
+constexpr size_t kF16ScratchBytes = (2 * DLCX_MAX_RANK + 64) * sizeof(float);
+
 size_t mfma_project_workspace_bytes(int mma, int64_t m, int64_t n, int r, int K) {
-    const int ns = ns_of(mma), cb = cb_of(r);
+    // DLCX_MMA_F16: one fp16 piece beside the two bf16 pieces of the stand-by launch
+    const int ns = mma == DLCX_MMA_F16 ? 3 : ns_of(mma), cb = cb_of(r);
     const size_t p_frags = (size_t)ceil_div(n, 64) * 4 * cb * ns * 1024;
     const QPlan q = q_plan(m, n, r, K);
     const size_t q_frags = (size_t)q.KS * cb * ns * 1024;
     const size_t slabs = q.S > 1 ? (size_t)K * q.S * r * n * sizeof(float) : 0;
     const size_t a = a256(p_frags), b = a256(q_frags) + a256(slabs);
-    return a > b ? a : b;
+    return (a > b ? a : b) + (mma == DLCX_MMA_F16 ? a256(kF16ScratchBytes) : 0);
 }
 
 template <int NS>
 static int pack_kcontig(const float *src, int nrows, int64_t L, int RB, int64_t KS, uint4 *frags,
-                        hipStream_t st) {
+                        hipStream_t st, const float *row_scale = nullptr) {
     const int64_t nf = KS * RB;
     Timed timed(KID_PACK, st);
     hipLaunchKernelGGL(pack_kcontig_kernel<NS>, dim3((unsigned)ceil_div(nf, 4)), dim3(kW), 0, st,
-                       src, nrows, L, RB, KS, frags);
+                       src, nrows, L, RB, KS, frags, row_scale);
     return check_launch("pack_kcontig");
+}
+
+// scales and record of the fp16 form inside its scratch block
+struct F16Scratch {
+    float *in_scale, *out_scale;
+    uint32_t *record;
+};
+static F16Scratch f16_scratch(void *block) {
+    F16Scratch f;
+    f.in_scale = reinterpret_cast<float *>(block);
+    f.out_scale = f.in_scale + DLCX_MAX_RANK;
+    f.record = reinterpret_cast<uint32_t *>(f.out_scale + DLCX_MAX_RANK);
+    return f;
+}
+static int basis_scales(const float *basis, int r, int64_t L, const F16Scratch &f, hipStream_t st) {
+    Timed timed(KID_PACK, st);
+    hipLaunchKernelGGL(basis_scale_kernel, dim3((unsigned)r), dim3(kW), 0, st, basis, L, f.in_scale,
+                       f.out_scale, f.record);
+    return check_launch("basis_scale");
 }
 
 template <int NS, int CBW, int WC, int WK, int WR, int RB>
@@ -1238,7 +1368,8 @@ static int project_p_launch(const PtrPack<const float *> &delta, const uint4 *fr
 template <int NS, int CBW, int WC, int WR, int RB>
 static int project_p_ws_launch(const PtrPack<const float *> &delta, const uint4 *frags,
                                const PtrPack<float *> &out, int64_t m, int64_t n, int r, int K,
-                               hipStream_t st) {
+                               hipStream_t st, uint32_t *record = nullptr,
+                               const float *out_scale = nullptr, const uint32_t *guard = nullptr) {
     constexpr int lds = 2 * NS * 32 * RB * kPPitch;
     static size_t granted = 0;
     int rc = grant_dynamic_lds(
@@ -1247,8 +1378,43 @@ static int project_p_ws_launch(const PtrPack<const float *> &delta, const uint4 
     if (rc != DLCX_OK) return rc;
     const dim3 grid((unsigned)ceil_div(m, 32 * RB), (unsigned)K);
     hipLaunchKernelGGL((project_p_ws_kernel<NS, CBW, WC, WR, RB>), grid, dim3(kWs), lds, st, delta,
-                       frags, out, m, n, r);
+                       frags, out, m, n, r, record, out_scale, guard);
     return DLCX_OK;
+}
+
+// The projection at 4 or 8 basis blocks (ranks above 64) in its fp16 form, where the matrix cores
+// and not the stream of delta set the pace: one fp16 product per block instead of three bf16
+// ones, followed by the bf16 kernel as a stand-by that returns at once unless the fp16 launch
+// recorded a largest |delta| outside the window in which fp16 is safe.  False: not applicable
+// (fewer basis blocks, or too few rows for the two-role kernel), the caller goes on as usual.
+static bool project_p_f16(int64_t m, int64_t n, int r, int K, const PtrPack<const float *> &delta,
+                          const float *q_in, const PtrPack<float *> &out, void *workspace,
+                          hipStream_t st, int *rc_out) {
+    const int cb = cb_of(r);
+    if (cb < 4 || ceil_div(m, 128) * K < 256) return false;
+    const int64_t KS = ceil_div(n, 64) * 4;
+    char *ws = reinterpret_cast<char *>(workspace);
+    uint4 *frags2 = reinterpret_cast<uint4 *>(ws);                                // two bf16 pieces
+    uint4 *frags1 = reinterpret_cast<uint4 *>(ws + (size_t)KS * cb * 2 * 1024);   // one fp16 piece
+    const F16Scratch f = f16_scratch(ws + a256((size_t)KS * cb * 3 * 1024));
+    int rc = basis_scales(q_in, r, n, f, st);
+    if (rc == DLCX_OK) rc = pack_kcontig<1>(q_in, r, n, cb, KS, frags1, st, f.in_scale);
+    if (rc == DLCX_OK) rc = pack_kcontig<2>(q_in, r, n, cb, KS, frags2, st);
+    if (rc == DLCX_OK) {
+        Timed timed(KID_PROJECT_P, st);
+        if (cb == 4) {
+            rc = project_p_ws_launch<1, 2, 2, 2, 4>(delta, frags1, out, m, n, r, K, st, f.record, f.out_scale);
+            if (rc == DLCX_OK)
+                rc = project_p_ws_launch<2, 2, 2, 2, 4>(delta, frags2, out, m, n, r, K, st, nullptr, nullptr, f.record);
+        } else {
+            rc = project_p_ws_launch<1, 2, 4, 1, 4>(delta, frags1, out, m, n, r, K, st, f.record, f.out_scale);
+            if (rc == DLCX_OK)
+                rc = project_p_ws_launch<2, 2, 4, 1, 4>(delta, frags2, out, m, n, r, K, st, nullptr, nullptr, f.record);
+        }
+        if (rc == DLCX_OK) rc = check_launch("project_p_f16");
+    }
+    *rc_out = rc;
+    return true;
 }
 
 template <int NS>
@@ -1293,41 +1459,63 @@ int launch_sum_slabs(int K, const PtrPack<const float *> &slabs, const PtrPack<f
 template <int NS, int CBW, int WCB>
 static int project_q_ws_launch(const dim3 &grid, hipStream_t st, const PtrPack<const float *> &delta,
                                const uint4 *frags, const PtrPack<float *> &dst, int64_t m,
-                               int64_t n, int r, int64_t ksteps_per_wg, int64_t slab) {
+                               int64_t n, int r, int64_t ksteps_per_wg, int64_t slab,
+                               uint32_t *record = nullptr, const float *out_scale = nullptr,
+                               const uint32_t *guard = nullptr) {
     constexpr int lds = 2 * 16 * NS * 1024;
     static size_t granted = 0;
     int rc = grant_dynamic_lds(reinterpret_cast<const void *>(project_q_ws_kernel<NS, CBW, WCB>),
                                lds, &granted, "project_q attribute");
     if (rc != DLCX_OK) return rc;
     hipLaunchKernelGGL((project_q_ws_kernel<NS, CBW, WCB>), grid, dim3(kWs), lds, st, delta, frags, dst,
-                       m, n, r, ksteps_per_wg, slab);
+                       m, n, r, ksteps_per_wg, slab, record, out_scale, guard);
     return DLCX_OK;
 }
 
-template <int NS>
+// F16: the fp16 form for 4 or 8 basis blocks (see project_p_f16), with the bf16 kernel as its
+// stand-by; NS is then the stand-by's piece count (2) and the workspace holds three pieces.
+template <int NS, bool F16>
 static int project_q_ns(int64_t m, int64_t n, int r, int K, const PtrPack<const float *> &delta,
                         const float *p_hat, const PtrPack<float *> &out, void *workspace,
                         hipStream_t st) {
     const int cb = cb_of(r);
     const QPlan q = q_plan(m, n, r, K);
-    uint4 *frags = reinterpret_cast<uint4 *>(workspace);
-    int rc = pack_kcontig<NS>(p_hat, r, m, cb, q.KS, frags, st);
+    const bool f16 = F16 && cb >= 4;
+    const int pieces = F16 ? 3 : NS;  // as the workspace was sized
+    char *wsb = reinterpret_cast<char *>(workspace);
+    uint4 *frags = reinterpret_cast<uint4 *>(wsb);
+    uint4 *frags1 = reinterpret_cast<uint4 *>(wsb + (size_t)q.KS * cb * NS * 1024);
+    F16Scratch f = f16_scratch(nullptr);
+    int rc = DLCX_OK;
+    if (f16) {
+        const size_t slab_bytes = q.S > 1 ? a256((size_t)K * q.S * r * n * sizeof(float)) : 0;
+        f = f16_scratch(wsb + a256((size_t)q.KS * cb * pieces * 1024) + slab_bytes);
+        rc = basis_scales(p_hat, r, m, f, st);
+        if (rc == DLCX_OK) rc = pack_kcontig<1>(p_hat, r, m, cb, q.KS, frags1, st, f.in_scale);
+        if (rc != DLCX_OK) return rc;
+    }
+    rc = pack_kcontig<NS>(p_hat, r, m, cb, q.KS, frags, st);
     if (rc != DLCX_OK) return rc;
     const int64_t slab = (int64_t)r * n;
     PtrPack<float *> dst = out;
     if (q.S > 1) {
-        float *base = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
-                                                a256((size_t)q.KS * cb * NS * 1024));
+        float *base = reinterpret_cast<float *>(wsb + a256((size_t)q.KS * cb * pieces * 1024));
         for (int k = 0; k < K; ++k) dst.p[k] = base + (int64_t)k * q.S * slab;
     }
     const dim3 grid((unsigned)ceil_div(n, 32 * q.JB), (unsigned)K, (unsigned)q.S);
     {
     Timed timed(KID_PROJECT_Q, st);
+    if (f16) {  // the stand-by launches below then carry the record as their guard
+        if (cb == 4) rc = project_q_ws_launch<1, 1, 4>(grid, st, delta, frags1, dst, m, n, r, q.ksteps_per_wave * 4, slab, f.record, f.out_scale);
+        else rc = project_q_ws_launch<1, 2, 4>(grid, st, delta, frags1, dst, m, n, r, q.ksteps_per_wave * 4, slab, f.record, f.out_scale);
+        if (rc != DLCX_OK) return rc;
+    }
+    const uint32_t *guard = f16 ? f.record : nullptr;
     switch (cb) {
         case 1: hipLaunchKernelGGL((project_q_mfma_kernel<NS, 1, 4, 2>), grid, dim3(kW), 0, st, delta, frags, dst, m, n, r, q.ksteps_per_wave, slab); break;
         case 2: rc = project_q_ws_launch<NS, 1, 2>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
-        case 4: rc = project_q_ws_launch<NS, 1, 4>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
-        default: rc = project_q_ws_launch<NS, 2, 4>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab); break;
+        case 4: rc = project_q_ws_launch<NS, 1, 4>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab, nullptr, nullptr, guard); break;
+        default: rc = project_q_ws_launch<NS, 2, 4>(grid, st, delta, frags, dst, m, n, r, q.ksteps_per_wave * 4, slab, nullptr, nullptr, guard); break;
     }
     if (rc == DLCX_OK) rc = check_launch("project_q_mfma");
     }
@@ -1341,14 +1529,20 @@ int launch_project_p_mfma(int mma, int64_t m, int64_t n, int r, int K,
                           const PtrPack<const float *> &delta, const float *q_in,
                           const PtrPack<float *> &out, void *workspace, hipStream_t st) {
     if (mma == DLCX_MMA_F32) return project_p_ns<3>(m, n, r, K, delta, q_in, out, workspace, st);
+    int rc = DLCX_OK;
+    if (mma == DLCX_MMA_F16 && project_p_f16(m, n, r, K, delta, q_in, out, workspace, st, &rc))
+        return rc;
     return project_p_ns<2>(m, n, r, K, delta, q_in, out, workspace, st);
 }
 
 int launch_project_q_mfma(int mma, int64_t m, int64_t n, int r, int K,
                           const PtrPack<const float *> &delta, const float *p_hat,
                           const PtrPack<float *> &out, void *workspace, hipStream_t st) {
-    if (mma == DLCX_MMA_F32) return project_q_ns<3>(m, n, r, K, delta, p_hat, out, workspace, st);
-    return project_q_ns<2>(m, n, r, K, delta, p_hat, out, workspace, st);
+    if (mma == DLCX_MMA_F32)
+        return project_q_ns<3, false>(m, n, r, K, delta, p_hat, out, workspace, st);
+    if (mma == DLCX_MMA_F16)
+        return project_q_ns<2, true>(m, n, r, K, delta, p_hat, out, workspace, st);
+    return project_q_ns<2, false>(m, n, r, K, delta, p_hat, out, workspace, st);
 }
 
 size_t mfma_reconstruct_workspace_bytes(int mma, int64_t m, int64_t n, int r) {

@@ -32,8 +32,10 @@ def rel_l2(got, want):
 # mode (rel-L2 against the oracle); GUARD is what the tests hold the kernels to: the fp32-accurate
 # modes at the contract, the two-piece bf16 mode at 1e-4 (it measures 5e-6 .. 2e-5: the contract's
 # 2e-3 would let a wrong tail row or a bad tile of a large output through).
-CONTRACT = {dlcx.MMA_FMA: 1e-5, dlcx.MMA_F32: 1e-5, dlcx.MMA_BF16: 2e-3}
-GUARD = {dlcx.MMA_FMA: 1e-5, dlcx.MMA_F32: 1e-5, dlcx.MMA_BF16: 1e-4}
+# The fp16 form of the projections at ranks above 64 (MMA_F16) rounds both operands to 11 bits
+# once: 2e-5 .. 4e-4 measured, held to 1e-3.
+CONTRACT = {dlcx.MMA_FMA: 1e-5, dlcx.MMA_F32: 1e-5, dlcx.MMA_BF16: 2e-3, dlcx.MMA_F16: 2e-3}
+GUARD = {dlcx.MMA_FMA: 1e-5, dlcx.MMA_F32: 1e-5, dlcx.MMA_BF16: 1e-4, dlcx.MMA_F16: 1e-3}
 
 
 def close(got, want, tol):

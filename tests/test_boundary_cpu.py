@@ -42,7 +42,7 @@ def test_payload_bytes_follow_the_layout():
 
 @pytest.mark.parametrize("bad", [
     dict(m=0), dict(n=-16), dict(r=0), dict(r=257), dict(r=600), dict(qbits=3), dict(qbits=16),
-    dict(group=48), dict(group=0), dict(m=520), dict(mma=3), dict(mma=-1)])
+    dict(group=48), dict(group=0), dict(m=520), dict(mma=4), dict(mma=-1)])
 def test_bad_descriptors_are_rejected(bad):
     kw = dict(m=512, n=512, r=8, qbits=4, group=64, mma=0)
     kw.update(bad)

@@ -154,6 +154,73 @@ def test_project_p_and_q(mma, m, n, r, K, group):
         assert close(to_np(outs[k]), want_q[k], TOL[mma]), ("Q", k)
 
 
+# ranks above 64 in the fp16 form: (Q only: few rows) / (P and Q: the two-role P kernel is used)
+SHAPES_F16 = [(640, 2048, 96, 2, 128), (2048, 512, 256, 1, 64), (4096, 320, 200, 8, 64),
+              (4112, 336, 72, 8, 16), (4112, 336, 130, 8, 16)]
+
+
+@pytest.mark.parametrize("m,n,r,K,group", SHAPES_F16)
+def test_project_p_and_q_fp16_form(m, n, r, K, group):
+    test_project_p_and_q(dlcx.MMA_F16, m, n, r, K, group)
+
+
+def test_fp16_form_is_the_bf16_form_up_to_rank_64():
+    m, n, r, K, group = 1024, 768, 64, 4, 128
+    inp, deltas = _lowrank_inputs(m, n, r, K, seed=5)
+    basis_q = rng(9).standard_normal((r, m)).astype(np.float32)
+    outs = {}
+    for mma in (dlcx.MMA_BF16, dlcx.MMA_F16):
+        d = dlcx.desc(m, n, r, 4, group, mma)
+        po = [torch.zeros(r, m, device=DEV) for _ in range(K)]
+        qo = [torch.zeros(r, n, device=DEV) for _ in range(K)]
+        dd = [to_dev(x) for x in deltas]
+        dlcx.dlcx_project(d, dlcx.PHASE_P, dd, to_dev(inp.q_in), po, ws_for(d, K))
+        dlcx.dlcx_project(d, dlcx.PHASE_Q, dd, to_dev(basis_q), qo, ws_for(d, K))
+        outs[mma] = [to_np(x) for x in po + qo]
+    for a, b in zip(outs[dlcx.MMA_BF16], outs[dlcx.MMA_F16]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+@pytest.mark.parametrize("case", ["in-range", "huge-element", "tiny", "zero"])
+def test_fp16_form_stands_by_outside_its_range(case):
+    """The fp16 launch records the largest |delta|; outside [2^-14, 15.99) the stand-by launch
+    redoes the projection in the bf16 arithmetic, so the result is then that of DLCX_MMA_BF16 bit
+    for bit -- a single element of 1e3 among values of 1e-3, a matrix of values around 1e-9, an
+    all-zero matrix.  In range, the result is the fp16 one (close to, not equal to, the bf16 one)."""
+    m, n, r, K, group = 4096, 320, 200, 8, 64
+    inp, deltas = _lowrank_inputs(m, n, r, K, seed=77)
+    if case == "huge-element":
+        deltas[3][1234, 77] = 1.0e3
+    elif case == "tiny":
+        deltas = [(x * 1e-7).astype(np.float32) for x in deltas]
+    elif case == "zero":
+        deltas = [np.zeros_like(x) for x in deltas]
+    d_deltas = [to_dev(x) for x in deltas]
+    p_hat = ref.orthonormalize(ref.project_p(deltas[0] if case != "zero" else inp.theta_g, inp.q_in))
+    res = {}
+    for mma in (dlcx.MMA_BF16, dlcx.MMA_F16):
+        d = dlcx.desc(m, n, r, 4, group, mma)
+        ws = ws_for(d, K)
+        po = [torch.zeros(r, m, device=DEV) for _ in range(K)]
+        qo = [torch.zeros(r, n, device=DEV) for _ in range(K)]
+        dlcx.dlcx_project(d, dlcx.PHASE_P, d_deltas, to_dev(inp.q_in), po, ws)
+        dlcx.dlcx_project(d, dlcx.PHASE_Q, d_deltas, to_dev(p_hat), qo, ws)
+        res[mma] = [to_np(x) for x in po + qo]
+    same = all(np.array_equal(a.view(np.uint32), b.view(np.uint32))
+               for a, b in zip(res[dlcx.MMA_BF16], res[dlcx.MMA_F16]))
+    if case == "in-range":
+        assert not same
+        for a, b in zip(res[dlcx.MMA_BF16], res[dlcx.MMA_F16]):
+            assert close(b, a, TOL[dlcx.MMA_F16])
+        want = ref.project_q(deltas[2], p_hat)
+        assert close(res[dlcx.MMA_F16][K + 2], want, TOL[dlcx.MMA_F16])
+    else:
+        assert same
+        if case != "zero":
+            want = ref.project_q(deltas[3], p_hat)
+            assert rel_l2(res[dlcx.MMA_F16][K + 3], want) <= TOL[dlcx.MMA_BF16]
+
+
 @pytest.mark.parametrize("mma", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("m,n,r,K,group", SHAPES)
 def test_decompress_and_error_buffer(mma, m, n, r, K, group):

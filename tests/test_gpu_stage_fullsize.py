@@ -23,6 +23,8 @@ from gpu_util import DEV, to_np
 pytestmark = pytest.mark.gpu
 
 STEPS = 3
+# product arithmetic of each configuration, as bench.py times it
+MODE = {2: dlcx.MMA_BF16, 3: dlcx.MMA_F16, 4: dlcx.MMA_BF16}
 
 
 def _digest(t):
@@ -69,7 +71,7 @@ def test_whole_stage_three_streams_properties_and_single_stream_bits(CFG):
     qbits = cfg["qbits"]
     qmax = 2 ** (qbits - 1) - 1
 
-    stage, inputs_, _ = bench.build_stage(CFG, dlcx.MMA_BF16, layers, DEV, True, 3)
+    stage, inputs_, _ = bench.build_stage(CFG, MODE[CFG], layers, DEV, True, 3)
     locals_ = [t["theta_l"] for t in inputs_]
     assert stage.nstreams == 3 and stage.batched and len(stage.mats) == 7 * layers
     inputs = _input_digest(stage, locals_)
@@ -111,7 +113,7 @@ def test_whole_stage_three_streams_properties_and_single_stream_bits(CFG):
 
     del stage, locals_, inputs_, M, e, codes, scales
     torch.cuda.empty_cache()
-    stage, inputs_, _ = bench.build_stage(CFG, dlcx.MMA_BF16, layers, DEV, True, 3)
+    stage, inputs_, _ = bench.build_stage(CFG, MODE[CFG], layers, DEV, True, 3)
     locals_ = [t["theta_l"] for t in inputs_]
     assert np.array_equal(_input_digest(stage, locals_), inputs), "the seeded generator did not repeat"
     for _ in range(STEPS):
