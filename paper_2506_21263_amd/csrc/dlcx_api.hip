@@ -690,7 +690,10 @@ int dlcx_ef_delta_apply_compress(const dlcx_desc *desc, int32_t r_prev, const fl
     // fragments of both products; the feedback / update sweep followed by the projection kernel
     // moves 16 more bytes per element and is faster there (measured at ranks 96 and 128 on the
     // benchmark shapes with two workers per launch: 0.91 against 1.30 ms for an 8192 x 8192
-    // matrix with four workers, 3.45 against 4.30 ms for 8192 x 28672).
+    // matrix with four workers, 3.45 against 4.30 ms for 8192 x 28672).  Dealing the rank out over
+    // the wavefronts instead (one launch for four workers, delta tiles exchanged through LDS) was
+    // measured too: 1.74 against 1.27 + 0.40 ms per matrix at rank 187, its matrix-core phases
+    // run with no loads of that workgroup in flight.
     if (desc->mma == DLCX_MMA_FMA || desc->r > 64) {
         if (r_prev > 0) {
             dlcx_desc dp = *desc;
