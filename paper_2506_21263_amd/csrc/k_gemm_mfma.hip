@@ -620,7 +620,9 @@ __device__ __forceinline__ void vec_to_array<4>(const float4 &v, float (&out)[4]
     out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
 }
 
-// Used up to 2 basis blocks (r <= 64); above that project_q_ws_kernel below.
+// Used for one basis block (r <= 32); from two blocks on project_q_ws_kernel below (at two
+// blocks this kernel needs 326 registers, one wavefront per SIMD: 4.8 - 5.5 TB/s on the large
+// shapes against 4.9 - 6.0).
 template <int JB>
 __device__ __forceinline__ typename VecOf<JB>::type stream_load_vec(const float *p);
 template <>
