@@ -123,6 +123,11 @@ SHAPES = [  # (m, n, r, K, group): several tiles and ragged tails in both dimens
     (4240, 208, 40, 8, 16),
     (4112, 336, 72, 8, 16),
     (4112, 336, 130, 8, 16),
+    # the smallest sizes the descriptor admits (one group per side, rank 1), the largest number
+    # of workers, a rank equal to the smaller side
+    (16, 16, 1, 1, 16),
+    (32, 48, 16, 16, 16),
+    (64, 48, 40, 2, 16),
 ]
 
 

@@ -45,6 +45,9 @@ CASES = [
     ("rank96", 640, 2048, 2, 96, 4, 128, "bf16", 2, 1e-3),
     ("rank128-K3", 768, 1280, 3, 128, 4, 128, "bf16", 2, 1e-3),
     ("rank256-K5", 2048, 512, 5, 256, 8, 64, "f32", 2, 1e-3),
+    # degenerate sizes: one worker, rank 1, a single quantiser group per row; the most workers
+    ("tiny", 16, 32, 1, 1, 4, 16, "f32", 3, 1e-3),
+    ("K16", 64, 48, 16, 12, 8, 16, "bf16", 2, 1e-3),
 ]
 
 
