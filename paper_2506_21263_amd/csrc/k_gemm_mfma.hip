@@ -429,8 +429,9 @@ __global__ __launch_bounds__(kW) void project_p_mfma_kernel(PtrPack<const float 
 // lives in register set s & 1, is split into bf16 pieces and laid down in LDS buffer s & 1 one
 // stage before it is used, and its set is refilled at once with stage s + 2, so that every
 // request has two stages of time to come back.  Wavefronts 0..3 (consumers) own WC x WR blocks of
-// the output, fetch their basis fragments through L2 two k-steps ahead (their load counter never
-// waits for HBM) and keep the matrix cores busy on the buffer the producers filled last.  One
+// the output, fetch their basis fragments through L2 two or four k-steps ahead (their load
+// counter never waits for HBM) and keep the matrix cores busy on the buffer the producers filled
+// last.  One
 // LDS-only barrier per stage for all eight.  Loads past the matrix or past the last stage are
 // clamped to a valid address and zeroed / never read, which keeps both loops free of branches.
 // ---------------------------------------------------------------------------------------------
@@ -538,9 +539,13 @@ __global__ __launch_bounds__(kWs) void project_p_ws_kernel(PtrPack<const float *
         for (int b = 0; b < RBW; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-    // fragments of global k-step g (4 per stage) in ring position g % AD (a deeper ring, a whole
-    // stage, measured no faster)
-    constexpr int AD = 2;
+    // fragments of global k-step g (4 per stage) in ring position g % AD: requested two k-steps
+    // ahead, or a whole stage ahead where that is at most 8 registers per position (one fp16
+    // piece, or one basis block per wavefront).  There the matrix-core work of two k-steps is
+    // shorter than a trip to L2 and the consumers, hence the stage barrier, waited for fragments:
+    // 4 - 10 % on the kernel at rank 64, 4 - 7 % in the fp16 form at ranks 192 and 256.  With two
+    // blocks of two bf16 pieces the matrix cores set the pace and the deeper ring gains nothing.
+    constexpr int AD = CBW * NS <= 2 ? 4 : 2;
     uint4 a[AD][CBW][NS];
     const int64_t gmax = nstages * 4 - 1;
     auto load_frags = [&](int64_t g, int pos) {
@@ -1226,7 +1231,8 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
         for (int b = 0; b < QW; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-    uint4 a[2][CBW][NS];  // fragments of k-step g in ring position g & 1
+    constexpr int AD = CBW * NS <= 2 ? 4 : 2;  // as in project_p_ws_kernel
+    uint4 a[AD][CBW][NS];                      // fragments of k-step g in ring position g % AD
     const int64_t gmax = s_begin + ksteps_per_wg - 1;
     auto load_frags = [&](int64_t g, int pos) {
         const int64_t gc = g < gmax ? g : gmax;
@@ -1236,8 +1242,8 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
             for (int h = 0; h < NS; ++h)
                 a[pos][cb][h] = afrags[((gc * CB + wcb * CBW + cb) * NS + h) * 64 + lane];
     };
-    load_frags(s_begin, 0);
-    load_frags(s_begin + 1, 1);
+#pragma unroll
+    for (int g = 0; g < AD; ++g) load_frags(s_begin + g, g);
     lds_barrier();
     for (int64_t t = 0; t < nstages; ++t) {
         const unsigned char *buf = lds + (t & 1) * kBuf;
@@ -1254,8 +1260,8 @@ __global__ __launch_bounds__(kWs) void project_q_ws_kernel(PtrPack<const float *
 #pragma unroll
             for (int cb = 0; cb < CBW; ++cb)
 #pragma unroll
-                for (int q = 0; q < QW; ++q) mfma_split<NS>(a[ks & 1][cb], b[q], acc[cb][q]);
-            load_frags(s_begin + t * 4 + ks + 2, ks & 1);
+                for (int q = 0; q < QW; ++q) mfma_split<NS>(a[ks % AD][cb], b[q], acc[cb][q]);
+            load_frags(s_begin + t * 4 + ks + AD, ks % AD);
             __builtin_amdgcn_sched_barrier(0);
         }
         lds_barrier();
