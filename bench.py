@@ -442,7 +442,19 @@ def masked_stream(device, cu_lo, cu_hi, total_cus=256):
     rc = hip.hipExtStreamCreateWithCUMask(C.byref(handle), C.c_uint32(words), mask)
     if rc != 0:
         raise RuntimeError("hipExtStreamCreateWithCUMask failed: %d" % rc)
+    _MASKED_STREAMS.append((hip, handle))
     return torch.cuda.ExternalStream(handle.value, device=device)
+
+
+_MASKED_STREAMS = []
+
+
+def destroy_masked_streams():
+    """The streams of masked_stream are this script's to destroy (torch only wraps them): call
+    once nothing is queued on them any more and nothing will be."""
+    while _MASKED_STREAMS:
+        hip, handle = _MASKED_STREAMS.pop()
+        hip.hipStreamDestroy(handle)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -719,9 +731,11 @@ def lowrank(args):
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, K, cfg["r"], iters=args.power_iters,
                                            requant=args.requant)
+    torch.cuda.synchronize()
     del stage, inputs, locals_, load, selector
     gc.collect()
     torch.cuda.empty_cache()
+    destroy_masked_streams()
     return out
 
 
