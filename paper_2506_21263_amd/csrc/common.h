@@ -137,6 +137,6 @@ int launch_effective_rank(int64_t L, int r, const float *q_bar, double tau, int3
 int launch_effective_rank_batch(const FactorBatch &batch, double tau, hipStream_t st);
 // fp64 Gram matrix partials of r x L factors: part[chunk][a][b] for a <= b (others untouched)
 int gram_chunks(int64_t L);
-int launch_gram_partials_batch(const FactorBatch &batch, hipStream_t st);
+int launch_gram_partials_batch(const FactorBatch &batch, FactorBatch *reduced, hipStream_t st);
 
 }  // namespace dlcx

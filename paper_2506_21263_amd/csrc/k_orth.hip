@@ -89,17 +89,43 @@ __global__ __launch_bounds__(kGT) void gram_partial_kernel(FactorBatch batch) {
         }
 }
 
-int launch_gram_partials_batch(const FactorBatch &batch, hipStream_t st) {
-    int max_chunks = 1, max_tiles = 1;
+// part[0][a][b] <- sum over the chunks, in chunk order, for a <= b: the sum that the one workgroup
+// per matrix of the Cholesky and eigenvalue kernels would otherwise form by itself (r^2 x chunks
+// loads by one workgroup: 1 - 2 ms of its 3 - 7 ms at r = 256 and L = 28672), here spread over
+// the GPU.  Same additions in the same order, so the same bits.
+__global__ __launch_bounds__(kGT) void gram_reduce_kernel(FactorBatch batch) {
+    const FactorItem it = batch.it[blockIdx.y];
+    const int r = it.r;
+    const int64_t rr = (int64_t)r * r;
+    const int64_t x = (int64_t)blockIdx.x * kGT + threadIdx.x;
+    if (x >= rr || it.nchunks < 2) return;
+    if (x / r > x % r) return;  // lower triangle: never written, never read
+    double s = 0.0;
+    for (int c = 0; c < it.nchunks; ++c) s += it.part[(int64_t)c * rr + x];
+    it.part[x] = s;
+}
+
+// Partial Gram sums of every factor of the batch, then their sum in part[0]: *reduced is the
+// batch as the kernels that consume the Gram matrices have to see it (one chunk each).
+int launch_gram_partials_batch(const FactorBatch &batch, FactorBatch *reduced, hipStream_t st) {
+    int max_chunks = 1, max_tiles = 1, max_r = 1;
     for (int i = 0; i < batch.n; ++i) {
         const int nt = (batch.it[i].r + 63) / 64;
         if (batch.it[i].nchunks > max_chunks) max_chunks = batch.it[i].nchunks;
         if (nt * (nt + 1) / 2 > max_tiles) max_tiles = nt * (nt + 1) / 2;
+        if (batch.it[i].r > max_r) max_r = batch.it[i].r;
     }
     const dim3 grid((unsigned)max_chunks, (unsigned)max_tiles, (unsigned)batch.n);
     Timed timed(KID_GRAM, st);
     hipLaunchKernelGGL(gram_partial_kernel, grid, dim3(kGT), 0, st, batch);
-    return check_launch("gram_partials");
+    int rc = check_launch("gram_partials");
+    if (rc != DLCX_OK) return rc;
+    *reduced = batch;
+    if (max_chunks < 2) return DLCX_OK;
+    const dim3 rgrid((unsigned)ceil_div((int64_t)max_r * max_r, kGT), (unsigned)batch.n);
+    hipLaunchKernelGGL(gram_reduce_kernel, rgrid, dim3(kGT), 0, st, batch);
+    for (int i = 0; i < batch.n; ++i) reduced->it[i].nchunks = 1;
+    return check_launch("gram_reduce");
 }
 
 // One workgroup per matrix.  g (r rows of pitch r + 1, fp64, LDS or global) <- sum of the
@@ -241,7 +267,8 @@ size_t orth_workspace_bytes(int64_t L, int r) {
 }
 
 static int cholqr_pass(const FactorBatch &batch, hipStream_t st) {
-    int rc = launch_gram_partials_batch(batch, st);
+    FactorBatch summed;  // the same factors with their Gram sums in one chunk
+    int rc = launch_gram_partials_batch(batch, &summed, st);
     if (rc != DLCX_OK) return rc;
     size_t g_bytes = 0, a_bytes = 0;
     int64_t max_rows = 1;
@@ -263,7 +290,7 @@ static int cholqr_pass(const FactorBatch &batch, hipStream_t st) {
         for (int i = 0; i < batch.n; ++i)
             large = large || (size_t)batch.it[i].r * (batch.it[i].r + 1) * sizeof(double) > kCholLdsMax;
         hipLaunchKernelGGL(chol_inverse_kernel, dim3((unsigned)batch.n),
-                           dim3(large ? kCTLarge : kCT), g_bytes, st, batch);
+                           dim3(large ? kCTLarge : kCT), g_bytes, st, summed);
         rc = check_launch("chol_inverse");
     }
     if (rc != DLCX_OK) return rc;

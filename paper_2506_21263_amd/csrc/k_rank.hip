@@ -265,7 +265,8 @@ void effrank_item(FactorItem *it, const float *q_bar, int64_t L, int r, int32_t 
 
 int launch_effective_rank_batch(const FactorBatch &batch, double tau, hipStream_t st) {
     if (batch.n == 0) return DLCX_OK;
-    int rc = launch_gram_partials_batch(batch, st);
+    FactorBatch summed;  // the same factors with their Gram sums in one chunk
+    int rc = launch_gram_partials_batch(batch, &summed, st);
     if (rc != DLCX_OK) return rc;
     size_t bytes = 0;
     for (int i = 0; i < batch.n; ++i) {
@@ -285,7 +286,7 @@ int launch_effective_rank_batch(const FactorBatch &batch, double tau, hipStream_
     int threads = ((rmax + 1) / 2 * 16 + 255) / 256 * 256;
     threads = threads < 256 ? 256 : (threads > kJT || rmax > 128 ? kJT : threads);
     hipLaunchKernelGGL(jacobi_rank_kernel, dim3((unsigned)batch.n), dim3((unsigned)threads), bytes,
-                       st, batch, tau);
+                       st, summed, tau);
     return check_launch("jacobi_rank");
 }
 
