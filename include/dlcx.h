@@ -333,8 +333,10 @@ int dlcx_effective_rank(int64_t L, int32_t r, const float *q_bar, double tau,
 
 /* ---- instrumentation ----------------------------------------------------------------------
  * Per-kernel timing with HIP events on the launch stream.  dlcx_profile_enable(1) clears the
- * records and starts recording every kernel launch of this library (process-wide, not
- * thread-safe, meant for benchmarks); dlcx_profile_read waits for the recorded launches of one
+ * records and starts recording every kernel launch of this library (process-wide; the records
+ * are guarded by a lock, so launches from several host threads may be recorded at once, but
+ * enabling or disabling while another thread launches loses that thread's launches in flight;
+ * meant for benchmarks); dlcx_profile_read waits for the recorded launches of one
  * kernel id (0 .. dlcx_profile_kernels()-1) and returns their summed duration and count;
  * dlcx_profile_enable(0) stops recording and frees the events. */
 int dlcx_profile_enable(int on);
