@@ -526,7 +526,10 @@ def lowrank(args):
         # the null stream: streams created with a compute-unit mask are ordinary blocking streams,
         # and every operation on the null stream (the fork and join events of a step) would wait
         # for, and be waited for by, all work on them -- the load and the step would serialise.
-        torch.cuda.set_stream(torch.cuda.Stream(device=device))
+        # The stream it is issued from is the first of the stage's own rather than one more: the
+        # process has four hardware queues, and with the three of the stage, the load's and a
+        # further one two streams share a queue and wait for each other (4 % on the step).
+        torch.cuda.set_stream(stage.side[0] if stage.side else torch.cuda.Stream(device=device))
 
     def issue_load():
         with torch.cuda.stream(load["stream"]):
