@@ -735,6 +735,8 @@ def lowrank(args):
         out["cpu_baseline"] = cpu_baseline(args.config, K, cfg["r"], iters=args.power_iters,
                                            requant=args.requant)
     torch.cuda.synchronize()
+    # back to torch's default stream before the streams of this run go away
+    torch.cuda.set_stream(torch.cuda.default_stream(torch.device(device)))
     del stage, inputs, locals_, load, selector
     gc.collect()
     torch.cuda.empty_cache()
